@@ -1,0 +1,245 @@
+/*
+ * st3.h - C ABI of the ST3 attention / visual-token-trimming hot path for AMD MI355X (gfx950).
+ *
+ * The calls follow the problem statement of "ST3: Spatial-Temporal Visual Token Trimming"
+ * (Alg. 3, "PVTP+VTA (KV cache implementation)"): per decoder layer, causal attention over a
+ * sequence laid out [S, V, I, O] (Eq. 1) whose visual segment V shrinks over layers at prefill
+ * (Progressive Visual Token Pruning, Eq. 3) and over decode steps (Visual Token Annealing,
+ * Eq. 7-8), driven by the attention the last query row pays to each visual key (Sec. 3.2).
+ *
+ * Conventions (all entry points unless stated otherwise)
+ *   - extern "C"; every pointer documented as DEVICE points to HIP device memory owned by the
+ *     caller; every pointer documented as HOST is ordinary host memory.  The library never
+ *     allocates or frees device memory, keeps no per-call state, and never synchronises: work is
+ *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream) and results are
+ *     valid once the caller has synchronised that stream.
+ *   - Arguments are checked on the host before anything is enqueued.  On an error the call
+ *     returns a non-zero st3_status and enqueues nothing.  A failed HIP launch returns
+ *     ST3_ERR_HIP and st3_last_hip_error() gives the hipError_t (thread-local).
+ *   - Element types: ST3_F32 (4 bytes) or ST3_BF16 (2 bytes, upper half of an IEEE float32).
+ *     Arithmetic is float32 throughout; outputs are rounded to the element type (nearest even).
+ *   - head_dim must be 64 or 128.  Rows of head_dim elements are contiguous and 16-byte aligned;
+ *     strides are given in ELEMENTS unless a parameter says bytes.
+ *   - Counts of kept tokens are integers chosen by the caller (see the schedule helpers below);
+ *     no ratio is ever rounded on the device.
+ */
+#ifndef ST3_H
+#define ST3_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Symbols below are the only ones the shared library exports. */
+#define ST3_EXPORT __attribute__((visibility("default")))
+
+typedef enum {
+    ST3_OK = 0,
+    ST3_ERR_INVALID_ARG = 1,        /* null pointer, negative size, k > n, length > capacity ... */
+    ST3_ERR_UNSUPPORTED = 2,        /* head_dim / dtype / size outside what the kernels handle  */
+    ST3_ERR_WORKSPACE_TOO_SMALL = 3,
+    ST3_ERR_HIP = 4
+} st3_status;
+
+typedef enum { ST3_F32 = 0, ST3_BF16 = 1 } st3_dtype;
+
+/* How select-and-compact rearranges a layer's cache (see st3_select_compact_layer). */
+typedef enum { ST3_STABLE = 0, ST3_HOLE_FILL = 1 } st3_compact_mode;
+
+/* Attenuation function of Eq. 8 / Sec. 4.4, plus the fixed per-step drop used by the tiny case. */
+typedef enum { ST3_ANNEAL_COS = 0, ST3_ANNEAL_LINEAR = 1, ST3_ANNEAL_EXP = 2, ST3_ANNEAL_DROP = 3,
+               ST3_ANNEAL_NONE = 4 } st3_anneal_kind;
+
+typedef struct {
+    int32_t batch;          /* B  */
+    int32_t heads;          /* H  (multi-head attention: as many KV heads as query heads) */
+    int32_t head_dim;       /* d: 64 or 128 */
+    int32_t dtype;          /* st3_dtype of q/k/v/out */
+    float   softmax_scale;  /* logits are (q.k)*softmax_scale; 0 means 1/sqrt(d) (Eq. 2) */
+} st3_attn_shape;
+
+/* A [B, H, n, d] tensor on the DEVICE; element (b,h,t,c) at data + b*stride_b + h*stride_h + t*stride_t + c. */
+typedef struct {
+    void*   data;
+    int64_t stride_b, stride_h, stride_t;
+} st3_tensor4;
+
+/* One layer's KV cache on the DEVICE: K and V share strides; `capacity` rows exist per (b,h). */
+typedef struct {
+    void*   k;
+    void*   v;
+    int64_t stride_b, stride_h, stride_t;
+    int32_t capacity;
+} st3_kv_layer;
+
+/* Where the visual keys sit in a layer's cache.  For sequence b the cache holds kv_len[b] rows;
+ * rows [sys_len, sys_len + vis_len[b]) are visual keys; everything else (system prompt, instruction,
+ * generated tokens) is never pruned.  kv_len and vis_len live on the DEVICE because the kernels
+ * update them; max_kv_len / max_vis_len are HOST-side upper bounds used to size launches and to
+ * index the workspace (kv_len[b] <= max_kv_len <= capacity, vis_len[b] <= max_vis_len). */
+typedef struct {
+    int32_t  sys_len;
+    int32_t  max_vis_len;
+    int32_t  max_kv_len;
+    int32_t* vis_len;       /* DEVICE [B] */
+    int32_t* kv_len;        /* DEVICE [B] */
+} st3_segments;
+
+ST3_EXPORT const char* st3_status_string(st3_status s);
+ST3_EXPORT int st3_last_hip_error(void);
+ST3_EXPORT uint32_t st3_version(void);                 /* major<<16 | minor<<8 | patch */
+
+/* Bytes of DEVICE workspace that any call below needs for the given bounds (256-byte aligned
+ * base expected).  max_q_len is the longest prefill sequence, score_window the largest W. */
+ST3_EXPORT size_t st3_workspace_bytes(const st3_attn_shape* shape, int32_t max_kv_len, int32_t max_vis_len,
+                           int32_t max_q_len, int32_t score_window);
+
+/* ---------------------------------------------------------------------------------------------
+ * Prefill attention with visual-mass output (Eq. 2; score extraction of Sec. 3.2).
+ *   out[b,h,i,:] = sum_{j<=i} softmax_j((q_i . k_j) * scale) v_j          for i in [0, n)
+ *   vis_mass[b,j] = (1/H) sum_h sum_{i in last `score_window` rows} A_h[i, sys_len + j],  j in [0, vis_len)
+ * q, k, v, out: DEVICE [B,H,n,d] with their own strides (k/v may point straight into a layer's
+ * cache so that they become its first n rows).  vis_mass: DEVICE float32, row b at
+ * vis_mass + b*mass_stride (mass_stride >= vis_len), may be NULL.
+ * The paper takes the last row only (score_window = 1).  Requires 1 <= score_window <= min(n, 16),
+ * sys_len + vis_len <= n <= 32768.
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_prefill_attention(const st3_attn_shape* shape, const st3_tensor4* q, const st3_tensor4* k,
+                                 const st3_tensor4* v, int32_t n, int32_t sys_len, int32_t vis_len,
+                                 int32_t score_window, const st3_tensor4* out, float* vis_mass,
+                                 int64_t mass_stride, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * KV append (KV-cache use of Sec. 4.3): writes k_new/v_new (DEVICE, contiguous [B,H,d]) at row
+ * kv_len[b] of the layer's cache, then kv_len[b] += 1.  Host check: max_kv_len < capacity.
+ * A sequence with kv_len[b] >= capacity is left unchanged (device-side guard).
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_kv_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                         const void* k_new, const void* v_new, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Decode attention with visual-mass output (Eq. 2 with one query row that follows every cached
+ * key; score extraction of Sec. 3.2 applied to that row).
+ *   out[b,h,:]   = sum_{j<kv_len[b]} p_j v_j,  p = softmax over the kv_len[b] cached keys
+ *   vis_mass[b,j] = (1/H) sum_h p_h[sys_len + j],  j in [0, vis_len[b])
+ * q, out: DEVICE contiguous [B,H,d].  vis_mass: DEVICE float32 with row stride `mass_stride`
+ * (>= max_vis_len) or NULL; entries j >= vis_len[b] are left untouched.  Split-KV: the cache is
+ * read once, in chunks handled by different workgroups whose partial results are merged by a
+ * second kernel; the merge order is fixed, so results are reproducible run to run.
+ * A sequence with kv_len[b] == 0 gets out = 0.
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_decode_attention(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
+                                const st3_segments* seg, void* out, float* vis_mass, int64_t mass_stride,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Top-k selection (Eq. 3: indices of the G highest scores).  Total order: higher score first,
+ * then lower tie id first (tie_ids == NULL: the position itself).  -0.0 ranks equal to +0.0.
+ *   scores:  DEVICE float32, row b at scores + b*score_stride, n_dev[b] valid entries
+ *            (n_dev == NULL: every row has n entries).  n <= 16384.
+ *   tie_ids: DEVICE int32 with row stride id_stride, distinct non-negative values per row, or NULL.
+ *   k:       entries to keep; row b keeps min(k, n_b).
+ *   keep_mask: DEVICE uint8 [B, n]  (1 = kept; entries >= n_b are written 0), may be NULL.
+ *   keep_idx:  DEVICE int32, row b at keep_idx + b*idx_stride (idx_stride >= k): positions of the
+ *              kept entries in ascending order, padded with -1 up to k entries; may be NULL.
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_select_topk(const float* scores, int64_t score_stride, const int32_t* tie_ids, int64_t id_stride,
+                           int32_t batch, const int32_t* n_dev, int32_t n, int32_t k,
+                           uint8_t* keep_mask, int32_t* keep_idx, int64_t idx_stride, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Stable in-place row compaction (Alg. 1/3: V = V[T]; X = [S, V, I] rebuilt, order preserved).
+ * For every (b, i) with b < batch, i < inner, on the strip that starts at
+ * rows + b*stride_b_bytes + i*stride_inner_bytes:
+ *   row[r] <- row[keep_idx[b][r]]   for r in [0, k)      (keep_idx row b at keep_idx + b*idx_stride,
+ *                                                          ascending; entries outside [0, n) are skipped)
+ *   row[k_b + j] <- row[n + j]      for j in [0, tail_rows)   (k_b = number of valid indices)
+ * Rows are row_bytes long (multiple of 4), stride_row_bytes apart.  Used for Q/K/V rows of a
+ * layer's input, hidden rows, and the score / id columns (row_bytes = 4).
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_compact_rows(void* rows, int32_t batch, int32_t inner, int64_t stride_b_bytes,
+                            int64_t stride_inner_bytes, int64_t stride_row_bytes, int32_t row_bytes,
+                            const int32_t* keep_idx, int64_t idx_stride, int32_t k, int32_t n, int32_t tail_rows,
+                            void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Select-and-compact for one layer at one decode step (Eq. 7: C_v <- C_v[: |V^{l,0}| * beta^t];
+ * Alg. 3, VTA branch; eviction semantics of Sec. 4.3).  For every sequence b with
+ * vis_len[b] > keep_count: ranks the layer's visual keys by score_col (total order of
+ * st3_select_topk, ties by id_col), keeps the best keep_count, evicts the rest from K and V,
+ * applies the same rearrangement to score_col and id_col, and updates vis_len[b] / kv_len[b].
+ *   score_col: DEVICE float32, row stride col_stride; entry p ranks cache row sys_len + p.
+ *   id_col:    DEVICE int32,  same layout; original visual token ids (distinct per row).
+ *   mode ST3_STABLE:    survivors keep their relative order and the rows after the visual segment
+ *                       move down by the number evicted (what a slice assignment would do).
+ *   mode ST3_HOLE_FILL: survivors from the evicted tail of the segment move into the holes, and
+ *                       the vacated end of the segment is refilled from the END of the cache, so
+ *                       at most 2*(evicted) rows move.  Valid for decode only, where softmax
+ *                       attention does not depend on the order of cached keys.
+ * max_vis_len / max_kv_len in `seg` must bound the lengths BEFORE the call.
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_select_compact_layer(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                                    float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
+                                    int32_t mode, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * One layer of one decode step, in the order of Alg. 3's VTA branch:
+ *   (1) select-and-compact to keep_count (skipped when keep_count < 0),
+ *   (2) append k_new/v_new,
+ *   (3) decode attention of q over the resulting cache, with visual mass.
+ * Same arguments as the three calls it replaces.  max_* in `seg` bound the lengths before the
+ * call; host check: max_kv_len < capacity.
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_decode_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                                 float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
+                                 int32_t mode, const void* q, const void* k_new, const void* v_new,
+                                 void* out, float* vis_mass, int64_t mass_stride,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Retention schedules: HOST-only pure functions that fill integer tables.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Strided progressive pruning (Sec. 3.2 "avoid pruning in the first three layers"; Alg. 1
+ * condition l >= 3 and (l-3) % S == 0; Eq. 9 with P the first event's ratio and R each later
+ * event's, both relative to the original count).  Ratios in basis points.  keep_l: HOST [L]. */
+ST3_EXPORT st3_status st3_schedule_pvtp(int32_t L, int32_t n_vis, int32_t first_layer, int32_t stride_S,
+                             int32_t P_bp, int32_t R_bp, int32_t* keep_l);
+
+/* Keep ratio 1 up to last_full_layer, then falling linearly to end_ratio_bp at layer L-1. */
+ST3_EXPORT st3_status st3_schedule_linear(int32_t L, int32_t n_vis, int32_t last_full_layer, int32_t end_ratio_bp,
+                               int32_t* keep_l);
+
+/* Eq. 7-8: keep_lt[l*(T+1) + t] = floor(keep_l0[l] * beta(t)), t = 0..T; beta per `kind` with
+ * param = tau (COS, LINEAR), sigma (EXP) or tokens dropped per step (DROP).  HOST arrays. */
+ST3_EXPORT st3_status st3_schedule_anneal(int32_t kind, double param, int32_t T, const int32_t* keep_l0, int32_t L,
+                               int32_t* keep_lt);
+
+/* KV-cache bytes held by `batch` sequences whose layer l caches kv_lens[l] keys (HOST array [L]). */
+ST3_EXPORT int64_t st3_kv_bytes(int32_t batch, int32_t heads, int32_t head_dim, int32_t dtype, const int32_t* kv_lens,
+                     int32_t L);
+
+/* ---------------------------------------------------------------------------------------------
+ * Diagnostics: timing of the split-KV decode kernel (the kernel that streams K and V).
+ * st3_profile_enable(n) creates (host-side) hipEvents for up to n launches and makes
+ * st3_decode_attention / st3_decode_layer_step record one event right before and one right after
+ * that kernel on the caller's stream; recording stops silently once n launches are used.
+ * st3_profile_read waits for the recorded events, returns the summed / min / max kernel time in
+ * milliseconds and the number of launches timed, and switches recording off.  HOST pointers, any
+ * may be NULL.  Not thread-safe; intended for benchmarks.
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_profile_enable(int32_t max_launches);
+ST3_EXPORT st3_status st3_profile_read(double* total_ms, int64_t* launches, double* min_ms, double* max_ms);
+
+/* Test hook: which kernel st3_prefill_attention uses for bf16 inputs.  0 = automatic (MFMA
+ * kernel), 1 = the float32 row kernel, 2 = MFMA or fail.  Lets the two be compared on one input.
+ * Process-wide; not for production use. */
+ST3_EXPORT void st3_debug_set_prefill_path(int path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ST3_H */

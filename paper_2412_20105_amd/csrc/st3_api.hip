@@ -1,0 +1,205 @@
+// Status/version queries, workspace sizing, the fused per-layer decode step, and the host-only
+// retention-schedule helpers (Sec. 3.2, Eq. 7-9, Alg. 1 of the paper).
+#include <cmath>
+#include <vector>
+
+#include "st3_common.h"
+
+namespace st3 {
+
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+// ---------------------------------------------------------------------------------------------
+// Optional timing of the split-KV decode kernel: a pool of hipEvent pairs recorded on the
+// caller's stream right before and right after that kernel.  Off unless st3_profile_enable().
+// ---------------------------------------------------------------------------------------------
+struct DecodeProfiler {
+    std::vector<hipEvent_t> ev;     // 2 per launch
+    size_t used = 0;                // launches recorded
+    bool on = false;
+};
+static DecodeProfiler g_prof;
+
+void profile_mark(hipStream_t st, bool after) {
+    if (!g_prof.on) return;
+    if (!after && (g_prof.used + 1) * 2 > g_prof.ev.size()) { g_prof.on = false; return; }   // pool exhausted
+    (void)hipEventRecord(g_prof.ev[g_prof.used * 2 + (after ? 1 : 0)], st);
+    if (after) g_prof.used += 1;
+}
+
+st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
+st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
+                          const st3_segments* seg, int32_t max_kv_len, void* out, float* vis_mass,
+                          int64_t mass_stride, void* workspace, size_t workspace_bytes, hipStream_t st);
+st3_status enqueue_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                          const void* k_new, const void* v_new, hipStream_t st);
+st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                                  float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
+                                  int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st);
+
+}  // namespace st3
+
+extern "C" const char* st3_status_string(st3_status s) {
+    switch (s) {
+        case ST3_OK: return "ok";
+        case ST3_ERR_INVALID_ARG: return "invalid argument";
+        case ST3_ERR_UNSUPPORTED: return "unsupported shape, type or size";
+        case ST3_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case ST3_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+extern "C" int st3_last_hip_error(void) { return st3::g_last_hip_error; }
+extern "C" uint32_t st3_version(void) { return (0u << 16) | (1u << 8) | 0u; }
+
+extern "C" size_t st3_workspace_bytes(const st3_attn_shape* shape, int32_t max_kv_len, int32_t max_vis_len,
+                                      int32_t max_q_len, int32_t score_window) {
+    if (st3::check_shape(shape) != ST3_OK) return 0;
+    if (max_kv_len < 0 || max_vis_len < 0 || max_q_len < 0) return 0;
+    if (score_window < 1) score_window = 1;
+    if (score_window > st3::kMaxWindow) score_window = st3::kMaxWindow;
+    // the fused step appends before attending, so its split count is taken at max_kv_len + 1
+    return st3::workspace_layout(shape->batch, shape->heads, shape->head_dim, max_kv_len + 1, max_vis_len,
+                                 max_q_len, score_window).total;
+}
+
+extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv,
+                                            const st3_segments* seg, float* score_col, int32_t* id_col,
+                                            int64_t col_stride, int32_t keep_count, int32_t mode, const void* q,
+                                            const void* k_new, const void* v_new, void* out, float* vis_mass,
+                                            int64_t mass_stride, void* workspace, size_t workspace_bytes,
+                                            void* stream) {
+    using namespace st3;
+    st3_status s = check_shape(shape);
+    if (s != ST3_OK) return s;
+    s = validate_kv(shape, kv, seg);
+    if (s != ST3_OK) return s;
+    if (!q || !k_new || !v_new || !out || !workspace) return ST3_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(workspace))
+        return ST3_ERR_INVALID_ARG;
+    if (seg->max_kv_len >= kv->capacity) return ST3_ERR_INVALID_ARG;
+    if (vis_mass && mass_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
+    if (keep_count >= 0) {
+        if (!score_col || !id_col || col_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
+        if (mode != ST3_STABLE && mode != ST3_HOLE_FILL) return ST3_ERR_INVALID_ARG;
+    }
+    // all size checks before the first launch, so that an error enqueues nothing
+    WorkspaceLayout wl = workspace_layout(shape->batch, shape->heads, shape->head_dim, seg->max_kv_len + 1,
+                                          seg->max_vis_len, 0, 1);
+    if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (keep_count >= 0) {
+        s = enqueue_select_compact(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, workspace,
+                                   workspace_bytes, st);
+        if (s != ST3_OK) return s;
+    }
+    s = enqueue_append(shape, kv, seg, k_new, v_new, st);
+    if (s != ST3_OK) return s;
+    return enqueue_decode(shape, q, kv, seg, seg->max_kv_len + 1, out, vis_mass, mass_stride, workspace,
+                          workspace_bytes, st);
+}
+
+extern "C" st3_status st3_profile_enable(int32_t max_launches) {
+    using namespace st3;
+    if (max_launches <= 0 || max_launches > (1 << 22)) return ST3_ERR_INVALID_ARG;
+    while (g_prof.ev.size() < (size_t)max_launches * 2) {
+        hipEvent_t e;
+        hipError_t err = hipEventCreate(&e);
+        if (err != hipSuccess) { set_last_hip_error(err); return ST3_ERR_HIP; }
+        g_prof.ev.push_back(e);
+    }
+    g_prof.used = 0;
+    g_prof.on = true;
+    return ST3_OK;
+}
+
+extern "C" st3_status st3_profile_read(double* total_ms, int64_t* launches, double* min_ms, double* max_ms) {
+    using namespace st3;
+    g_prof.on = false;
+    double tot = 0.0, mn = 1e30, mx = 0.0;
+    for (size_t i = 0; i < g_prof.used; ++i) {
+        hipError_t err = hipEventSynchronize(g_prof.ev[2 * i + 1]);
+        float ms = 0.f;
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]);
+        if (err != hipSuccess) { set_last_hip_error(err); return ST3_ERR_HIP; }
+        tot += ms; mn = ms < mn ? ms : mn; mx = ms > mx ? ms : mx;
+    }
+    if (total_ms) *total_ms = tot;
+    if (launches) *launches = (int64_t)g_prof.used;
+    if (min_ms) *min_ms = g_prof.used ? mn : 0.0;
+    if (max_ms) *max_ms = mx;
+    g_prof.used = 0;
+    return ST3_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Retention schedules (host only)
+// ---------------------------------------------------------------------------------------------
+extern "C" st3_status st3_schedule_pvtp(int32_t L, int32_t n_vis, int32_t first_layer, int32_t stride_S,
+                                        int32_t P_bp, int32_t R_bp, int32_t* keep_l) {
+    if (!keep_l || L <= 0 || n_vis < 0 || first_layer < 0 || stride_S <= 0) return ST3_ERR_INVALID_ARG;
+    if (P_bp < 0 || P_bp > 10000 || R_bp < 0 || R_bp > 10000) return ST3_ERR_INVALID_ARG;
+    int64_t gone_bp = 0;            // share of the ORIGINAL count removed so far
+    for (int32_t l = 0; l < L; ++l) {
+        if (l == first_layer) gone_bp += P_bp;
+        else if (l > first_layer && (l - first_layer) % stride_S == 0) gone_bp += R_bp;
+        int64_t left_bp = gone_bp >= 10000 ? 0 : 10000 - gone_bp;
+        keep_l[l] = (int32_t)(((int64_t)n_vis * left_bp) / 10000);
+    }
+    return ST3_OK;
+}
+
+extern "C" st3_status st3_schedule_linear(int32_t L, int32_t n_vis, int32_t last_full_layer, int32_t end_ratio_bp,
+                                          int32_t* keep_l) {
+    if (!keep_l || L <= 0 || n_vis < 0 || last_full_layer < 0) return ST3_ERR_INVALID_ARG;
+    if (end_ratio_bp < 0 || end_ratio_bp > 10000) return ST3_ERR_INVALID_ARG;
+    const int64_t span = (int64_t)(L - 1) - last_full_layer;
+    for (int32_t l = 0; l < L; ++l) {
+        if (l <= last_full_layer || span <= 0) { keep_l[l] = n_vis; continue; }
+        const int64_t num = (int64_t)n_vis * (10000 - end_ratio_bp) * (l - last_full_layer);
+        const int64_t den = 10000 * span;
+        keep_l[l] = (int32_t)(n_vis - (num + den - 1) / den);       // dropped count rounded up
+    }
+    return ST3_OK;
+}
+
+extern "C" st3_status st3_schedule_anneal(int32_t kind, double param, int32_t T, const int32_t* keep_l0, int32_t L,
+                                          int32_t* keep_lt) {
+    if (!keep_l0 || !keep_lt || L <= 0 || T < 0) return ST3_ERR_INVALID_ARG;
+    if (kind < ST3_ANNEAL_COS || kind > ST3_ANNEAL_NONE) return ST3_ERR_INVALID_ARG;
+    if (kind != ST3_ANNEAL_NONE && kind != ST3_ANNEAL_DROP && !(param > 0.0)) return ST3_ERR_INVALID_ARG;
+    const double half_pi = 1.57079632679489661923;
+    for (int32_t l = 0; l < L; ++l) {
+        const int32_t k0 = keep_l0[l];
+        if (k0 < 0) return ST3_ERR_INVALID_ARG;
+        for (int32_t t = 0; t <= T; ++t) {
+            int64_t c;
+            switch (kind) {
+                case ST3_ANNEAL_COS:
+                    c = t < param ? (int64_t)std::floor(k0 * std::cos(t * half_pi / param) + 1e-9) : 0; break;
+                case ST3_ANNEAL_LINEAR:
+                    c = t < param ? (int64_t)std::floor(k0 * (1.0 - t / param) + 1e-9) : 0; break;
+                case ST3_ANNEAL_EXP:
+                    c = (int64_t)std::floor(k0 * std::exp(-t / param) + 1e-9); break;
+                case ST3_ANNEAL_DROP:
+                    c = (int64_t)k0 - (int64_t)param * t; break;
+                default:
+                    c = k0;
+            }
+            if (c < 0) c = 0;
+            if (c > k0) c = k0;
+            keep_lt[(int64_t)l * (T + 1) + t] = (int32_t)c;
+        }
+    }
+    return ST3_OK;
+}
+
+extern "C" int64_t st3_kv_bytes(int32_t batch, int32_t heads, int32_t head_dim, int32_t dtype,
+                                const int32_t* kv_lens, int32_t L) {
+    if (!kv_lens || batch < 0 || heads < 0 || head_dim < 0 || L < 0) return -1;
+    int64_t rows = 0;
+    for (int32_t l = 0; l < L; ++l) rows += kv_lens[l];
+    return (int64_t)batch * rows * 2 * heads * head_dim * st3::elem_bytes(dtype);
+}

@@ -1,0 +1,115 @@
+// One wavefront streaming a range of cached K/V rows for a single query (Eq. 2 with one row).
+//
+// Layout of the work inside the wave: a row of D elements is 16*LPR bytes, so LPR consecutive
+// lanes each own a 16-byte slice of it and one 64-lane load instruction fetches RPL = 64/LPR
+// whole rows, fully coalesced.  Lane l therefore always sees row-group l / LPR and column slice
+// l % LPR, for K and for V alike: the logit of a row is reduced over the LPR lanes that hold it
+// (DPP), and the probability it yields multiplies exactly the V slice the same lane has loaded.
+// U such loads of K and U of V are in flight per tile, i.e. U*RPL keys.
+#pragma once
+
+#include "st3_common.h"
+
+namespace st3 {
+
+template <typename T, int D>
+struct RowMap {
+    static constexpr int EPL = ElemTraits<T>::kPerVec;          // elements per lane
+    static constexpr int LPR = D / EPL;                         // lanes per row
+    static constexpr int RPL = kWave / LPR;                     // rows per wave-wide load
+};
+
+template <typename T, int D>
+__device__ __forceinline__ void load_q_slice(const T* qrow, int lane, float* qf) {
+    using M = RowMap<T, D>;
+    uint4 raw = *reinterpret_cast<const uint4*>(qrow + (lane % M::LPR) * M::EPL);
+    ElemTraits<T>::unpack(raw, qf);
+}
+
+// Online-softmax state of one wave.  `l` holds, per lane, the sum of probabilities over the rows
+// of that lane's row-group only; `acc` likewise.  finish_wave() folds the row-groups together.
+template <int EPL>
+struct WaveState {
+    float m;            // running maximum (log2 domain), wave-uniform
+    float l;
+    float acc[EPL];
+};
+
+// Streams rows [r0, r1) (r0 < r1).  kbase/vbase point at row 0 of this (b,h) strip.
+// logit_out (may be null): float array indexed by (row - vis_lo) for rows in [vis_lo, vis_hi),
+// receives the scaled logit in the log2 domain.
+template <typename T, int D, int U>
+__device__ __forceinline__ void wave_attend(const float* qf, const T* kbase, const T* vbase, int64_t stride_t,
+                                            int r0, int r1, float scale_l2, int lane,
+                                            WaveState<RowMap<T, D>::EPL>& st,
+                                            float* logit_out, int vis_lo, int vis_hi) {
+    using M = RowMap<T, D>;
+    constexpr int EPL = M::EPL, LPR = M::LPR, RPL = M::RPL;
+    const int grp = lane / LPR;
+    const int64_t col = (int64_t)(lane % LPR) * EPL;
+    for (int t0 = r0; t0 < r1; t0 += U * RPL) {
+        uint4 kr[U], vr[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int row = t0 + u * RPL + grp;
+            ok[u] = row < r1;
+            int64_t off = (int64_t)(ok[u] ? row : r0) * stride_t + col;
+            kr[u] = *reinterpret_cast<const uint4*>(kbase + off);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int row = t0 + u * RPL + grp;
+            int64_t off = (int64_t)(ok[u] ? row : r0) * stride_t + col;
+            vr[u] = *reinterpret_cast<const uint4*>(vbase + off);
+        }
+        float s[U];
+        float mt = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float kf[EPL];
+            ElemTraits<T>::unpack(kr[u], kf);
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) part = fmaf(qf[e], kf[e], part);
+            part = group_sum<LPR>(part) * scale_l2;
+            int row = t0 + u * RPL + grp;
+            if (logit_out != nullptr && ok[u] && (lane % LPR) == 0 && row >= vis_lo && row < vis_hi)
+                logit_out[row - vis_lo] = part;
+            s[u] = ok[u] ? part : -INFINITY;
+            mt = fmaxf(mt, s[u]);
+        }
+#pragma unroll
+        for (int off = LPR; off < kWave; off <<= 1) mt = fmaxf(mt, __shfl_xor(mt, off));
+        float m_new = fmaxf(st.m, mt);
+        float alpha = exp2_fast(st.m - m_new);       // first tile: exp2(-inf) = 0
+        st.m = m_new;
+        st.l *= alpha;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) st.acc[e] *= alpha;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float p = exp2_fast(s[u] - m_new);       // masked rows: exp2(-inf) = 0
+            st.l += p;
+            float vf[EPL];
+            ElemTraits<T>::unpack(vr[u], vf);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) st.acc[e] = fmaf(p, vf[e], st.acc[e]);
+        }
+    }
+}
+
+// Folds the row-groups of a wave together: afterwards every lane holds the wave's total l and
+// the total acc for its column slice.
+template <typename T, int D>
+__device__ __forceinline__ void finish_wave(WaveState<RowMap<T, D>::EPL>& st) {
+    using M = RowMap<T, D>;
+#pragma unroll
+    for (int off = M::LPR; off < kWave; off <<= 1) {
+        st.l += __shfl_xor(st.l, off);
+#pragma unroll
+        for (int e = 0; e < M::EPL; ++e) st.acc[e] += __shfl_xor(st.acc[e], off);
+    }
+}
+
+}  // namespace st3

@@ -1,0 +1,142 @@
+// Internal helpers shared by the HIP translation units of libst3 (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "st3.h"
+
+namespace st3 {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+void set_last_hip_error(hipError_t e);
+
+// Launch-error capture used by every entry point after enqueueing its kernels.
+inline st3_status check_launch() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_last_hip_error(e);
+        return ST3_ERR_HIP;
+    }
+    return ST3_OK;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int elem_bytes(int dtype) { return dtype == ST3_BF16 ? 2 : 4; }
+
+// Validates what every attention entry point needs from `shape`.
+inline st3_status check_shape(const st3_attn_shape* s) {
+    if (!s) return ST3_ERR_INVALID_ARG;
+    if (s->batch <= 0 || s->heads <= 0) return ST3_ERR_INVALID_ARG;
+    if (s->dtype != ST3_F32 && s->dtype != ST3_BF16) return ST3_ERR_UNSUPPORTED;
+    if (s->head_dim != 64 && s->head_dim != 128) return ST3_ERR_UNSUPPORTED;
+    if (s->heads > 1024 || s->batch > 65535) return ST3_ERR_UNSUPPORTED;
+    if (!(s->softmax_scale >= 0.0f)) return ST3_ERR_INVALID_ARG;
+    return ST3_OK;
+}
+
+inline float scale_log2(const st3_attn_shape* s) {
+    float sc = s->softmax_scale > 0.0f ? s->softmax_scale : 1.0f / sqrtf((float)s->head_dim);
+    return sc * kLog2e;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Workspace carving.  One layout serves every call; offsets are fixed by the bounds alone.
+// ---------------------------------------------------------------------------------------------
+constexpr int kDecodeChunk = 256;          // keys per decode workgroup (split-KV granularity)
+constexpr int kMaxWindow = 16;
+
+struct WorkspaceLayout {
+    size_t part_o, part_ml, logits, moves_cnt, moves, pre_logits, pre_ml, total;
+    int nsplit_max;
+    int max_moves;
+};
+
+inline WorkspaceLayout workspace_layout(int B, int H, int D, int max_kv, int max_vis, int max_q, int window) {
+    WorkspaceLayout w{};
+    if (max_kv < 1) max_kv = 1;
+    if (max_vis < 0) max_vis = 0;
+    if (window < 1) window = 1;
+    w.nsplit_max = (max_kv + kDecodeChunk - 1) / kDecodeChunk;
+    w.max_moves = max_kv > 2 * max_vis ? max_kv : 2 * max_vis;
+    size_t off = 0;
+    size_t BH = (size_t)B * H;
+    w.part_o = off;     off = align_up(off + BH * w.nsplit_max * D * sizeof(float), 256);
+    w.part_ml = off;    off = align_up(off + BH * w.nsplit_max * 2 * sizeof(float), 256);
+    w.logits = off;     off = align_up(off + BH * (size_t)max_vis * sizeof(float), 256);
+    w.moves_cnt = off;  off = align_up(off + (size_t)B * sizeof(int32_t), 256);
+    w.moves = off;      off = align_up(off + (size_t)B * w.max_moves * 2 * sizeof(int32_t), 256);
+    w.pre_logits = off; off = align_up(off + BH * (size_t)window * max_vis * sizeof(float), 256);
+    w.pre_ml = off;     off = align_up(off + BH * (size_t)window * 2 * sizeof(float), 256);
+    (void)max_q;
+    w.total = off;
+    return w;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Device helpers
+// ---------------------------------------------------------------------------------------------
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// float32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+template <typename T> struct ElemTraits;
+template <> struct ElemTraits<float> {
+    static constexpr int kBytes = 4;
+    static constexpr int kPerVec = 4;       // elements in a 16-byte vector
+    __device__ static __forceinline__ void unpack(const uint4& r, float* f) {
+        f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+        f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+    }
+    __device__ static __forceinline__ uint4 pack(const float* f) {
+        return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    }
+};
+struct bf16_t { uint16_t bits; };
+template <> struct ElemTraits<bf16_t> {
+    static constexpr int kBytes = 2;
+    static constexpr int kPerVec = 8;
+    __device__ static __forceinline__ void unpack(const uint4& r, float* f) {
+        f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+        f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+    }
+    __device__ static __forceinline__ uint4 pack(const float* f) {
+        return make_uint4(f32_to_bf16_bits(f[0]) | (f32_to_bf16_bits(f[1]) << 16),
+                          f32_to_bf16_bits(f[2]) | (f32_to_bf16_bits(f[3]) << 16),
+                          f32_to_bf16_bits(f[4]) | (f32_to_bf16_bits(f[5]) << 16),
+                          f32_to_bf16_bits(f[6]) | (f32_to_bf16_bits(f[7]) << 16));
+    }
+};
+
+// Sum over aligned groups of G consecutive lanes (G in {8,16,32}); every lane of a group ends
+// with the group's total.  Steps below 16 lanes use DPP row operations; they rely on all lanes
+// of the already-reduced sub-group holding the same value, so a mirror acts as the XOR step.
+template <int G>
+__device__ __forceinline__ float group_sum(float v) {
+    // xor 1, xor 2 inside a quad
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+    // row_half_mirror: lane i <-> 7-i within 8 lanes
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
+    if (G >= 16)  // row_mirror: lane i <-> 15-i within 16 lanes
+        v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
+    if (G >= 32) v += __shfl_xor(v, 16);
+    return v;
+}
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+#endif  // __HIPCC__
+
+}  // namespace st3

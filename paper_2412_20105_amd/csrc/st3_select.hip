@@ -1,0 +1,487 @@
+// Top-k selection of visual tokens by attention mass (Eq. 3), the in-place compaction of rows
+// that follows it (Alg. 1/3: V = V[T]), and the per-layer, per-step eviction of visual KV rows
+// (Eq. 7, Alg. 3 VTA branch).
+//
+// Selection is an exact radix select on the order-preserving 32-bit image of the float32 score
+// (4 passes of 8 bits, histogram in LDS), followed - only when the k-th score is shared - by a
+// second radix select on the tie ids, so that the result is the unique top-k set under the total
+// order (score descending, id ascending).  One workgroup per sequence.
+#include "st3_common.h"
+
+namespace st3 {
+
+namespace {
+
+constexpr int kSelThreads = 256;
+constexpr int kSelWaves = kSelThreads / kWave;
+constexpr int kSelLdsKeys = 8192;
+
+__device__ __forceinline__ uint32_t score_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    if (u == 0x80000000u) u = 0u;                       // -0.0 ranks with +0.0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger float <-> larger key
+}
+
+struct SelShared {
+    uint32_t keys[kSelLdsKeys];
+    uint32_t flags[kSelLdsKeys / 32];
+    int hist[256];
+    int wave_tot[kSelWaves];
+    int sel_bin, sel_want, sel_cnt;
+    int red;
+};
+
+// Inclusive scan of one int per thread over the 256 threads of the block, in thread order.
+__device__ __forceinline__ int block_incl_scan(int v, SelShared& sm) {
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        int t = __shfl_up(v, off);
+        if (lane >= off) v += t;
+    }
+    __syncthreads();                                    // protects wave_tot from the previous use
+    if (lane == kWave - 1) sm.wave_tot[wave] = v;
+    __syncthreads();
+    int base = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) base += (w < wave) ? sm.wave_tot[w] : 0;
+    return v + base;
+}
+
+// Finds, among the elements i in [0,n) for which f(i, key) is true, the key of rank `want`
+// (1-based, descending).  Returns it; `want` becomes the number of elements equal to that key
+// that still belong to the top set, `ties` the number of elements equal to it.
+template <class F>
+__device__ __forceinline__ uint32_t radix_select_desc(F f, int n, int& want, int& ties, SelShared& sm) {
+    uint32_t prefix = 0, pmask = 0;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        sm.hist[threadIdx.x] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < n; i += kSelThreads) {
+            uint32_t key;
+            if (f(i, key) && (key & pmask) == prefix) atomicAdd(&sm.hist[(key >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        int v = sm.hist[255 - threadIdx.x];             // thread order = descending bin order
+        int incl = block_incl_scan(v, sm);
+        if (incl >= want && incl - v < want) {
+            sm.sel_bin = 255 - threadIdx.x;
+            sm.sel_want = want - (incl - v);
+            sm.sel_cnt = v;
+        }
+        __syncthreads();
+        prefix |= (uint32_t)sm.sel_bin << shift;
+        pmask |= 255u << shift;
+        want = sm.sel_want;
+        ties = sm.sel_cnt;
+        __syncthreads();
+    }
+    return prefix;
+}
+
+// Marks the top-k entries of one row in sm.flags (bit p of word p/32).  Requires n <= kSelLdsKeys
+// when `staged`; otherwise keys are recomputed from global memory on every pass.
+// ids == nullptr: the position is the id.
+__device__ void mark_topk(const float* scores, const int32_t* ids, int n, int k, bool staged, SelShared& sm,
+                          uint32_t& thr, uint32_t& thr_id, bool& all_ties) {
+    auto key_at = [&](int i) -> uint32_t { return staged ? sm.keys[i] : score_key(scores[i]); };
+    if (staged) {
+        for (int i = threadIdx.x; i < n; i += kSelThreads) sm.keys[i] = score_key(scores[i]);
+        __syncthreads();
+    }
+    int want = k, ties = 0;
+    thr = radix_select_desc([&](int i, uint32_t& key) { key = key_at(i); return true; }, n, want, ties, sm);
+    all_ties = (want == ties);
+    thr_id = 0;
+    if (!all_ties) {
+        const uint32_t t = thr;
+        int want2 = want, ties2 = 0;
+        thr_id = radix_select_desc(
+            [&](int i, uint32_t& key) {
+                key = ~(uint32_t)(ids ? ids[i] : i);    // descending on ~id == ascending on id
+                return key_at(i) == t;
+            },
+            n, want2, ties2, sm);
+    }
+}
+
+__device__ __forceinline__ bool is_kept(uint32_t key, uint32_t idkey, uint32_t thr, uint32_t thr_id, bool all_ties) {
+    return key > thr || (key == thr && (all_ties || idkey >= thr_id));
+}
+
+// ---------------------------------------------------------------------------------------------
+// st3_select_topk
+// ---------------------------------------------------------------------------------------------
+struct TopkArgs {
+    const float* scores;
+    int64_t score_stride;
+    const int32_t* ids;
+    int64_t id_stride;
+    const int32_t* n_dev;
+    int32_t n, k;
+    uint8_t* mask;
+    int32_t* idx;
+    int64_t idx_stride;
+};
+
+__global__ __launch_bounds__(kSelThreads) void select_topk_kernel(TopkArgs a) {
+    __shared__ SelShared sm;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int n = a.n_dev ? a.n_dev[b] : a.n;
+    n = max(0, min(n, a.n));
+    const int k = min(a.k, n);
+    const float* scores = a.scores + b * a.score_stride;
+    const int32_t* ids = a.ids ? a.ids + b * a.id_stride : nullptr;
+    uint8_t* mask = a.mask ? a.mask + (int64_t)b * a.n : nullptr;
+    int32_t* idx = a.idx ? a.idx + (int64_t)b * a.idx_stride : nullptr;
+    const bool staged = n <= kSelLdsKeys;
+    uint32_t thr = 0, thr_id = 0;
+    bool all_ties = true;
+    if (k > 0 && k < n) mark_topk(scores, ids, n, k, staged, sm, thr, thr_id, all_ties);
+    int base = 0;
+    const int n_pad = (a.n + kSelThreads - 1) / kSelThreads * kSelThreads;
+    for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
+        const int p = p0 + tid;
+        bool keep = false;
+        if (p < n) {
+            if (k >= n) keep = true;
+            else if (k > 0) {
+                uint32_t key = staged ? sm.keys[p] : score_key(scores[p]);
+                uint32_t idkey = ~(uint32_t)(ids ? ids[p] : p);
+                keep = is_kept(key, idkey, thr, thr_id, all_ties);
+            }
+        }
+        if (mask && p < a.n) mask[p] = keep ? 1 : 0;
+        int incl = block_incl_scan(keep ? 1 : 0, sm);
+        if (keep && idx && base + incl - 1 < a.k) idx[base + incl - 1] = p;
+        __syncthreads();
+        if (tid == kSelThreads - 1) sm.red = incl;
+        __syncthreads();
+        base += sm.red;
+    }
+    if (idx) for (int i = k + tid; i < a.k; i += kSelThreads) idx[i] = -1;
+}
+
+// ---------------------------------------------------------------------------------------------
+// st3_compact_rows: stable in-place gather.  grid (slabs, inner, batch).
+// Destination rows are produced in ascending chunks; a chunk is loaded completely before any of
+// it is stored, and since keep_idx is ascending with keep_idx[r] >= r no later chunk reads a row
+// an earlier chunk has overwritten.
+// ---------------------------------------------------------------------------------------------
+struct CompactArgs {
+    char* rows;
+    int64_t stride_b, stride_inner, stride_row;     // bytes
+    int32_t row_units, slab_units, unit_bytes;      // a unit is 16 or 4 bytes
+    const int32_t* idx;
+    int64_t idx_stride;
+    int32_t k, n, tail;
+};
+
+template <typename V>
+__global__ __launch_bounds__(256) void compact_rows_kernel(CompactArgs a) {
+    constexpr int UR = 4;
+    __shared__ int sm_kb;
+    __shared__ int sm_cnt[4];
+    const int tid = threadIdx.x, b = blockIdx.z;
+    const int32_t* idx = a.idx + (int64_t)b * a.idx_stride;
+    // number of leading valid indices (0 <= idx < n)
+    int local = 0;
+    for (int i = tid; i < a.k; i += 256) local += (idx[i] >= 0 && idx[i] < a.n) ? 1 : 0;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) local += __shfl_xor(local, off);
+    if (tid % kWave == 0) sm_cnt[tid / kWave] = local;
+    __syncthreads();
+    if (tid == 0) sm_kb = sm_cnt[0] + sm_cnt[1] + sm_cnt[2] + sm_cnt[3];
+    __syncthreads();
+    const int kb = sm_kb;
+    const int total = kb + a.tail;
+    char* strip = a.rows + b * a.stride_b + (int64_t)blockIdx.y * a.stride_inner;
+    const int rows_per_pass = 256 / a.slab_units;
+    const int rr = tid / a.slab_units;
+    const int cu = blockIdx.x * a.slab_units + tid % a.slab_units;
+    const bool col_ok = cu < a.row_units;
+    for (int r0 = 0; r0 < total; r0 += UR * rows_per_pass) {
+        V tmp[UR];
+        int dst[UR];
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            int r = r0 + u * rows_per_pass + rr;
+            dst[u] = -1;
+            if (r < total && col_ok) {
+                int src = r < kb ? idx[r] : a.n + (r - kb);
+                if (src > r && src < a.n + a.tail) {     // src == r: already in place
+                    tmp[u] = *reinterpret_cast<const V*>(strip + src * a.stride_row + (int64_t)cu * sizeof(V));
+                    dst[u] = r;
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < UR; ++u)
+            if (dst[u] >= 0) *reinterpret_cast<V*>(strip + dst[u] * a.stride_row + (int64_t)cu * sizeof(V)) = tmp[u];
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Decode-time eviction: ranking + move list + column update (one workgroup per sequence), then
+// a second kernel that applies the move list to every (b,h) strip of K and V.
+// ---------------------------------------------------------------------------------------------
+struct EvictArgs {
+    float* score_col;
+    int32_t* id_col;
+    int64_t col_stride;
+    int32_t* vis_len;
+    int32_t* kv_len;
+    int32_t sys_len, max_vis, max_kv, keep_count, mode;
+    int32_t* move_cnt;          // [B]
+    int32_t* moves;             // [B][max_moves][2] = (dst row, src row)
+    int32_t max_moves;
+};
+
+__device__ __forceinline__ bool flag_at(const SelShared& sm, int p) { return (sm.flags[p >> 5] >> (p & 31)) & 1u; }
+
+__global__ __launch_bounds__(kSelThreads) void evict_plan_kernel(EvictArgs a) {
+    __shared__ SelShared sm;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int n = max(0, min(a.vis_len[b], a.max_vis));
+    const int len = max(0, min(a.kv_len[b], a.max_kv));
+    const int k = max(0, min(a.keep_count, n));
+    if (k >= n || a.sys_len + n > len) {                // nothing to evict (or inconsistent lengths)
+        if (tid == 0) a.move_cnt[b] = 0;
+        return;
+    }
+    float* scores = a.score_col + b * a.col_stride;
+    int32_t* ids = a.id_col + b * a.col_stride;
+    int32_t* mv = a.moves + (int64_t)b * a.max_moves * 2;
+    uint32_t thr = 0, thr_id = 0;
+    bool all_ties = true;
+    if (k > 0) mark_topk(scores, ids, n, k, true, sm, thr, thr_id, all_ties);
+    else {
+        for (int i = tid; i < n; i += kSelThreads) sm.keys[i] = 0;
+        __syncthreads();
+    }
+    // flags -> LDS bitmap (one 32-bit word per 32 positions, built by ballot halves)
+    const int n_pad = (n + kSelThreads - 1) / kSelThreads * kSelThreads;
+    for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
+        const int p = p0 + tid;
+        bool keep = false;
+        if (p < n && k > 0) keep = is_kept(sm.keys[p], ~(uint32_t)ids[p], thr, thr_id, all_ties);
+        unsigned long long bal = __ballot(keep);
+        if (tid % kWave == 0) {
+            sm.flags[(p >> 5)] = (uint32_t)bal;
+            sm.flags[(p >> 5) + 1] = (uint32_t)(bal >> 32);
+        }
+    }
+    __syncthreads();
+    const int g = n - k;                                // rows evicted
+    const int r = len - (a.sys_len + n);                // rows behind the visual segment
+    int m = 0;                                          // moves inside the visual segment
+    if (a.mode == ST3_HOLE_FILL) {
+        int base_h = 0, base_f = 0;
+        for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
+            const int p = p0 + tid;
+            const bool kept = p < n && flag_at(sm, p);
+            const bool hole = p < k && !kept;
+            const bool fill = p >= k && kept;
+            int packed = (hole ? 1 : 0) | (fill ? (1 << 16) : 0);
+            int incl = block_incl_scan(packed, sm);
+            if (hole) mv[2 * (base_h + (incl & 0xffff) - 1)] = a.sys_len + p;
+            if (fill) mv[2 * (base_f + (incl >> 16) - 1) + 1] = a.sys_len + p;
+            __syncthreads();
+            if (tid == kSelThreads - 1) sm.red = incl;
+            __syncthreads();
+            base_h += sm.red & 0xffff;
+            base_f += sm.red >> 16;
+        }
+        m = min(base_h, base_f);                        // equal when the ids are distinct
+        __syncthreads();                                // move list visible to the whole block
+        for (int i = tid; i < m; i += kSelThreads) {    // sources >= k, destinations < k: disjoint
+            int dst = mv[2 * i] - a.sys_len, src = mv[2 * i + 1] - a.sys_len;
+            scores[dst] = scores[src];
+            ids[dst] = ids[src];
+        }
+        const int cnt = min(g, r);
+        const int src0 = (r >= g) ? len - g : a.sys_len + n;
+        for (int j = tid; j < cnt; j += kSelThreads) {
+            mv[2 * (m + j)] = a.sys_len + k + j;
+            mv[2 * (m + j) + 1] = src0 + j;
+        }
+        if (tid == 0) a.move_cnt[b] = m + cnt;
+    } else {
+        // first hole = number of leading kept positions
+        int fh = n;
+        for (int p = tid; p < n; p += kSelThreads)
+            if (!flag_at(sm, p)) { fh = p; break; }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) fh = min(fh, __shfl_xor(fh, off));
+        if (tid % kWave == 0) sm.wave_tot[tid / kWave] = fh;
+        __syncthreads();
+        fh = min(min(sm.wave_tot[0], sm.wave_tot[1]), min(sm.wave_tot[2], sm.wave_tot[3]));
+        __syncthreads();
+        int base = 0;
+        for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
+            const int p = p0 + tid;
+            const bool kept = p < n && flag_at(sm, p);
+            float sv = 0.f; int32_t iv = 0;
+            if (kept) { sv = scores[p]; iv = ids[p]; }
+            int incl = block_incl_scan(kept ? 1 : 0, sm);       // contains barriers: loads precede stores
+            const int rank = base + incl - 1;
+            if (kept && p > fh) {
+                scores[rank] = sv; ids[rank] = iv;
+                mv[2 * (rank - fh)] = a.sys_len + rank;
+                mv[2 * (rank - fh) + 1] = a.sys_len + p;
+            }
+            __syncthreads();
+            if (tid == kSelThreads - 1) sm.red = incl;
+            __syncthreads();
+            base += sm.red;
+        }
+        m = k - fh;
+        for (int j = tid; j < r; j += kSelThreads) {
+            mv[2 * (m + j)] = a.sys_len + k + j;
+            mv[2 * (m + j) + 1] = a.sys_len + n + j;
+        }
+        if (tid == 0) a.move_cnt[b] = m + r;
+    }
+    if (tid == 0) { a.vis_len[b] = k; a.kv_len[b] = len - g; }
+}
+
+struct ApplyArgs {
+    char* k;
+    char* v;
+    int64_t stride_b, stride_h, stride_t;   // bytes
+    const int32_t* move_cnt;
+    const int32_t* moves;
+    int32_t max_moves, H, vecs_per_row;
+};
+
+// grid (2*H, B): x < H moves K rows of head x, x >= H moves V rows of head x-H.
+// Moves are applied in list order in chunks; a chunk is loaded completely before it is stored.
+// The plan kernel orders the list so that no move reads a row that an earlier chunk has written
+// unless that is the intended (already shifted) content.
+__global__ __launch_bounds__(256) void evict_apply_kernel(ApplyArgs a) {
+    constexpr int UR = 4;
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const int M = min(a.move_cnt[b], a.max_moves);
+    if (M <= 0) return;
+    const int h = blockIdx.x % a.H;
+    char* strip = (blockIdx.x < a.H ? a.k : a.v) + b * a.stride_b + h * a.stride_h;
+    const int32_t* mv = a.moves + (int64_t)b * a.max_moves * 2;
+    const int rpp = 256 / a.vecs_per_row;
+    const int rr = tid / a.vecs_per_row;
+    const int64_t cb = (int64_t)(tid % a.vecs_per_row) * 16;
+    for (int c0 = 0; c0 < M; c0 += UR * rpp) {
+        uint4 tmp[UR];
+        int dst[UR];
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            int i = c0 + u * rpp + rr;
+            dst[u] = -1;
+            if (i < M) {
+                dst[u] = mv[2 * i];
+                tmp[u] = *reinterpret_cast<const uint4*>(strip + mv[2 * i + 1] * a.stride_t + cb);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < UR; ++u)
+            if (dst[u] >= 0) *reinterpret_cast<uint4*>(strip + dst[u] * a.stride_t + cb) = tmp[u];
+        __syncthreads();
+    }
+}
+
+}  // namespace
+
+st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
+
+st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                                  float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
+                                  int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st) {
+    const int B = shape->batch, H = shape->heads, D = shape->head_dim;
+    if (seg->max_vis_len > kSelLdsKeys) return ST3_ERR_UNSUPPORTED;
+    WorkspaceLayout wl = workspace_layout(B, H, D, seg->max_kv_len, seg->max_vis_len, 0, 1);
+    if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
+    char* ws = reinterpret_cast<char*>(workspace);
+    EvictArgs ea{};
+    ea.score_col = score_col; ea.id_col = id_col; ea.col_stride = col_stride;
+    ea.vis_len = seg->vis_len; ea.kv_len = seg->kv_len;
+    ea.sys_len = seg->sys_len; ea.max_vis = seg->max_vis_len; ea.max_kv = seg->max_kv_len;
+    ea.keep_count = keep_count; ea.mode = mode;
+    ea.move_cnt = reinterpret_cast<int32_t*>(ws + wl.moves_cnt);
+    ea.moves = reinterpret_cast<int32_t*>(ws + wl.moves);
+    ea.max_moves = wl.max_moves;
+    evict_plan_kernel<<<B, kSelThreads, 0, st>>>(ea);
+    const int eb = elem_bytes(shape->dtype);
+    ApplyArgs aa{};
+    aa.k = reinterpret_cast<char*>(kv->k); aa.v = reinterpret_cast<char*>(kv->v);
+    aa.stride_b = kv->stride_b * eb; aa.stride_h = kv->stride_h * eb; aa.stride_t = kv->stride_t * eb;
+    aa.move_cnt = ea.move_cnt; aa.moves = ea.moves; aa.max_moves = wl.max_moves; aa.H = H;
+    aa.vecs_per_row = D * eb / 16;
+    evict_apply_kernel<<<dim3(2 * H, B), 256, 0, st>>>(aa);
+    return check_launch();
+}
+
+}  // namespace st3
+
+extern "C" st3_status st3_select_topk(const float* scores, int64_t score_stride, const int32_t* tie_ids,
+                                      int64_t id_stride, int32_t batch, const int32_t* n_dev, int32_t n, int32_t k,
+                                      uint8_t* keep_mask, int32_t* keep_idx, int64_t idx_stride, void* stream) {
+    if (!scores || batch <= 0 || n < 0 || k < 0 || k > n) return ST3_ERR_INVALID_ARG;
+    if (keep_idx && idx_stride < k) return ST3_ERR_INVALID_ARG;
+    if (n > 16384 || batch > 65535 * 32) return ST3_ERR_UNSUPPORTED;
+    if (score_stride < n || (tie_ids && id_stride < n)) return ST3_ERR_INVALID_ARG;
+    if (n == 0) return ST3_OK;
+    st3::TopkArgs a{};
+    a.scores = scores; a.score_stride = score_stride; a.ids = tie_ids; a.id_stride = id_stride;
+    a.n_dev = n_dev; a.n = n; a.k = k; a.mask = keep_mask; a.idx = keep_idx; a.idx_stride = idx_stride;
+    st3::select_topk_kernel<<<batch, st3::kSelThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(a);
+    return st3::check_launch();
+}
+
+extern "C" st3_status st3_compact_rows(void* rows, int32_t batch, int32_t inner, int64_t stride_b_bytes,
+                                       int64_t stride_inner_bytes, int64_t stride_row_bytes, int32_t row_bytes,
+                                       const int32_t* keep_idx, int64_t idx_stride, int32_t k, int32_t n,
+                                       int32_t tail_rows, void* stream) {
+    if (!rows || !keep_idx || batch <= 0 || inner <= 0 || k < 0 || n < 0 || k > n || tail_rows < 0)
+        return ST3_ERR_INVALID_ARG;
+    if (idx_stride < k) return ST3_ERR_INVALID_ARG;
+    if (row_bytes <= 0 || row_bytes % 4 || stride_row_bytes < row_bytes) return ST3_ERR_INVALID_ARG;
+    if (batch > 65535 || inner > 65535) return ST3_ERR_UNSUPPORTED;
+    if (k + tail_rows == 0) return ST3_OK;
+    const bool vec16 = (row_bytes % 16 == 0) && (stride_row_bytes % 16 == 0) && (stride_b_bytes % 16 == 0) &&
+                       (stride_inner_bytes % 16 == 0) && st3::aligned16(rows);
+    if (!vec16 && ((stride_row_bytes % 4) || (stride_b_bytes % 4) || (stride_inner_bytes % 4) ||
+                   (reinterpret_cast<uintptr_t>(rows) & 3)))
+        return ST3_ERR_INVALID_ARG;
+    st3::CompactArgs a{};
+    a.rows = reinterpret_cast<char*>(rows);
+    a.stride_b = stride_b_bytes; a.stride_inner = stride_inner_bytes; a.stride_row = stride_row_bytes;
+    a.unit_bytes = vec16 ? 16 : 4;
+    a.row_units = row_bytes / a.unit_bytes;
+    int slab = 1;
+    while (slab * 2 <= a.row_units && slab * 2 <= 256) slab *= 2;
+    a.slab_units = slab;
+    a.idx = keep_idx; a.idx_stride = idx_stride; a.k = k; a.n = n; a.tail = tail_rows;
+    dim3 grid((a.row_units + slab - 1) / slab, inner, batch);
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (vec16) st3::compact_rows_kernel<uint4><<<grid, 256, 0, st>>>(a);
+    else st3::compact_rows_kernel<uint32_t><<<grid, 256, 0, st>>>(a);
+    return st3::check_launch();
+}
+
+extern "C" st3_status st3_select_compact_layer(const st3_attn_shape* shape, const st3_kv_layer* kv,
+                                               const st3_segments* seg, float* score_col, int32_t* id_col,
+                                               int64_t col_stride, int32_t keep_count, int32_t mode,
+                                               void* workspace, size_t workspace_bytes, void* stream) {
+    st3_status s = st3::check_shape(shape);
+    if (s != ST3_OK) return s;
+    s = st3::validate_kv(shape, kv, seg);
+    if (s != ST3_OK) return s;
+    if (!score_col || !id_col || !workspace || keep_count < 0) return ST3_ERR_INVALID_ARG;
+    if (col_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
+    if (mode != ST3_STABLE && mode != ST3_HOLE_FILL) return ST3_ERR_INVALID_ARG;
+    if (!st3::aligned16(workspace)) return ST3_ERR_INVALID_ARG;
+    return st3::enqueue_select_compact(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, workspace,
+                                       workspace_bytes, reinterpret_cast<hipStream_t>(stream));
+}

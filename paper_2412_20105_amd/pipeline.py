@@ -1,0 +1,164 @@
+"""Call sequencing of Alg. 3 (PVTP at prefill, VTA at decode) over the C-ABI.
+
+This module owns torch buffers (KV caches, score/id columns, lengths, workspace)
+and issues the library calls in the paper's order.  It computes nothing itself:
+attention, mass, ranking, compaction, eviction and append all run in libst3's
+kernels; the only torch operations are allocations and device-to-device copies
+that place a layer's inputs where the kernels expect them.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as st3
+
+
+def keep_table_for(workload) -> List[List[int]]:
+    """keep[l][t] from a workload's schedule parameters, via the library's host helpers."""
+    ls, ss = workload.layer_schedule, workload.step_schedule
+    L, nv, T = workload.layers, workload.n_vis, workload.steps
+    if ls["kind"] == "table":
+        keep0 = list(ls["keep"])
+    elif ls["kind"] == "linear":
+        keep0 = st3.st3_schedule_linear(L, nv, ls["last_full_layer"], ls["end_ratio_bp"])
+    elif ls["kind"] == "pvtp":
+        keep0 = st3.st3_schedule_pvtp(L, nv, 3, ls["S"], ls["P_bp"], ls["R_bp"])
+    elif ls["kind"] == "full":
+        keep0 = [nv] * L
+    else:
+        raise ValueError(ls["kind"])
+    kinds = {"cos": (st3.ST3_ANNEAL_COS, "tau"), "linear": (st3.ST3_ANNEAL_LINEAR, "tau"),
+             "exp": (st3.ST3_ANNEAL_EXP, "sigma"), "drop": (st3.ST3_ANNEAL_DROP, "per_step"),
+             "none": (st3.ST3_ANNEAL_NONE, None)}
+    kind, pname = kinds[ss["kind"]]
+    return st3.st3_schedule_anneal(kind, ss[pname] if pname else 1.0, T, keep0)
+
+
+class LayerCache:
+    def __init__(self, B, H, d, cap, cap_v, dtype, device):
+        self.k = torch.empty((B, H, cap, d), dtype=dtype, device=device)
+        self.v = torch.empty((B, H, cap, d), dtype=dtype, device=device)
+        self.score = torch.zeros((B, max(cap_v, 1)), dtype=torch.float32, device=device)
+        self.ids = torch.zeros((B, max(cap_v, 1)), dtype=torch.int32, device=device)
+        self.mass = torch.zeros((B, max(cap_v, 1)), dtype=torch.float32, device=device)
+        self.vis_len = torch.zeros((B,), dtype=torch.int32, device=device)
+        self.kv_len = torch.zeros((B,), dtype=torch.int32, device=device)
+        self.kv = st3.kv_layer(self.k, self.v)
+        # host-side bounds (exact here, since every sequence follows the same table)
+        self.h_vis = 0
+        self.h_kv = 0
+
+
+class Generation:
+    """One batch of sequences going through prefill and decode steps.
+
+    keep: table keep[l][t] (t = 0 .. steps).  mode: "static" ranks by the column
+    fixed at prefill, "current" by the layer's latest decode mass.
+    """
+
+    def __init__(self, layers: int, heads: int, head_dim: int, dtype: torch.dtype, batch: int,
+                 n_sys: int, n_vis: int, n_txt: int, steps: int, keep: Sequence[Sequence[int]],
+                 window: int = 1, mode: str = "static", compact_mode: int = st3.ST3_HOLE_FILL,
+                 device: str = "cuda:0"):
+        self.L, self.H, self.d, self.B = layers, heads, head_dim, batch
+        self.n_sys, self.n_vis, self.n_txt, self.T = n_sys, n_vis, n_txt, steps
+        self.keep = [list(r) for r in keep]
+        self.window, self.mode, self.compact_mode = window, mode, compact_mode
+        self.dtype, self.device = dtype, device
+        self.shape = st3.make_shape(batch, heads, head_dim, st3._dtype_code(torch.empty(0, dtype=dtype)))
+        self.N0 = n_sys + n_vis + n_txt
+        self.layers: List[LayerCache] = []
+        for l in range(layers):
+            cap = n_sys + self.keep[l][0] + n_txt + steps
+            cap = max(cap, self.N0)                 # the unpruned prompt is staged in the cache first
+            self.layers.append(LayerCache(batch, heads, head_dim, cap, n_vis, dtype, device))
+        ws_bytes = st3.st3_workspace_bytes(self.shape, self.N0 + steps, n_vis, self.N0, window)
+        self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
+        self.q_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
+        self.out_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
+        self.dec_out = torch.empty((batch, heads, head_dim), dtype=dtype, device=device)
+        self.keep_idx = torch.empty((batch, max(n_vis, 1)), dtype=torch.int32, device=device)
+        self._alive = n_vis                 # visual tokens alive in the layer being prefetched
+        self._inherit: Optional[torch.Tensor] = None
+        self.t = 0
+        eb = 2 if dtype == torch.bfloat16 else 4
+        self._eb = eb
+
+    # ------------------------------------------------------------------------------------
+    def _compact_strips(self, t: torch.Tensor, idx: torch.Tensor, k: int, n: int, tail: int):
+        """Stable gather of rows [n_sys, n_sys+n) of a [B,H,rows,d] tensor by idx, then the tail."""
+        eb = self._eb
+        base = t.data_ptr() + self.n_sys * t.stride(2) * eb
+        st3.st3_compact_rows(base, self.B, self.H, t.stride(0) * eb, t.stride(1) * eb, t.stride(2) * eb,
+                             self.d * eb, idx, k, n, tail)
+
+    def _compact_column(self, col: torch.Tensor, idx: torch.Tensor, k: int, n: int):
+        st3.st3_compact_rows(col.data_ptr(), self.B, 1, col.stride(0) * 4, 0, 4, 4, idx, k, n, 0)
+
+    def prefill_layer(self, l: int, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor):
+        """Q, K, V: device tensors [B,H,N0,d] over the unpruned prompt (Alg. 3, PVTP branch).
+
+        Returns (out view [B,H,n_l,d], mass view [B,keep_l]).
+        """
+        lc = self.layers[l]
+        B, ns, nv, nx = self.B, self.n_sys, self.n_vis, self.n_txt
+        k_l = self.keep[l][0]
+        if l == 0:
+            self._alive = nv
+            lc.ids[:, :nv] = torch.arange(nv, dtype=torch.int32, device=self.device)
+        else:
+            prev = self.layers[l - 1]
+            lc.ids.copy_(prev.ids)
+            if k_l < self._alive:
+                # Eq. 3: keep the k_l visual tokens the PREVIOUS layer's last row attended to most
+                st3.st3_select_topk(prev.mass, prev.ids, None, self._alive, k_l, None, self.keep_idx)
+                self._compact_column(lc.ids, self.keep_idx, k_l, self._alive)
+                if self._inherit is None:
+                    self._inherit = torch.empty_like(prev.mass)
+                self._inherit.copy_(prev.mass)
+                self._compact_column(self._inherit, self.keep_idx, k_l, self._alive)
+                self._alive = k_l
+        alive = self._alive
+        n_l = ns + alive + nx
+        # stage the layer's inputs: K and V straight into the cache, Q into scratch
+        lc.k[:, :, :self.N0].copy_(K)
+        lc.v[:, :, :self.N0].copy_(V)
+        self.q_stage.copy_(Q)
+        if alive < nv:
+            # Alg. 1/3: X = [S, V[T], I]; ids are ascending original positions of the survivors
+            for t in (lc.k, lc.v, self.q_stage):
+                self._compact_strips(t, lc.ids, alive, nv, nx)
+        out = self.out_stage[:, :, :n_l]
+        st3.st3_prefill_attention(self.shape, self.q_stage[:, :, :n_l], lc.k[:, :, :n_l], lc.v[:, :, :n_l],
+                                  n_l, ns, alive, self.window, out, lc.mass, self.ws)
+        # ranking column: scores of the most recent prune event, else the layer's own mass
+        lc.score.copy_(lc.mass if self._inherit is None else self._inherit)
+        lc.vis_len.fill_(alive)
+        lc.kv_len.fill_(n_l)
+        lc.h_vis, lc.h_kv = alive, n_l
+        return out, lc.mass[:, :alive]
+
+    # ------------------------------------------------------------------------------------
+    def decode_layer(self, l: int, t: int, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor):
+        """q, k_new, v_new: device [B,H,d].  Alg. 3, VTA branch, layer l of step t >= 1.
+
+        Returns (out [B,H,d] (reused buffer), mass view [B, keep[l][t]]).
+        """
+        lc = self.layers[l]
+        target = min(self.keep[l][t], lc.h_vis)
+        keep_count = target if target < lc.h_vis else -1
+        seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len)
+        mass_dst = lc.score if self.mode == "current" else lc.mass
+        st3.st3_decode_layer_step(self.shape, lc.kv, seg, lc.score, lc.ids, keep_count, self.compact_mode,
+                                  q, k_new, v_new, self.dec_out, mass_dst, self.ws)
+        lc.h_kv = lc.h_kv - (lc.h_vis - target) + 1
+        lc.h_vis = target
+        return self.dec_out, mass_dst[:, :target]
+
+    def kv_lens(self) -> List[int]:
+        return [lc.h_kv for lc in self.layers]
+
+    def kv_bytes(self) -> int:
+        return st3.st3_kv_bytes(self.B, self.H, self.d, self.shape.dtype, self.kv_lens())

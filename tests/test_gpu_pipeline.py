@@ -1,0 +1,142 @@
+"""End-to-end parity of the Alg. 3 call sequence (prefill with PVTP, decode with VTA) against
+the CPU oracle, on the tiny workload in full and on cut-down versions of the large ones."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import (DEV, TORCH_DTYPE, assert_attention_close, assert_mass_close, assert_selection_matches, to_dev,
+                      to_np64)
+from oracle import st3_oracle as orc
+from paper_2412_20105_amd import binding as st3
+from paper_2412_20105_amd import pipeline
+from workloads import decode_qkv, get_workload, prefill_qkv
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None):
+    T = w.steps if steps is None else steps
+    keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
+    keep_np = np.array(keep)
+    assert np.array_equal(keep_np, orc.schedule_for(w)[:, :T + 1])
+    gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt,
+                              T, keep, window=window, mode=mode, compact_mode=compact_mode, device=DEV)
+    ref = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, keep_np, window=window, mode=mode)
+    pre = [prefill_qkv(w, l, B) for l in range(w.layers)]
+    r = ref.prefill(lambda l: pre[l])
+    diverged = np.zeros((w.layers, B), bool)      # a near-tie was resolved differently: values no longer comparable
+    near_ties = 0
+
+    def check_sets(l, b, prev_scores, prev_ids, k, what):
+        nonlocal near_ties
+        lc = gen.layers[l]
+        ids = lc.ids[b, :lc.h_vis].cpu().numpy()
+        assert lc.h_vis == k
+        if prev_scores is None:
+            assert sorted(ids.tolist()) == list(range(w.n_vis))
+            return
+        same = assert_selection_matches(ids, prev_scores, prev_ids, k, what)
+        if not same:
+            near_ties += 1
+            diverged[l:, b] = True
+
+    for l in range(w.layers):
+        print(f"{w.name} prefill layer {l}", flush=True)
+        q, k, v = (to_dev(x, w.dtype) for x in pre[l])
+        out, mass = gen.prefill_layer(l, q, k, v)
+        torch.cuda.synchronize()
+        got_o, got_m = to_np64(out), to_np64(mass)
+        lc = gen.layers[l]
+        for b in range(B):
+            if l == 0:
+                check_sets(l, b, None, None, keep[l][0], "")
+            elif not diverged[l - 1, b]:
+                check_sets(l, b, r["mass"][l - 1][b], r["ids"][l - 1][b], keep[l][0], f"prefill l={l} b={b}")
+            if diverged[l, b]:
+                continue
+            # prefill storage is order preserving: ids ascending
+            assert np.array_equal(lc.ids[b, :lc.h_vis].cpu().numpy(), r["ids"][l][b])
+            assert_attention_close(got_o[b], r["out"][l][b], w.dtype, f"prefill out l={l} b={b}")
+            assert_mass_close(got_m[b], r["mass"][l][b], f"prefill mass l={l} b={b}")
+            assert_mass_close(lc.score[b, :lc.h_vis].double().cpu().numpy(), ref.rho[l][b], f"rho l={l} b={b}")
+    for t in range(1, T + 1):
+        if t % 16 == 1:
+            print(f"{w.name} decode step {t}", flush=True)
+        dec = [decode_qkv(w, l, t, B) for l in range(w.layers)]
+        rho_before = [[x.copy() for x in ref.rho[l]] for l in range(w.layers)]
+        ids_before = [[x.copy() for x in ref.ids[l]] for l in range(w.layers)]
+        s = ref.decode_step(lambda l: dec[l])
+        for l in range(w.layers):
+            q, k, v = (to_dev(x, w.dtype) for x in dec[l])
+            out, mass = gen.decode_layer(l, t, q, k, v)
+            torch.cuda.synchronize()
+            got_o, got_m = to_np64(out), to_np64(mass)
+            lc = gen.layers[l]
+            assert lc.vis_len.cpu().tolist() == [keep[l][t]] * B
+            assert lc.kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, keep[l][t], w.n_txt, t)] * B
+            assert lc.h_kv == s["kv_len"][l][0]
+            for b in range(B):
+                if diverged[l, b]:
+                    continue
+                check_sets(l, b, rho_before[l][b], ids_before[l][b], keep[l][t], f"t={t} l={l} b={b}")
+                if diverged[l, b]:
+                    continue
+                assert_attention_close(got_o[b], s["out"][l][b], w.dtype, f"decode out t={t} l={l} b={b}")
+                # mass comes back in cache order; map through the id column
+                ids = lc.ids[b, :lc.h_vis].cpu().numpy()
+                pos = np.searchsorted(s["ids"][l][b], ids)
+                assert_mass_close(got_m[b], s["mass"][l][b][pos], f"decode mass t={t} l={l} b={b}")
+    # KV bytes actually held == closed form
+    assert gen.kv_bytes() == orc.kv_bytes(B, w.heads, w.head_dim, 2 if w.dtype == "bf16" else 4, ref.cache_lens())
+    return near_ties, diverged
+
+
+@pytest.mark.parametrize("mode", ["static", "current"])
+@pytest.mark.parametrize("compact_mode", [st3.ST3_HOLE_FILL, st3.ST3_STABLE])
+def test_tiny_workload_full(mode, compact_mode):
+    w = get_workload("tiny")
+    near, div = _run_and_compare(w, 1, mode=mode, compact_mode=compact_mode)
+    assert not div.any(), "tiny workload resolved a near-tie differently from the oracle"
+
+
+def test_tiny_workload_batched_window():
+    w = get_workload("tiny")
+    _run_and_compare(w, 3, window=2)
+
+
+def test_13b_shape_cut_down():
+    """Head dim, token counts and schedule form of the 13B workload; fewer layers, heads, steps."""
+    w = dataclasses.replace(get_workload("llava15_13b"), layers=6, heads=8, steps=12,
+                            step_schedule={"kind": "cos", "tau": 12})
+    near, div = _run_and_compare(w, 2)
+    assert div.mean() < 0.5
+
+
+def test_7b_shape_cut_down_stable_compaction():
+    w = dataclasses.replace(get_workload("llava15_7b"), layers=5, heads=4, steps=6,
+                            step_schedule={"kind": "linear", "tau": 8})
+    _run_and_compare(w, 1, compact_mode=st3.ST3_STABLE)
+
+
+def test_highres_shape_cut_down():
+    w = dataclasses.replace(get_workload("llava_next_hr"), layers=4, heads=2, steps=3,
+                            step_schedule={"kind": "cos", "tau": 3})
+    _run_and_compare(w, 1)
+
+
+def test_skewed_workload_ties():
+    """Planted exact ties (lowest id must win) and one-ulp near-ties (tolerance rule)."""
+    w = dataclasses.replace(get_workload("skewed_13b"), layers=5, heads=4, steps=6,
+                            step_schedule={"kind": "cos", "tau": 8})
+    near, div = _run_and_compare(w, 2)
+    print(f"skewed: {near} selections resolved a near-tie differently", flush=True)
+
+
+def test_pvtp_stride_schedule_with_exp_annealing():
+    """The paper's own 13B setting (S=4, R=5%, P=50%) on a cut-down model, exponential decay."""
+    w = dataclasses.replace(get_workload("llava15_13b"), layers=12, heads=4, steps=5, n_vis=200, n_txt=20,
+                            layer_schedule={"kind": "pvtp", "S": 4, "P_bp": 5000, "R_bp": 500},
+                            step_schedule={"kind": "exp", "sigma": 3})
+    _run_and_compare(w, 1)
