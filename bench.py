@@ -57,7 +57,7 @@ class Job:
         self.pre = [tuple(randn(shape_p) for _ in range(3)) for _ in range(w.layers)]
         self.dec = [randn(shape_d) for _ in range(T)]
         self.gen = pipeline.Generation(w.layers, w.heads, w.head_dim, dt, B, w.n_sys, w.n_vis, w.n_txt, T, keep,
-                                       device=dev)
+                                       defer_mass=True, device=dev)
 
     def run(self):
         gen, w = self.gen, self.w
@@ -69,6 +69,8 @@ class Job:
             d = self.dec[t - 1]
             for l in range(w.layers):
                 gen.decode_layer(l, t, d[l, 0], d[l, 1], d[l, 2])
+        for l in range(w.layers):           # the last step's masses are still pending
+            gen.finalize_mass(l)
 
     def run_prefill_only(self):
         gen, w = self.gen, self.w

@@ -92,10 +92,20 @@ ST3_EXPORT const char* st3_status_string(st3_status s);
 ST3_EXPORT int st3_last_hip_error(void);
 ST3_EXPORT uint32_t st3_version(void);                 /* major<<16 | minor<<8 | patch */
 
-/* Bytes of DEVICE workspace that any call below needs for the given bounds (256-byte aligned
- * base expected).  max_q_len is the longest prefill sequence, score_window the largest W. */
-ST3_EXPORT size_t st3_workspace_bytes(const st3_attn_shape* shape, int32_t max_kv_len, int32_t max_vis_len,
-                           int32_t max_q_len, int32_t score_window);
+/* Bytes of DEVICE workspace (256-byte aligned base expected) that any call below needs for a
+ * layer whose cache has `kv_capacity` rows per (b,h), prefill sequences with at most max_vis_len
+ * visual tokens and a score window of at most `score_window` rows.  The decode-path calls lay the
+ * workspace out from the cache capacity alone; a layer that defers its visual mass
+ * (st3_decode_layer_step with defer_mass) must keep a workspace of its own between steps. */
+ST3_EXPORT size_t st3_workspace_bytes(const st3_attn_shape* shape, int32_t kv_capacity, int32_t max_vis_len,
+                                      int32_t score_window);
+
+/* Prepares a workspace for the decode-path calls: clears the per-sequence "mass pending"
+ * descriptors (a few integers) with a small kernel on `stream`.  Required once before the first
+ * st3_decode_layer_step / st3_select_compact_layer on a workspace that was not zero-filled.
+ * Prefill scratch lives at the end of the workspace and never overlaps those descriptors. */
+ST3_EXPORT st3_status st3_workspace_init(const st3_attn_shape* shape, int32_t kv_capacity, void* workspace,
+                                         size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Prefill attention with visual-mass output (Eq. 2; score extraction of Sec. 3.2).
@@ -126,9 +136,10 @@ ST3_EXPORT st3_status st3_kv_append(const st3_attn_shape* shape, const st3_kv_la
  *   out[b,h,:]   = sum_{j<kv_len[b]} p_j v_j,  p = softmax over the kv_len[b] cached keys
  *   vis_mass[b,j] = (1/H) sum_h p_h[sys_len + j],  j in [0, vis_len[b])
  * q, out: DEVICE contiguous [B,H,d].  vis_mass: DEVICE float32 with row stride `mass_stride`
- * (>= max_vis_len) or NULL; entries j >= vis_len[b] are left untouched.  Split-KV: the cache is
- * read once, in chunks handled by different workgroups whose partial results are merged by a
- * second kernel; the merge order is fixed, so results are reproducible run to run.
+ * (>= max_vis_len) or NULL; entries j >= vis_len[b] are left untouched.  The cache is read once;
+ * when B*H alone does not fill the chip each (b,h) strip is cut into chunks handled by different
+ * workgroups whose partial results a second kernel merges in a fixed order, so results are
+ * reproducible run to run.
  * A sequence with kv_len[b] == 0 gets out = 0.
  * ------------------------------------------------------------------------------------------- */
 ST3_EXPORT st3_status st3_decode_attention(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
@@ -187,17 +198,34 @@ ST3_EXPORT st3_status st3_select_compact_layer(const st3_attn_shape* shape, cons
 
 /* ---------------------------------------------------------------------------------------------
  * One layer of one decode step, in the order of Alg. 3's VTA branch:
- *   (1) select-and-compact to keep_count (skipped when keep_count < 0),
+ *   (1) select-and-compact to keep_count (no eviction when keep_count < 0),
  *   (2) append k_new/v_new,
  *   (3) decode attention of q over the resulting cache, with visual mass.
- * Same arguments as the three calls it replaces.  max_* in `seg` bound the lengths before the
- * call; host check: max_kv_len < capacity.
+ * Two kernels: one workgroup per sequence does (1), moving the few evicted rows itself, and bumps
+ * kv_len; the attention kernel reads the new token's row from k_new/v_new and stores it into
+ * the cache while streaming K and V once.  max_* in `seg` bound the lengths before the call;
+ * host check: max_kv_len < capacity.
+ * vis_mass (may be NULL: no mass) and defer_mass:
+ *   defer_mass == 0: vis_mass holds this call's mass once the stream is synchronised.
+ *   defer_mass != 0: the head reduction of this call's mass is postponed: the logits stay in
+ *     `workspace`, and the NEXT st3_decode_layer_step on the same workspace (or
+ *     st3_decode_mass_finalize) writes the finished mass to the vis_mass it is given, before it
+ *     ranks anything.  This saves one launch per layer and step; with vis_mass == score_col the
+ *     next step then ranks by the latest mass.  The workspace must not be used for another layer
+ *     in between.
  * ------------------------------------------------------------------------------------------- */
-ST3_EXPORT st3_status st3_decode_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
-                                 float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
-                                 int32_t mode, const void* q, const void* k_new, const void* v_new,
-                                 void* out, float* vis_mass, int64_t mass_stride,
-                                 void* workspace, size_t workspace_bytes, void* stream);
+ST3_EXPORT st3_status st3_decode_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv,
+                                            const st3_segments* seg, float* score_col, int32_t* id_col,
+                                            int64_t col_stride, int32_t keep_count, int32_t mode, const void* q,
+                                            const void* k_new, const void* v_new, void* out, float* vis_mass,
+                                            int64_t mass_stride, int32_t defer_mass, void* workspace,
+                                            size_t workspace_bytes, void* stream);
+
+/* Finishes a visual mass that st3_decode_layer_step left pending in `workspace` (no effect when
+ * none is pending).  `seg` must describe the cache as that call left it. */
+ST3_EXPORT st3_status st3_decode_mass_finalize(const st3_attn_shape* shape, const st3_kv_layer* kv,
+                                               const st3_segments* seg, float* vis_mass, int64_t mass_stride,
+                                               void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Retention schedules: HOST-only pure functions that fill integer tables.

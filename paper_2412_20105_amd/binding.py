@@ -25,9 +25,9 @@ ST3_STABLE, ST3_HOLE_FILL = 0, 1
 ST3_ANNEAL_COS, ST3_ANNEAL_LINEAR, ST3_ANNEAL_EXP, ST3_ANNEAL_DROP, ST3_ANNEAL_NONE = 0, 1, 2, 3, 4
 
 EXPORTED = [
-    "st3_status_string", "st3_last_hip_error", "st3_version", "st3_workspace_bytes",
+    "st3_status_string", "st3_last_hip_error", "st3_version", "st3_workspace_bytes", "st3_workspace_init",
     "st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_select_topk",
-    "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step",
+    "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_mass_finalize",
     "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
     "st3_debug_set_prefill_path", "st3_profile_enable", "st3_profile_read",
 ]
@@ -78,8 +78,10 @@ def lib() -> C.CDLL:
         L.st3_last_hip_error.restype = C.c_int
         L.st3_version.restype = C.c_uint32
         L.st3_workspace_bytes.restype = C.c_size_t
-        L.st3_workspace_bytes.argtypes = [C.POINTER(AttnShape), C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        L.st3_workspace_bytes.argtypes = [C.POINTER(AttnShape), C.c_int32, C.c_int32, C.c_int32]
         P = C.POINTER
+        L.st3_workspace_init.argtypes = [P(AttnShape), C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.st3_workspace_init.restype = C.c_int
         L.st3_prefill_attention.argtypes = [P(AttnShape), P(Tensor4), P(Tensor4), P(Tensor4), C.c_int32, C.c_int32,
                                             C.c_int32, C.c_int32, P(Tensor4), C.c_void_p, C.c_int64, C.c_void_p,
                                             C.c_size_t, C.c_void_p]
@@ -94,7 +96,9 @@ def lib() -> C.CDLL:
                                                C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         L.st3_decode_layer_step.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_void_p, C.c_int64,
                                             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+                                            C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.st3_decode_mass_finalize.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_int64,
+                                               C.c_void_p, C.c_size_t, C.c_void_p]
         L.st3_schedule_pvtp.argtypes = [C.c_int32] * 6 + [C.c_void_p]
         L.st3_schedule_linear.argtypes = [C.c_int32] * 4 + [C.c_void_p]
         L.st3_schedule_anneal.argtypes = [C.c_int32, C.c_double, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
@@ -102,7 +106,7 @@ def lib() -> C.CDLL:
         L.st3_kv_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32]
         for name in ("st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_select_topk",
                      "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step",
-                     "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal"):
+                     "st3_decode_mass_finalize", "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal"):
             getattr(L, name).restype = C.c_int
         L.st3_profile_enable.argtypes = [C.c_int32]
         L.st3_profile_enable.restype = C.c_int
@@ -174,8 +178,14 @@ def st3_version() -> int:
     return lib().st3_version()
 
 
-def st3_workspace_bytes(shape: AttnShape, max_kv_len: int, max_vis_len: int, max_q_len: int, score_window: int = 1) -> int:
-    return lib().st3_workspace_bytes(C.byref(shape), max_kv_len, max_vis_len, max_q_len, score_window)
+def st3_workspace_bytes(shape: AttnShape, kv_capacity: int, max_vis_len: int, score_window: int = 1) -> int:
+    return lib().st3_workspace_bytes(C.byref(shape), kv_capacity, max_vis_len, score_window)
+
+
+def st3_workspace_init(shape: AttnShape, kv_capacity: int, workspace, stream=None) -> None:
+    _check(lib().st3_workspace_init(C.byref(shape), kv_capacity, workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)),
+           "st3_workspace_init")
 
 
 def st3_prefill_attention(shape, q, k, v, n, sys_len, vis_len, score_window, out, vis_mass, workspace, stream=None):
@@ -226,14 +236,22 @@ def st3_select_compact_layer(shape, kv: KvLayer, seg: Segments, score_col, id_co
 
 
 def st3_decode_layer_step(shape, kv: KvLayer, seg: Segments, score_col, id_col, keep_count, mode, q, k_new, v_new,
-                          out, vis_mass, workspace, stream=None):
+                          out, vis_mass, workspace, defer_mass=False, stream=None):
     ms = 0 if vis_mass is None else vis_mass.stride(0)
     cs = 0 if score_col is None else score_col.stride(0)
     _check(lib().st3_decode_layer_step(C.byref(shape), C.byref(kv), C.byref(seg), _ptr(score_col), _ptr(id_col), cs,
                                        keep_count, mode, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
-                                       out.data_ptr(), _ptr(vis_mass), ms, workspace.data_ptr(),
-                                       workspace.numel() * workspace.element_size(), _stream(stream)),
+                                       out.data_ptr(), _ptr(vis_mass), ms, 1 if defer_mass else 0,
+                                       workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                       _stream(stream)),
            "st3_decode_layer_step")
+
+
+def st3_decode_mass_finalize(shape, kv: KvLayer, seg: Segments, vis_mass, workspace, stream=None):
+    _check(lib().st3_decode_mass_finalize(C.byref(shape), C.byref(kv), C.byref(seg), vis_mass.data_ptr(),
+                                          vis_mass.stride(0), workspace.data_ptr(),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)),
+           "st3_decode_mass_finalize")
 
 
 # -- host-only schedule helpers ---------------------------------------------------------------

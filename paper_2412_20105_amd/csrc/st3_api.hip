@@ -30,13 +30,13 @@ void profile_mark(hipStream_t st, bool after) {
 
 st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
 st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
-                          const st3_segments* seg, int32_t max_kv_len, void* out, float* vis_mass,
-                          int64_t mass_stride, void* workspace, size_t workspace_bytes, hipStream_t st);
-st3_status enqueue_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
-                          const void* k_new, const void* v_new, hipStream_t st);
+                          const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
+                          void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
+                          void* workspace, size_t workspace_bytes, hipStream_t st);
 st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                                   float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
-                                  int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st);
+                                  int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st,
+                                  int do_append, float* mass_dst, int64_t mass_stride);
 
 }  // namespace st3
 
@@ -54,23 +54,45 @@ extern "C" const char* st3_status_string(st3_status s) {
 extern "C" int st3_last_hip_error(void) { return st3::g_last_hip_error; }
 extern "C" uint32_t st3_version(void) { return (0u << 16) | (1u << 8) | 0u; }
 
-extern "C" size_t st3_workspace_bytes(const st3_attn_shape* shape, int32_t max_kv_len, int32_t max_vis_len,
-                                      int32_t max_q_len, int32_t score_window) {
+extern "C" size_t st3_workspace_bytes(const st3_attn_shape* shape, int32_t kv_capacity, int32_t max_vis_len,
+                                      int32_t score_window) {
     if (st3::check_shape(shape) != ST3_OK) return 0;
-    if (max_kv_len < 0 || max_vis_len < 0 || max_q_len < 0) return 0;
+    if (kv_capacity < 0 || max_vis_len < 0) return 0;
     if (score_window < 1) score_window = 1;
     if (score_window > st3::kMaxWindow) score_window = st3::kMaxWindow;
-    // the fused step appends before attending, so its split count is taken at max_kv_len + 1
-    return st3::workspace_layout(shape->batch, shape->heads, shape->head_dim, max_kv_len + 1, max_vis_len,
-                                 max_q_len, score_window).total;
+    // decode region first, prefill scratch behind it: prefill never touches the pending-mass descriptors
+    const size_t d = st3::decode_ws(shape->batch, shape->heads, shape->head_dim, kv_capacity).total;
+    const size_t p = st3::prefill_ws(shape->batch, shape->heads, max_vis_len, score_window).total;
+    return d + p;
+}
+
+namespace st3 {
+__global__ void zero_i32_kernel(int32_t* p, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+}  // namespace st3
+
+extern "C" st3_status st3_workspace_init(const st3_attn_shape* shape, int32_t kv_capacity, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+    using namespace st3;
+    st3_status s = check_shape(shape);
+    if (s != ST3_OK) return s;
+    if (!workspace || !aligned16(workspace) || kv_capacity <= 0) return ST3_ERR_INVALID_ARG;
+    const DecodeWs wl = decode_ws(shape->batch, shape->heads, shape->head_dim, kv_capacity);
+    if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
+    const int n = shape->batch * 4;
+    zero_i32_kernel<<<(n + 255) / 256, 256, 0, reinterpret_cast<hipStream_t>(stream)>>>(
+        reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + wl.pending), n);
+    return check_launch();
 }
 
 extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv,
                                             const st3_segments* seg, float* score_col, int32_t* id_col,
                                             int64_t col_stride, int32_t keep_count, int32_t mode, const void* q,
                                             const void* k_new, const void* v_new, void* out, float* vis_mass,
-                                            int64_t mass_stride, void* workspace, size_t workspace_bytes,
-                                            void* stream) {
+                                            int64_t mass_stride, int32_t defer_mass, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
     using namespace st3;
     st3_status s = check_shape(shape);
     if (s != ST3_OK) return s;
@@ -86,19 +108,17 @@ extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
         if (mode != ST3_STABLE && mode != ST3_HOLE_FILL) return ST3_ERR_INVALID_ARG;
     }
     // all size checks before the first launch, so that an error enqueues nothing
-    WorkspaceLayout wl = workspace_layout(shape->batch, shape->heads, shape->head_dim, seg->max_kv_len + 1,
-                                          seg->max_vis_len, 0, 1);
+    const DecodeWs wl = decode_ws(shape->batch, shape->heads, shape->head_dim, kv->capacity);
     if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (keep_count >= 0) {
-        s = enqueue_select_compact(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, workspace,
-                                   workspace_bytes, st);
-        if (s != ST3_OK) return s;
-    }
-    s = enqueue_append(shape, kv, seg, k_new, v_new, st);
+    // (1) one workgroup per sequence: finish a mass left pending by the previous step, rank, evict
+    //     (rows moved in place), kv_len += 1 for the new token.  Runs even when nothing is evicted.
+    s = enqueue_select_compact(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, workspace,
+                               workspace_bytes, st, 1, vis_mass, mass_stride);
     if (s != ST3_OK) return s;
-    return enqueue_decode(shape, q, kv, seg, seg->max_kv_len + 1, out, vis_mass, mass_stride, workspace,
-                          workspace_bytes, st);
+    // (2) attention over the cache; the appended row is read from k_new/v_new and stored on the way
+    return enqueue_decode(shape, q, kv, seg, seg->max_kv_len + 1, k_new, v_new, out, vis_mass, mass_stride,
+                          vis_mass != nullptr, defer_mass != 0, workspace, workspace_bytes, st);
 }
 
 extern "C" st3_status st3_profile_enable(int32_t max_launches) {

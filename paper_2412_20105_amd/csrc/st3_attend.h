@@ -35,32 +35,34 @@ struct WaveState {
     float acc[EPL];
 };
 
-// Streams rows [r0, r1) (r0 < r1).  kbase/vbase point at row 0 of this (b,h) strip.
-// logit_out (may be null): float array indexed by (row - vis_lo) for rows in [vis_lo, vis_hi),
-// receives the scaled logit in the log2 domain.
+// Streams the tiles of U*RPL rows that start at r0, r0+step, r0+2*step, ... below r1; within a
+// tile only rows < r1 count.  `safe_row` is any row of the strip that may be read (lanes whose
+// row falls outside load it instead and are masked).  kbase/vbase point at row 0 of the (b,h)
+// strip.  logit_out (may be null): float array indexed by (row - vis_lo) for rows in
+// [vis_lo, vis_hi), receives the scaled logit in the log2 domain.
 template <typename T, int D, int U>
 __device__ __forceinline__ void wave_attend(const float* qf, const T* kbase, const T* vbase, int64_t stride_t,
-                                            int r0, int r1, float scale_l2, int lane,
+                                            int r0, int r1, int step, int safe_row, float scale_l2, int lane,
                                             WaveState<RowMap<T, D>::EPL>& st,
                                             float* logit_out, int vis_lo, int vis_hi) {
     using M = RowMap<T, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, RPL = M::RPL;
     const int grp = lane / LPR;
     const int64_t col = (int64_t)(lane % LPR) * EPL;
-    for (int t0 = r0; t0 < r1; t0 += U * RPL) {
+    for (int t0 = r0; t0 < r1; t0 += step) {
         uint4 kr[U], vr[U];
         bool ok[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int row = t0 + u * RPL + grp;
             ok[u] = row < r1;
-            int64_t off = (int64_t)(ok[u] ? row : r0) * stride_t + col;
+            int64_t off = (int64_t)(ok[u] ? row : safe_row) * stride_t + col;
             kr[u] = *reinterpret_cast<const uint4*>(kbase + off);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int row = t0 + u * RPL + grp;
-            int64_t off = (int64_t)(ok[u] ? row : r0) * stride_t + col;
+            int64_t off = (int64_t)(ok[u] ? row : safe_row) * stride_t + col;
             vr[u] = *reinterpret_cast<const uint4*>(vbase + off);
         }
         float s[U];

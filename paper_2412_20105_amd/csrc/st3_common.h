@@ -44,34 +44,67 @@ inline float scale_log2(const st3_attn_shape* s) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Workspace carving.  One layout serves every call; offsets are fixed by the bounds alone.
+// Workspace carving.  The decode-path region is laid out from the cache CAPACITY alone, so that
+// a layer which keeps its own workspace sees the same offsets at every step (the deferred visual
+// mass relies on the saved logits surviving from one call to the next).  The prefill region
+// starts behind it and depends on the call's own sizes.
 // ---------------------------------------------------------------------------------------------
-constexpr int kDecodeChunk = 256;          // keys per decode workgroup (split-KV granularity)
 constexpr int kMaxWindow = 16;
+constexpr int kDecodeTargetWgs = 1024;     // split the KV range until about this many workgroups exist
+constexpr int kDecodeMaxSplit = 64;
+constexpr int kDecodeMinChunk = 64;        // never cut a (b,h) strip into chunks shorter than this
 
-struct WorkspaceLayout {
-    size_t part_o, part_ml, logits, moves_cnt, moves, pre_logits, pre_ml, total;
-    int nsplit_max;
+// Number of chunks each (b,h) strip is cut into for a given upper bound on its length.
+inline int decode_nsplit(int B, int H, int max_kv) {
+    const int64_t bh = (int64_t)B * H;
+    int64_t want = (kDecodeTargetWgs + bh - 1) / bh;
+    int64_t by_len = ((int64_t)max_kv + kDecodeMinChunk - 1) / kDecodeMinChunk;
+    int64_t ns = want < by_len ? want : by_len;
+    if (ns > kDecodeMaxSplit) ns = kDecodeMaxSplit;
+    return ns < 1 ? 1 : (int)ns;
+}
+// Chunk length for that split count: a multiple of 32 rows.
+inline int decode_chunk(int max_kv, int nsplit) {
+    int c = (max_kv + nsplit - 1) / nsplit;
+    c = (c + 31) / 32 * 32;
+    return c < 32 ? 32 : c;
+}
+
+struct DecodeWs {
+    size_t part_o, part_ml, logits, pending, moves_cnt, moves, total;
+    int nsplit_cap;
     int max_moves;
 };
 
-inline WorkspaceLayout workspace_layout(int B, int H, int D, int max_kv, int max_vis, int max_q, int window) {
-    WorkspaceLayout w{};
-    if (max_kv < 1) max_kv = 1;
-    if (max_vis < 0) max_vis = 0;
-    if (window < 1) window = 1;
-    w.nsplit_max = (max_kv + kDecodeChunk - 1) / kDecodeChunk;
-    w.max_moves = max_kv > 2 * max_vis ? max_kv : 2 * max_vis;
+inline DecodeWs decode_ws(int B, int H, int D, int capacity) {
+    DecodeWs w{};
+    if (capacity < 1) capacity = 1;
+    w.nsplit_cap = decode_nsplit(B, H, capacity);
+    w.max_moves = capacity;                 // a stable shift moves every row at most once
     size_t off = 0;
-    size_t BH = (size_t)B * H;
-    w.part_o = off;     off = align_up(off + BH * w.nsplit_max * D * sizeof(float), 256);
-    w.part_ml = off;    off = align_up(off + BH * w.nsplit_max * 2 * sizeof(float), 256);
-    w.logits = off;     off = align_up(off + BH * (size_t)max_vis * sizeof(float), 256);
+    const size_t BH = (size_t)B * H;
+    w.part_o = off;     off = align_up(off + BH * w.nsplit_cap * D * sizeof(float), 256);
+    w.part_ml = off;    off = align_up(off + BH * w.nsplit_cap * 2 * sizeof(float), 256);
+    w.logits = off;     off = align_up(off + BH * (size_t)capacity * sizeof(float), 256);   // [B,H,capacity]
+    w.pending = off;    off = align_up(off + (size_t)B * 4 * sizeof(int32_t), 256);         // [B][4]
     w.moves_cnt = off;  off = align_up(off + (size_t)B * sizeof(int32_t), 256);
     w.moves = off;      off = align_up(off + (size_t)B * w.max_moves * 2 * sizeof(int32_t), 256);
-    w.pre_logits = off; off = align_up(off + BH * (size_t)window * max_vis * sizeof(float), 256);
+    w.total = off;
+    return w;
+}
+
+struct PrefillWs {
+    size_t pre_logits, pre_ml, total;
+};
+
+inline PrefillWs prefill_ws(int B, int H, int vis_len, int window) {
+    PrefillWs w{};
+    if (vis_len < 0) vis_len = 0;
+    if (window < 1) window = 1;
+    const size_t BH = (size_t)B * H;
+    size_t off = 0;
+    w.pre_logits = off; off = align_up(off + BH * (size_t)window * vis_len * sizeof(float), 256);
     w.pre_ml = off;     off = align_up(off + BH * (size_t)window * 2 * sizeof(float), 256);
-    (void)max_q;
     w.total = off;
     return w;
 }

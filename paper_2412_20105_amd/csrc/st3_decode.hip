@@ -1,6 +1,27 @@
-// Decode attention over a ragged KV cache with fused visual-mass output, KV append, and the
-// merge kernel that finishes both (Eq. 2 with a single query row; score extraction of Sec. 3.2).
-#include "st3_attend.h"
+// Decode attention over a ragged KV cache (Eq. 2 with a single query row that follows every
+// cached key) with the visual mass of Sec. 3.2, plus KV append.
+//
+// decode_attend_kernel streams K and V exactly once.  Each (b,h) strip is cut into `nsplit`
+// chunks (one workgroup each); nsplit is 1 as soon as B*H alone fills the chip, and then the
+// workgroup writes the finished output row itself.  With nsplit > 1 the workgroups leave
+// un-normalised partials that decode_finish_kernel merges in chunk order.  For the visual mass the
+// attend kernel saves the scaled logits of the visual keys and every chunk's (max, sum); turning
+// them into probabilities and adding them over heads - in head order, so the sum is the same on
+// every run - is done by finish_mass(), either in decode_finish_kernel right away or, when the
+// caller defers it, at the start of the layer's next select-and-compact kernel.
+// When a token is appended in the same call its row is read from k_new/v_new by the workgroup
+// that owns the end of the strip, which also stores it into the cache.
+//
+// No kernel here communicates between workgroups of one launch: device-scope fences cost a
+// write-back and invalidate of the XCD-private L2 on this part and were measured to be ruinous.
+#include "st3_decode.h"
+
+#ifndef ST3_DECODE_U
+#define ST3_DECODE_U 8              // 16-byte loads of K (and of V) in flight per lane and tile
+#endif
+#ifndef ST3_DECODE_MIN_BLOCKS
+#define ST3_DECODE_MIN_BLOCKS 4     // workgroups per CU the register budget must allow
+#endif
 
 namespace st3 {
 
@@ -10,38 +31,57 @@ namespace {
 
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = kDecodeThreads / kWave;
-constexpr int kKeysPerWave = kDecodeChunk / kDecodeWaves;
 
 struct DecodeArgs {
     const void* q;
-    const void* k;
-    const void* v;
+    void* k;
+    void* v;
     int64_t stride_b, stride_h, stride_t;
     const int32_t* kv_len;
     const int32_t* vis_len;
-    int32_t sys_len, max_vis, max_kv, H, nsplit_max;
+    int32_t sys_len, max_vis, max_kv, H, nsplit, nsplit_cap, chunk, capacity;
+    int32_t defer;          // 1: the mass of this call is finished later; mark it pending
     float scale_l2;
-    float* part_o;
-    float* part_ml;
-    float* logits;          // null when no mass is wanted
+    float* part_o;          // [B,H,nsplit_cap,D]   (nsplit > 1 only)
+    float* part_ml;         // [B,H,nsplit_cap,2]
+    float* logits;          // [B,H,capacity]; null when no mass is wanted
+    int32_t* pending;       // [B][4]: {valid, nsplit, chunk, -} of a mass still to be finished (null: none)
+    const void* k_new;      // [B,H,D] rows of the token being appended (null: none); the cache row
+    const void* v_new;      //         kv_len[b]-1 is then taken from here and written to the cache
+    void* out;              // [B,H,D]
 };
 
-// grid (nsplit_max, H, B); one workgroup = one chunk of kDecodeChunk keys of one (b,h).
+template <typename T>
+__device__ __forceinline__ void store_out(void* out, int64_t idx, float o) {
+    if (sizeof(T) == 4) reinterpret_cast<float*>(out)[idx] = o;
+    else reinterpret_cast<uint16_t*>(out)[idx] = (uint16_t)f32_to_bf16_bits(o);
+}
+
+// grid (nsplit, H, B)
 template <typename T, int D, int U>
-__global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_attend_kernel(DecodeArgs a) {
     using M = RowMap<T, D>;
-    constexpr int EPL = M::EPL, LPR = M::LPR;
+    constexpr int EPL = M::EPL, LPR = M::LPR, TILE = U * M::RPL;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int len = min(a.kv_len[b], a.max_kv);      // never trust a device length past the host bound
-    const int c0 = split * kDecodeChunk;
-    if (c0 >= len) return;
-    const int c1 = min(c0 + kDecodeChunk, len);
+    const int c0 = split * a.chunk;
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-
     const int64_t bh = (int64_t)b * a.H + h;
+    if (split == 0 && h == 0 && tid == 0 && a.pending != nullptr) {
+        a.pending[b * 4 + 0] = (a.logits != nullptr && len > 0 && a.defer) ? 1 : 0;
+        a.pending[b * 4 + 1] = a.nsplit;
+        a.pending[b * 4 + 2] = a.chunk;
+    }
+    if (len <= 0) {                                  // empty sequence: out = 0, no mass
+        if (split == 0 && tid < D) store_out<T>(a.out, bh * D + tid, 0.f);
+        return;
+    }
+    if (c0 >= len) return;
+    const int c1 = min(c0 + a.chunk, len);
+
     const T* qrow = reinterpret_cast<const T*>(a.q) + bh * D;
-    const T* kbase = reinterpret_cast<const T*>(a.k) + b * a.stride_b + h * a.stride_h;
-    const T* vbase = reinterpret_cast<const T*>(a.v) + b * a.stride_b + h * a.stride_h;
+    T* kbase = reinterpret_cast<T*>(a.k) + b * a.stride_b + h * a.stride_h;
+    T* vbase = reinterpret_cast<T*>(a.v) + b * a.stride_b + h * a.stride_h;
 
     float qf[EPL];
     load_q_slice<T, D>(qrow, lane, qf);
@@ -51,14 +91,29 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(DecodeArgs
 #pragma unroll
     for (int e = 0; e < EPL; ++e) st.acc[e] = 0.f;
 
-    const int r0 = c0 + wave * kKeysPerWave;
-    const int r1 = min(r0 + kKeysPerWave, c1);
-    if (r0 < r1) {
-        float* lg = a.logits ? a.logits + bh * a.max_vis : nullptr;
-        int vis_lo = a.sys_len, vis_hi = a.sys_len + min(a.vis_len[b], a.max_vis);
-        wave_attend<T, D, U>(qf, kbase, vbase, a.stride_t, r0, r1, a.scale_l2, lane, st, lg, vis_lo, vis_hi);
-        finish_wave<T, D>(st);
+    const int nv = min(a.vis_len[b], a.max_vis);
+    float* lg = a.logits ? a.logits + bh * a.capacity : nullptr;
+    const int vis_lo = a.sys_len, vis_hi = a.sys_len + nv;
+    const bool has_new = a.k_new != nullptr && c1 == len;       // this workgroup owns the appended row
+    const int c1_cached = has_new ? c1 - 1 : c1;
+    // waves take the tiles of the chunk round-robin, so all four stay busy to the end
+    wave_attend<T, D, U>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0,
+                         a.scale_l2, lane, st, lg, vis_lo, vis_hi);
+    if (has_new && wave == 0) {
+        // address the new token's rows as if they were cache row len-1
+        const int64_t shift = (int64_t)(len - 1) * a.stride_t;
+        const T* kn = reinterpret_cast<const T*>(a.k_new) + bh * D;
+        const T* vn = reinterpret_cast<const T*>(a.v_new) + bh * D;
+        wave_attend<T, D, 1>(qf, kn - shift, vn - shift, a.stride_t, len - 1, len, M::RPL, len - 1, a.scale_l2, lane,
+                             st, lg, vis_lo, vis_hi);
+        if (lane < 2 * LPR) {
+            const int c = (lane % LPR) * EPL;
+            const T* src = (lane < LPR ? kn : vn) + c;
+            T* dst = (lane < LPR ? kbase : vbase) + shift + c;
+            *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+        }
     }
+    finish_wave<T, D>(st);
 
     __shared__ float sm_acc[kDecodeWaves][D];
     __shared__ float sm_m[kDecodeWaves], sm_l[kDecodeWaves];
@@ -69,88 +124,73 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(DecodeArgs
     if (lane == 0) { sm_m[wave] = st.m; sm_l[wave] = st.l; }
     __syncthreads();
     if (tid < D) {
-        float m = sm_m[0];                              // wave 0 always has rows: finite
+        float m = sm_m[0];
 #pragma unroll
-        for (int w = 1; w < kDecodeWaves; ++w) m = fmaxf(m, sm_m[w]);
+        for (int w = 1; w < kDecodeWaves; ++w) m = fmaxf(m, sm_m[w]);   // finite: the chunk is not empty
         float o = 0.f, l = 0.f;
 #pragma unroll
         for (int w = 0; w < kDecodeWaves; ++w) {
-            float f = exp2_fast(sm_m[w] - m);           // empty wave: exp2(-inf) = 0
+            float f = exp2_fast(sm_m[w] - m);           // wave without rows: exp2(-inf) = 0
             o = fmaf(sm_acc[w][tid], f, o);
             l = fmaf(sm_l[w], f, l);
         }
-        const int64_t slot = bh * a.nsplit_max + split;
-        a.part_o[slot * D + tid] = o;
+        const int64_t slot = bh * a.nsplit_cap + split;
+        if (a.nsplit == 1) store_out<T>(a.out, bh * D + tid, o / l);
+        else a.part_o[slot * D + tid] = o;
         if (tid == 0) { a.part_ml[slot * 2] = m; a.part_ml[slot * 2 + 1] = l; }
     }
 }
 
-struct MergeArgs {
+struct FinishArgs {
     const float* part_o;
     const float* part_ml;
     const float* logits;
     const int32_t* kv_len;
     const int32_t* vis_len;
-    int32_t H, nsplit_max, max_vis, max_kv;
-    void* out;
+    int32_t H, nsplit, nsplit_cap, chunk, capacity, max_vis, max_kv;
+    void* out;              // null: outputs already written (nsplit == 1)
     float* mass;            // null: no mass
     int64_t mass_stride;
+    const int32_t* pending; // descriptor left by the attend kernel
+    int32_t from_pending;   // 1: take nsplit/chunk from the descriptor, do nothing if none is pending
 };
 
-constexpr int kMergeThreads = 128;
-
-// grid (H + mass_blocks, B).  Blocks y < H merge the split partials of head y into out[b,y,:].
-// Blocks y >= H produce 128 mass entries each: they first rebuild (m_h, l_h) for every head,
-// then add the heads in index order, so the sum is the same on every run.
+// grid (out_blocks + mass_blocks, B), 256 threads.  Blocks x < H (when out != null) merge the
+// chunk partials of head x; the rest produce 256 mass entries each.
 template <typename T, int D>
-__global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(MergeArgs a) {
+__global__ __launch_bounds__(256) void decode_finish_kernel(FinishArgs a) {
     const int b = blockIdx.y, tid = threadIdx.x;
     const int len = min(a.kv_len[b], a.max_kv);
-    const int ns = (len + kDecodeChunk - 1) / kDecodeChunk;
-    if ((int)blockIdx.x < a.H) {
+    int nsplit = a.nsplit, chunk = a.chunk;
+    if (a.from_pending) {
+        if (a.pending[b * 4] == 0) return;
+        nsplit = min(a.pending[b * 4 + 1], a.nsplit_cap);
+        chunk = max(a.pending[b * 4 + 2], 32);
+    }
+    const int ns = len > 0 ? min((len + chunk - 1) / chunk, nsplit) : 0;
+    const int out_blocks = a.out ? a.H : 0;
+    if ((int)blockIdx.x < out_blocks) {
         const int h = blockIdx.x;
         const int64_t bh = (int64_t)b * a.H + h;
-        if (tid >= D) return;
-        float o = 0.f;
-        if (ns > 0) {
-            const float* ml = a.part_ml + bh * a.nsplit_max * 2;
-            float m = ml[0];
-            for (int s = 1; s < ns; ++s) m = fmaxf(m, ml[2 * s]);
-            float l = 0.f;
-            for (int s = 0; s < ns; ++s) {
-                float f = exp2_fast(ml[2 * s] - m);
-                l = fmaf(ml[2 * s + 1], f, l);
-                o = fmaf(a.part_o[(bh * a.nsplit_max + s) * D + tid], f, o);
-            }
-            o = o / l;
+        if (tid >= D || ns == 0) return;                // empty sequence: the attend kernel wrote zeros
+        const float* ml = a.part_ml + bh * a.nsplit_cap * 2;
+        float m = ml[0];
+        for (int s = 1; s < ns; ++s) m = fmaxf(m, ml[2 * s]);
+        float l = 0.f, o = 0.f;
+        for (int s = 0; s < ns; ++s) {                  // fixed order: chunk 0, 1, ...
+            float f = exp2_fast(ml[2 * s] - m);
+            l = fmaf(ml[2 * s + 1], f, l);
+            o = fmaf(a.part_o[(bh * a.nsplit_cap + s) * D + tid], f, o);
         }
-        if (sizeof(T) == 4) reinterpret_cast<float*>(a.out)[bh * D + tid] = o;
-        else reinterpret_cast<uint16_t*>(a.out)[bh * D + tid] = (uint16_t)f32_to_bf16_bits(o);
+        store_out<T>(a.out, bh * D + tid, o / l);
         return;
     }
     if (a.mass == nullptr) return;
     __shared__ float sm_m[1024], sm_rl[1024];
-    for (int h = tid; h < a.H; h += kMergeThreads) {
-        const float* ml = a.part_ml + ((int64_t)b * a.H + h) * a.nsplit_max * 2;
-        float m = -INFINITY, l = 0.f;
-        if (ns > 0) {
-            m = ml[0];
-            for (int s = 1; s < ns; ++s) m = fmaxf(m, ml[2 * s]);
-            for (int s = 0; s < ns; ++s) l = fmaf(ml[2 * s + 1], exp2_fast(ml[2 * s] - m), l);
-        }
-        sm_m[h] = m;
-        sm_rl[h] = ns > 0 ? 1.0f / l : 0.f;
-    }
-    __syncthreads();
-    const int j = (blockIdx.x - a.H) * kMergeThreads + tid;
     const int nv = min(a.vis_len[b], a.max_vis);
-    if (j >= nv) return;
-    float acc = 0.f;
-    for (int h = 0; h < a.H; ++h) {
-        float s = a.logits[((int64_t)b * a.H + h) * a.max_vis + j];
-        acc += exp2_fast(s - sm_m[h]) * sm_rl[h];
-    }
-    a.mass[(int64_t)b * a.mass_stride + j] = acc / (float)a.H;
+    head_norms(a.part_ml, b, a.H, ns, a.nsplit_cap, sm_m, sm_rl);
+    const int j0 = ((int)blockIdx.x - out_blocks) * 256;
+    finish_mass(a.logits, b, a.H, a.capacity, sm_m, sm_rl, j0, min(j0 + 256, nv), a.mass + (int64_t)b * a.mass_stride);
 }
 
 struct AppendArgs {
@@ -169,7 +209,7 @@ __global__ __launch_bounds__(64) void append_kernel(AppendArgs a) {
     using M = RowMap<T, D>;
     const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
     const int row = a.kv_len[b];
-    if (row >= a.capacity || lane >= 2 * M::LPR) return;
+    if (row < 0 || row >= a.capacity || lane >= 2 * M::LPR) return;
     const bool is_v = lane >= M::LPR;
     const int c = (lane % M::LPR) * M::EPL;
     const int64_t bh = (int64_t)b * a.H + h;
@@ -180,18 +220,20 @@ __global__ __launch_bounds__(64) void append_kernel(AppendArgs a) {
 
 __global__ void bump_len_kernel(int32_t* kv_len, int32_t B, int32_t capacity) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < B && kv_len[b] < capacity) kv_len[b] += 1;
+    if (b < B && kv_len[b] >= 0 && kv_len[b] < capacity) kv_len[b] += 1;
 }
 
 template <typename T, int D>
-void launch_decode(const DecodeArgs& da, const MergeArgs& ma, int B, hipStream_t st) {
-    dim3 g1(da.nsplit_max, da.H, B);
+void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
     profile_mark(st, false);
-    decode_split_kernel<T, D, 8><<<g1, kDecodeThreads, 0, st>>>(da);
+    decode_attend_kernel<T, D, ST3_DECODE_U><<<dim3(da.nsplit, da.H, B), kDecodeThreads, 0, st>>>(da);
     profile_mark(st, true);
-    int mass_blocks = ma.mass ? (ma.max_vis + kMergeThreads - 1) / kMergeThreads : 0;
-    dim3 g2(ma.H + mass_blocks, B);
-    decode_merge_kernel<T, D><<<g2, kMergeThreads, 0, st>>>(ma);
+}
+
+template <typename T, int D>
+void launch_finish(const FinishArgs& fa, int B, hipStream_t st) {
+    const int blocks = (fa.out ? fa.H : 0) + (fa.mass ? (fa.max_vis + 255) / 256 : 0);
+    if (blocks > 0) decode_finish_kernel<T, D><<<dim3(blocks, B), 256, 0, st>>>(fa);
 }
 
 template <typename T, int D>
@@ -199,6 +241,15 @@ void launch_append(const AppendArgs& aa, int B, int32_t* kv_len, hipStream_t st)
     append_kernel<T, D><<<dim3(aa.H, B), 64, 0, st>>>(aa);
     bump_len_kernel<<<(B + 255) / 256, 256, 0, st>>>(kv_len, B, aa.capacity);
 }
+
+#define ST3_DISPATCH(fn, shape, ...)                                                                   \
+    do {                                                                                               \
+        if ((shape)->dtype == ST3_BF16) {                                                              \
+            if ((shape)->head_dim == 128) fn<bf16_t, 128>(__VA_ARGS__); else fn<bf16_t, 64>(__VA_ARGS__); \
+        } else {                                                                                       \
+            if ((shape)->head_dim == 128) fn<float, 128>(__VA_ARGS__); else fn<float, 64>(__VA_ARGS__);   \
+        }                                                                                              \
+    } while (0)
 
 st3_status check_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg) {
     if (!kv || !seg || !kv->k || !kv->v || !seg->kv_len || !seg->vis_len) return ST3_ERR_INVALID_ARG;
@@ -216,48 +267,82 @@ st3_status check_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_s
 
 }  // namespace
 
-// Used by st3_decode_layer_step as well.
+// Enqueues attention (+ the finish kernel when it is needed).  max_kv_len bounds kv_len[] as the
+// kernels will see it.  k_new/v_new non-null: row kv_len[b]-1 is the token being appended.
+// defer_mass: leave the head reduction of the mass to the layer's next select-and-compact call
+// (or to st3_decode_mass_finalize); the logits stay in the workspace until then.
 st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
-                          const st3_segments* seg, int32_t max_kv_len, void* out, float* vis_mass,
-                          int64_t mass_stride, void* workspace, size_t workspace_bytes, hipStream_t st) {
+                          const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
+                          void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
+                          void* workspace, size_t workspace_bytes, hipStream_t st) {
     const int B = shape->batch, H = shape->heads, D = shape->head_dim;
-    WorkspaceLayout wl = workspace_layout(B, H, D, max_kv_len, seg->max_vis_len, 0, 1);
+    const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
     if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
     char* ws = reinterpret_cast<char*>(workspace);
+    want_mass = want_mass && seg->max_vis_len > 0;
     DecodeArgs da{};
     da.q = q; da.k = kv->k; da.v = kv->v;
     da.stride_b = kv->stride_b; da.stride_h = kv->stride_h; da.stride_t = kv->stride_t;
     da.kv_len = seg->kv_len; da.vis_len = seg->vis_len;
-    da.sys_len = seg->sys_len; da.max_vis = seg->max_vis_len; da.max_kv = max_kv_len; da.H = H; da.nsplit_max = wl.nsplit_max;
+    da.sys_len = seg->sys_len; da.max_vis = seg->max_vis_len; da.max_kv = max_kv_len; da.H = H;
+    da.nsplit = decode_nsplit(B, H, max_kv_len);
+    if (da.nsplit > wl.nsplit_cap) da.nsplit = wl.nsplit_cap;
+    da.nsplit_cap = wl.nsplit_cap;
+    da.chunk = decode_chunk(max_kv_len, da.nsplit);
+    da.capacity = kv->capacity;
     da.scale_l2 = scale_log2(shape);
     da.part_o = reinterpret_cast<float*>(ws + wl.part_o);
     da.part_ml = reinterpret_cast<float*>(ws + wl.part_ml);
-    da.logits = (vis_mass && seg->max_vis_len > 0) ? reinterpret_cast<float*>(ws + wl.logits) : nullptr;
-    MergeArgs ma{};
-    ma.part_o = da.part_o; ma.part_ml = da.part_ml; ma.logits = da.logits;
-    ma.kv_len = seg->kv_len; ma.vis_len = seg->vis_len;
-    ma.H = H; ma.nsplit_max = wl.nsplit_max; ma.max_vis = seg->max_vis_len; ma.max_kv = max_kv_len;
-    ma.out = out; ma.mass = da.logits ? vis_mass : nullptr; ma.mass_stride = mass_stride;
-    if (shape->dtype == ST3_BF16) {
-        if (D == 128) launch_decode<bf16_t, 128>(da, ma, B, st); else launch_decode<bf16_t, 64>(da, ma, B, st);
-    } else {
-        if (D == 128) launch_decode<float, 128>(da, ma, B, st); else launch_decode<float, 64>(da, ma, B, st);
+    da.logits = want_mass ? reinterpret_cast<float*>(ws + wl.logits) : nullptr;
+    da.pending = reinterpret_cast<int32_t*>(ws + wl.pending);
+    da.k_new = k_new; da.v_new = v_new;
+    da.out = out;
+    da.defer = (want_mass && defer_mass) ? 1 : 0;
+    ST3_DISPATCH(launch_attend, shape, da, B, st);
+    const bool mass_now = want_mass && !defer_mass;
+    if (da.nsplit > 1 || mass_now) {
+        FinishArgs fa{};
+        fa.part_o = da.part_o; fa.part_ml = da.part_ml; fa.logits = da.logits;
+        fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len;
+        fa.H = H; fa.nsplit = da.nsplit; fa.nsplit_cap = wl.nsplit_cap; fa.chunk = da.chunk;
+        fa.capacity = kv->capacity; fa.max_vis = seg->max_vis_len; fa.max_kv = max_kv_len;
+        fa.out = da.nsplit > 1 ? out : nullptr;
+        fa.mass = mass_now ? vis_mass : nullptr; fa.mass_stride = mass_stride;
+        fa.pending = da.pending;
+        ST3_DISPATCH(launch_finish, shape, fa, B, st);
     }
     return check_launch();
 }
 
 st3_status enqueue_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                           const void* k_new, const void* v_new, hipStream_t st) {
-    const int B = shape->batch, H = shape->heads, D = shape->head_dim;
+    const int B = shape->batch, H = shape->heads;
     AppendArgs aa{};
     aa.k = kv->k; aa.v = kv->v;
     aa.stride_b = kv->stride_b; aa.stride_h = kv->stride_h; aa.stride_t = kv->stride_t;
     aa.k_new = k_new; aa.v_new = v_new; aa.kv_len = seg->kv_len; aa.H = H; aa.capacity = kv->capacity;
-    if (shape->dtype == ST3_BF16) {
-        if (D == 128) launch_append<bf16_t, 128>(aa, B, seg->kv_len, st); else launch_append<bf16_t, 64>(aa, B, seg->kv_len, st);
-    } else {
-        if (D == 128) launch_append<float, 128>(aa, B, seg->kv_len, st); else launch_append<float, 64>(aa, B, seg->kv_len, st);
-    }
+    ST3_DISPATCH(launch_append, shape, aa, B, seg->kv_len, st);
+    return check_launch();
+}
+
+// Finishes a deferred mass, if one is pending in this workspace.
+st3_status enqueue_mass_finalize(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                                 float* vis_mass, int64_t mass_stride, void* workspace, size_t workspace_bytes,
+                                 hipStream_t st) {
+    const int B = shape->batch, H = shape->heads, D = shape->head_dim;
+    const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
+    if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
+    if (seg->max_vis_len == 0) return ST3_OK;
+    char* ws = reinterpret_cast<char*>(workspace);
+    FinishArgs fa{};
+    fa.part_ml = reinterpret_cast<float*>(ws + wl.part_ml);
+    fa.logits = reinterpret_cast<float*>(ws + wl.logits);
+    fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len;
+    fa.H = H; fa.nsplit = wl.nsplit_cap; fa.nsplit_cap = wl.nsplit_cap; fa.chunk = 32;
+    fa.capacity = kv->capacity; fa.max_vis = seg->max_vis_len; fa.max_kv = seg->max_kv_len;
+    fa.out = nullptr; fa.mass = vis_mass; fa.mass_stride = mass_stride;
+    fa.pending = reinterpret_cast<int32_t*>(ws + wl.pending); fa.from_pending = 1;
+    ST3_DISPATCH(launch_finish, shape, fa, B, st);
     return check_launch();
 }
 
@@ -277,8 +362,22 @@ extern "C" st3_status st3_decode_attention(const st3_attn_shape* shape, const vo
     if (!q || !out || !workspace) return ST3_ERR_INVALID_ARG;
     if (!st3::aligned16(q) || !st3::aligned16(workspace)) return ST3_ERR_INVALID_ARG;
     if (vis_mass && mass_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
-    return st3::enqueue_decode(shape, q, kv, seg, seg->max_kv_len, out, vis_mass, mass_stride, workspace,
-                               workspace_bytes, reinterpret_cast<hipStream_t>(stream));
+    return st3::enqueue_decode(shape, q, kv, seg, seg->max_kv_len, nullptr, nullptr, out, vis_mass, mass_stride,
+                               vis_mass != nullptr, false, workspace, workspace_bytes,
+                               reinterpret_cast<hipStream_t>(stream));
+}
+
+extern "C" st3_status st3_decode_mass_finalize(const st3_attn_shape* shape, const st3_kv_layer* kv,
+                                               const st3_segments* seg, float* vis_mass, int64_t mass_stride,
+                                               void* workspace, size_t workspace_bytes, void* stream) {
+    st3_status s = st3::check_shape(shape);
+    if (s != ST3_OK) return s;
+    s = st3::validate_kv(shape, kv, seg);
+    if (s != ST3_OK) return s;
+    if (!vis_mass || !workspace || !st3::aligned16(workspace)) return ST3_ERR_INVALID_ARG;
+    if (mass_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
+    return st3::enqueue_mass_finalize(shape, kv, seg, vis_mass, mass_stride, workspace, workspace_bytes,
+                                      reinterpret_cast<hipStream_t>(stream));
 }
 
 extern "C" st3_status st3_kv_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,

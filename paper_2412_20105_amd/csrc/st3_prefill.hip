@@ -8,22 +8,9 @@
 // (max, sum) in the workspace; prefill_mass_kernel turns them into probabilities and adds them
 // over heads and rows in a fixed order.
 #include "st3_attend.h"
+#include "st3_prefill.h"
 
 namespace st3 {
-
-struct PrefillArgs {
-    const void* q; const void* k; const void* v; void* out;
-    int64_t q_sb, q_sh, q_st;
-    int64_t k_sb, k_sh, k_st;
-    int64_t v_sb, v_sh, v_st;
-    int64_t o_sb, o_sh, o_st;
-    int32_t n, sys_len, vis_len, window, H;
-    float scale_l2;
-    float* pre_logits;      // [B,H,W,vis_len] log2-domain logits of the last W rows (null: no mass)
-    float* pre_ml;          // [B,H,W,2] row max and row sum
-};
-
-st3_status launch_prefill_mfma(const PrefillArgs& a, int B, int D, hipStream_t st);   // st3_prefill_mfma.hip
 
 namespace {
 
@@ -52,7 +39,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillArgs a) {
     float* lg = nullptr;
     if (a.pre_logits && w_idx >= 0) lg = a.pre_logits + (bh * a.window + w_idx) * a.vis_len;
     // K and V may have different strides; wave_attend takes one stride, so require equality here
-    wave_attend<T, D, 4>(qf, kbase, vbase, a.k_st, 0, i + 1, a.scale_l2, lane, st, lg, a.sys_len,
+    wave_attend<T, D, 4>(qf, kbase, vbase, a.k_st, 0, i + 1, 4 * M::RPL, 0, a.scale_l2, lane, st, lg, a.sys_len,
                          a.sys_len + a.vis_len);
     finish_wave<T, D>(st);
     if (lane < LPR) {
@@ -134,11 +121,13 @@ extern "C" st3_status st3_prefill_attention(const st3_attn_shape* shape, const s
     if (k->stride_t != v->stride_t) return ST3_ERR_UNSUPPORTED;
     const bool want_mass = vis_mass != nullptr && vis_len > 0;
     if (want_mass && mass_stride < vis_len) return ST3_ERR_INVALID_ARG;
-    WorkspaceLayout wl = workspace_layout(B, H, D, 1, vis_len, n, score_window);
+    const PrefillWs wl = prefill_ws(B, H, vis_len, score_window);
+    // the prefill scratch sits at the END of the workspace, clear of the decode-path region
     if (want_mass) {
         if (!workspace || !aligned16(workspace)) return ST3_ERR_INVALID_ARG;
         if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
     }
+    const size_t ws_base = want_mass ? (workspace_bytes - wl.total) / 256 * 256 : 0;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     PrefillArgs a{};
     a.q = q->data; a.k = k->data; a.v = v->data; a.out = out->data;
@@ -149,7 +138,7 @@ extern "C" st3_status st3_prefill_attention(const st3_attn_shape* shape, const s
     a.n = n; a.sys_len = sys_len; a.vis_len = vis_len; a.window = score_window; a.H = H;
     a.scale_l2 = scale_log2(shape);
     if (want_mass) {
-        char* ws = reinterpret_cast<char*>(workspace);
+        char* ws = reinterpret_cast<char*>(workspace) + ws_base;
         a.pre_logits = reinterpret_cast<float*>(ws + wl.pre_logits);
         a.pre_ml = reinterpret_cast<float*>(ws + wl.pre_ml);
     }

@@ -1,7 +1,232 @@
-// bf16 prefill attention on the MFMA units (placeholder until the tiled kernel lands).
-#include "st3_common.h"
+// bf16 prefill attention (Eq. 2, causal) on the MFMA units of gfx950, with the logits of the last
+// W query rows saved for the visual mass (Sec. 3.2).
+//
+// Tiling.  A workgroup of 4 wavefronts owns 128 consecutive query rows (32 per wave) of one (b,h)
+// and walks the key tiles of 64 keys up to its diagonal.  K and V tiles are staged in LDS once
+// per workgroup; V is stored transposed (Vt[d][key]) because both MFMA operands want the
+// contraction index contiguous per lane.
+//
+// Per wave and key tile, with v_mfma_f32_32x32x16_bf16 (A: 32 x 16, B: 16 x 32, C: 32 x 32; lane l
+// holds A[l%32][8*(l/32)..+8], B[8*(l/32)..+8][l%32] and C[8*(r/4) + 4*(l/32) + r%4][l%32], r < 16):
+//   S^T = K Q^T   A = K rows from LDS, B = Q fragments kept in registers.  A lane then owns ONE
+//                 query (column l%32) and 16 of the 32 keys of a sub-tile, so the softmax row
+//                 reductions are in-lane plus one exchange with lane l^32.
+//   O^T = V^T P^T A = Vt rows from LDS, B = P^T taken straight from the S^T accumulator registers.
+//                 The accumulator's row pattern fixes which keys a lane holds, so the contraction
+//                 slots are assigned to keys in that pattern and Vt is read in the same pattern.
+// Online softmax in the log2 domain, fp32.  For the second MFMA P is split into two bf16 terms,
+// P = P_hi + P_lo (16 mantissa bits together), and both are multiplied by V: rounding P to one
+// bf16 would put an error of 2^-9 of the row's magnitude on every output element, which is far
+// above the element-wise tolerance for outputs that happen to be small.
+#include "st3_prefill.h"
 
 namespace st3 {
-struct PrefillArgs;
-st3_status launch_prefill_mfma(const PrefillArgs&, int, int, hipStream_t) { return ST3_ERR_UNSUPPORTED; }
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kBM = 128;            // queries per workgroup
+constexpr int kBN = 64;             // keys per tile
+constexpr int kVPad = kBN + 2;      // Vt row stride in elements: 33 words, so column reads spread over banks
+
+union Frag {
+    bf16x8 v;
+    uint4 u4;
+    uint32_t w[4];
+};
+
+// grid (ceil(n/128), H, B); x reversed so the longest query tiles start first.
+template <int D>
+__global__ __launch_bounds__(256) void prefill_mfma_kernel(PrefillArgs a) {
+    constexpr int KS = D / 16;          // contraction steps of S^T
+    constexpr int DT = D / 32;          // 32-row tiles of O^T
+    constexpr int KPAD = D + 8;         // K row stride in LDS (elements)
+    constexpr int VPR = D / 8;          // 16-byte vectors per row
+    __shared__ __attribute__((aligned(16))) uint16_t Ks[kBN * KPAD];
+    __shared__ __attribute__((aligned(16))) uint16_t Vt[D * kVPad];
+
+    const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 5, c = lane & 31;
+    const int n = a.n;
+    const int q0 = qt * kBM + wave * 32;
+    const int myq = q0 + c;
+    const int64_t bh = (int64_t)b * a.H + h;
+
+    const uint16_t* Qp = reinterpret_cast<const uint16_t*>(a.q) + b * a.q_sb + h * a.q_sh;
+    const uint16_t* Kp = reinterpret_cast<const uint16_t*>(a.k) + b * a.k_sb + h * a.k_sh;
+    const uint16_t* Vp = reinterpret_cast<const uint16_t*>(a.v) + b * a.v_sb + h * a.v_sh;
+
+    Frag qf[KS];
+    {
+        const uint16_t* qrow = Qp + (int64_t)min(myq, n - 1) * a.q_st;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qf[s].u4 = *reinterpret_cast<const uint4*>(qrow + 16 * s + 8 * g);
+    }
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    float m_i = -INFINITY, l_i = 0.f;
+
+    // window rows (the last W queries) held by this wave?
+    const bool wave_has_window = a.pre_logits != nullptr && q0 + 31 >= n - a.window && q0 < n;
+    const int w_idx = myq - (n - a.window);
+    const bool lane_in_window = wave_has_window && w_idx >= 0 && myq < n;
+    float* lg_row = lane_in_window ? a.pre_logits + (bh * a.window + w_idx) * a.vis_len : nullptr;
+
+    const int k_end = min(n, qt * kBM + kBM);           // keys this workgroup can see
+    for (int k0 = 0; k0 < k_end; k0 += kBN) {
+        __syncthreads();                                // previous tile fully consumed
+        // ---- stage K tile: kBN rows x D, 16 bytes per thread and step, coalesced -------------
+#pragma unroll
+        for (int i = 0; i < kBN * VPR / 256; ++i) {
+            const int vec = tid + 256 * i;
+            const int row = vec / VPR, cv = vec % VPR;
+            const int key = min(k0 + row, n - 1);
+            const uint4 val = *reinterpret_cast<const uint4*>(Kp + (int64_t)key * a.k_st + cv * 8);
+            *reinterpret_cast<uint4*>(&Ks[row * KPAD + cv * 8]) = val;
+        }
+        // ---- stage V tile transposed: a thread takes 2 adjacent keys x 8 columns --------------
+#pragma unroll
+        for (int i = 0; i < (kBN / 2) * VPR / 256; ++i) {
+            const int item = tid + 256 * i;
+            const int cv = item % VPR, kp = item / VPR;
+            const int key_a = min(k0 + 2 * kp, n - 1), key_b = min(k0 + 2 * kp + 1, n - 1);
+            const uint4 va = *reinterpret_cast<const uint4*>(Vp + (int64_t)key_a * a.v_st + cv * 8);
+            const uint4 vb = *reinterpret_cast<const uint4*>(Vp + (int64_t)key_b * a.v_st + cv * 8);
+            const uint32_t wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t lo = (wa[e] & 0xffffu) | (wb[e] << 16);          // column 2e:   (key_a, key_b)
+                const uint32_t hi = (wa[e] >> 16) | (wb[e] & 0xffff0000u);      // column 2e+1
+                *reinterpret_cast<uint32_t*>(&Vt[(cv * 8 + 2 * e) * kVPad + 2 * kp]) = lo;
+                *reinterpret_cast<uint32_t*>(&Vt[(cv * 8 + 2 * e + 1) * kVPad + 2 * kp]) = hi;
+            }
+        }
+        __syncthreads();
+        if (k0 > q0 + 31) continue;                     // tile entirely above this wave's diagonal
+
+        // ---- S^T = K Q^T ------------------------------------------------------------------------
+        f32x16 sacc[2];
+        const bool sub_live[2] = {true, k0 + 32 <= q0 + 31};
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
+            if (sub_live[sub]) {
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    Frag ka;
+                    ka.u4 = *reinterpret_cast<const uint4*>(&Ks[(32 * sub + c) * KPAD + 16 * s + 8 * g]);
+                    sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, qf[s].v, sacc[sub], 0, 0, 0);
+                }
+            }
+        }
+        // ---- scale, causal / length mask, row maximum ---------------------------------------
+        float mx = -INFINITY;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = k0 + 32 * sub + 8 * (r / 4) + 4 * g + (r % 4);
+                float s = sacc[sub][r] * a.scale_l2;
+                if (key > myq || key >= n || !sub_live[sub]) s = -INFINITY;
+                sacc[sub][r] = s;
+                mx = fmaxf(mx, s);
+            }
+        if (wave_has_window) {
+            if (lg_row != nullptr) {
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = k0 + 32 * sub + 8 * (r / 4) + 4 * g + (r % 4);
+                        if (key >= a.sys_len && key < a.sys_len + a.vis_len && key <= myq)
+                            lg_row[key - a.sys_len] = sacc[sub][r];
+                    }
+            }
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        // every row sees key k0 (k0 <= q0 <= myq, k0 < n), so the maximum is finite
+        const float m_new = fmaxf(m_i, mx);
+        const float alpha = exp2_fast(m_i - m_new);
+        m_i = m_new;
+        float psum = 0.f;
+        Frag pb[2][2], pl[2][2];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float p = exp2_fast(sacc[sub][8 * kk + j] - m_new);
+                    psum += p;
+                    const __bf16 hi = (__bf16)p;
+                    pb[sub][kk].v[j] = hi;
+                    pl[sub][kk].v[j] = (__bf16)(p - (float)hi);
+                }
+        l_i = l_i * alpha + psum;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+        // ---- O^T += V^T P^T ---------------------------------------------------------------------
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            if (!sub_live[sub]) continue;
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const int base = 32 * sub + 16 * kk + 4 * g;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const uint16_t* row = &Vt[(32 * dt + c) * kVPad + base];
+                    Frag va;
+                    va.w[0] = *reinterpret_cast<const uint32_t*>(row);
+                    va.w[1] = *reinterpret_cast<const uint32_t*>(row + 2);
+                    va.w[2] = *reinterpret_cast<const uint32_t*>(row + 8);
+                    va.w[3] = *reinterpret_cast<const uint32_t*>(row + 10);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb[sub][kk].v, oacc[dt], 0, 0, 0);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pl[sub][kk].v, oacc[dt], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // ---- normalise and store -----------------------------------------------------------------
+    const float l_tot = l_i + __shfl_xor(l_i, 32);
+    const float rl = 1.0f / l_tot;
+    if (myq < n) {
+        uint16_t* orow = reinterpret_cast<uint16_t*>(a.out) + b * a.o_sb + h * a.o_sh + (int64_t)myq * a.o_st;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int dd = 32 * dt + 8 * rq + 4 * g;
+                uint2 pk;
+                pk.x = f32_to_bf16_bits(oacc[dt][4 * rq] * rl) | (f32_to_bf16_bits(oacc[dt][4 * rq + 1] * rl) << 16);
+                pk.y = f32_to_bf16_bits(oacc[dt][4 * rq + 2] * rl) | (f32_to_bf16_bits(oacc[dt][4 * rq + 3] * rl) << 16);
+                *reinterpret_cast<uint2*>(orow + dd) = pk;
+            }
+        if (lane_in_window && g == 0) {
+            a.pre_ml[(bh * a.window + w_idx) * 2] = m_i;
+            a.pre_ml[(bh * a.window + w_idx) * 2 + 1] = l_tot;
+        }
+    }
+}
+
+}  // namespace
+
+st3_status launch_prefill_mfma(const PrefillArgs& a, int B, int D, hipStream_t st) {
+    // 8-byte output stores and 16-byte input loads need these alignments (rows are 16-byte aligned already)
+    dim3 grid((a.n + kBM - 1) / kBM, a.H, B);
+    if (D == 128) prefill_mfma_kernel<128><<<grid, 256, 0, st>>>(a);
+    else if (D == 64) prefill_mfma_kernel<64><<<grid, 256, 0, st>>>(a);
+    else return ST3_ERR_UNSUPPORTED;
+    return ST3_OK;
+}
+
 }  // namespace st3

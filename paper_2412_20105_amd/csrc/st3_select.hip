@@ -6,7 +6,7 @@
 // (4 passes of 8 bits, histogram in LDS), followed - only when the k-th score is shared - by a
 // second radix select on the tie ids, so that the result is the unique top-k set under the total
 // order (score descending, id ascending).  One workgroup per sequence.
-#include "st3_common.h"
+#include "st3_decode.h"
 
 namespace st3 {
 
@@ -237,114 +237,183 @@ struct EvictArgs {
     int32_t* move_cnt;          // [B]
     int32_t* moves;             // [B][max_moves][2] = (dst row, src row)
     int32_t max_moves;
+    // extras used by the fused per-layer decode step
+    int32_t do_append;          // 1: after eviction, kv_len[b] += 1 (room for the new token's row)
+    int32_t capacity;
+    int32_t inline_apply;       // 1: HOLE_FILL moves are applied to K and V by this kernel
+    char* k;
+    char* v;
+    int64_t stride_b, stride_h, stride_t;   // bytes
+    int32_t H, vecs_per_row;
+    // deferred visual mass of the previous attention call on this workspace (all null: none)
+    const float* part_ml;
+    const float* logits;
+    int32_t* pending;           // [B][4] descriptor written by the attend kernel
+    int32_t nsplit_cap;
+    float* mass_dst;
+    int64_t mass_stride;
 };
 
 __device__ __forceinline__ bool flag_at(const SelShared& sm, int p) { return (sm.flags[p >> 5] >> (p & 31)) & 1u; }
+
+// Copies `count` rows (dst_i <- src_i, from the move list starting at entry `first`) on all 2*H
+// strips of sequence b.  Callers guarantee that no destination of the batch is a source of it.
+__device__ __forceinline__ void copy_rows_all_strips(const EvictArgs& a, int b, const int32_t* mv, int first, int count) {
+    constexpr int UR = 8;                               // independent 16-byte loads in flight per thread
+    const int per_move = 2 * a.H * a.vecs_per_row;
+    const int total = count * per_move;
+    for (int base = 0; base < total; base += UR * kSelThreads) {
+        uint4 tmp[UR];
+        char* dst[UR];
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            const int idx = base + u * kSelThreads + (int)threadIdx.x;
+            dst[u] = nullptr;
+            if (idx < total) {
+                const int i = first + idx / per_move;
+                const int rem = idx % per_move;
+                const int strip = rem / a.vecs_per_row, vec = rem % a.vecs_per_row;
+                char* p = (strip < a.H ? a.k : a.v) + b * a.stride_b + (int64_t)(strip % a.H) * a.stride_h +
+                          (int64_t)vec * 16;
+                tmp[u] = *reinterpret_cast<const uint4*>(p + mv[2 * i + 1] * a.stride_t);
+                dst[u] = p + mv[2 * i] * a.stride_t;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UR; ++u)
+            if (dst[u]) *reinterpret_cast<uint4*>(dst[u]) = tmp[u];
+    }
+}
 
 __global__ __launch_bounds__(kSelThreads) void evict_plan_kernel(EvictArgs a) {
     __shared__ SelShared sm;
     const int b = blockIdx.x, tid = threadIdx.x;
     const int n = max(0, min(a.vis_len[b], a.max_vis));
     const int len = max(0, min(a.kv_len[b], a.max_kv));
-    const int k = max(0, min(a.keep_count, n));
-    if (k >= n || a.sys_len + n > len) {                // nothing to evict (or inconsistent lengths)
-        if (tid == 0) a.move_cnt[b] = 0;
-        return;
-    }
-    float* scores = a.score_col + b * a.col_stride;
-    int32_t* ids = a.id_col + b * a.col_stride;
-    int32_t* mv = a.moves + (int64_t)b * a.max_moves * 2;
-    uint32_t thr = 0, thr_id = 0;
-    bool all_ties = true;
-    if (k > 0) mark_topk(scores, ids, n, k, true, sm, thr, thr_id, all_ties);
-    else {
-        for (int i = tid; i < n; i += kSelThreads) sm.keys[i] = 0;
-        __syncthreads();
-    }
-    // flags -> LDS bitmap (one 32-bit word per 32 positions, built by ballot halves)
-    const int n_pad = (n + kSelThreads - 1) / kSelThreads * kSelThreads;
-    for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
-        const int p = p0 + tid;
-        bool keep = false;
-        if (p < n && k > 0) keep = is_kept(sm.keys[p], ~(uint32_t)ids[p], thr, thr_id, all_ties);
-        unsigned long long bal = __ballot(keep);
-        if (tid % kWave == 0) {
-            sm.flags[(p >> 5)] = (uint32_t)bal;
-            sm.flags[(p >> 5) + 1] = (uint32_t)(bal >> 32);
+    const int k = a.keep_count < 0 ? n : min(a.keep_count, n);
+    int new_len = len, moves_left = 0;
+    if (a.pending != nullptr && a.mass_dst != nullptr) {
+        // finish the mass the previous attention call left pending: lengths are still the ones it saw
+        __shared__ float sm_hm[1024], sm_hrl[1024];
+        const int valid = a.pending[b * 4];
+        if (valid) {
+            const int nsplit = min(a.pending[b * 4 + 1], a.nsplit_cap);
+            const int chunk = max(a.pending[b * 4 + 2], 32);
+            const int ns = len > 0 ? min((len + chunk - 1) / chunk, nsplit) : 0;
+            head_norms(a.part_ml, b, a.H, ns, a.nsplit_cap, sm_hm, sm_hrl);
+            finish_mass(a.logits, b, a.H, a.capacity, sm_hm, sm_hrl, 0, n, a.mass_dst + b * a.mass_stride);
+            __syncthreads();                            // the ranking below may read these scores
+            if (tid == 0) a.pending[b * 4] = 0;
         }
     }
-    __syncthreads();
-    const int g = n - k;                                // rows evicted
-    const int r = len - (a.sys_len + n);                // rows behind the visual segment
-    int m = 0;                                          // moves inside the visual segment
-    if (a.mode == ST3_HOLE_FILL) {
-        int base_h = 0, base_f = 0;
+    if (k < n && a.sys_len + n <= len) {                // something to evict, lengths consistent
+        float* scores = a.score_col + b * a.col_stride;
+        int32_t* ids = a.id_col + b * a.col_stride;
+        int32_t* mv = a.moves + (int64_t)b * a.max_moves * 2;
+        uint32_t thr = 0, thr_id = 0;
+        bool all_ties = true;
+        if (k > 0) mark_topk(scores, ids, n, k, true, sm, thr, thr_id, all_ties);
+        // flags -> LDS bitmap (one 32-bit word per 32 positions, built from wave ballots)
+        const int n_pad = (n + kSelThreads - 1) / kSelThreads * kSelThreads;
         for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
             const int p = p0 + tid;
-            const bool kept = p < n && flag_at(sm, p);
-            const bool hole = p < k && !kept;
-            const bool fill = p >= k && kept;
-            int packed = (hole ? 1 : 0) | (fill ? (1 << 16) : 0);
-            int incl = block_incl_scan(packed, sm);
-            if (hole) mv[2 * (base_h + (incl & 0xffff) - 1)] = a.sys_len + p;
-            if (fill) mv[2 * (base_f + (incl >> 16) - 1) + 1] = a.sys_len + p;
-            __syncthreads();
-            if (tid == kSelThreads - 1) sm.red = incl;
-            __syncthreads();
-            base_h += sm.red & 0xffff;
-            base_f += sm.red >> 16;
-        }
-        m = min(base_h, base_f);                        // equal when the ids are distinct
-        __syncthreads();                                // move list visible to the whole block
-        for (int i = tid; i < m; i += kSelThreads) {    // sources >= k, destinations < k: disjoint
-            int dst = mv[2 * i] - a.sys_len, src = mv[2 * i + 1] - a.sys_len;
-            scores[dst] = scores[src];
-            ids[dst] = ids[src];
-        }
-        const int cnt = min(g, r);
-        const int src0 = (r >= g) ? len - g : a.sys_len + n;
-        for (int j = tid; j < cnt; j += kSelThreads) {
-            mv[2 * (m + j)] = a.sys_len + k + j;
-            mv[2 * (m + j) + 1] = src0 + j;
-        }
-        if (tid == 0) a.move_cnt[b] = m + cnt;
-    } else {
-        // first hole = number of leading kept positions
-        int fh = n;
-        for (int p = tid; p < n; p += kSelThreads)
-            if (!flag_at(sm, p)) { fh = p; break; }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) fh = min(fh, __shfl_xor(fh, off));
-        if (tid % kWave == 0) sm.wave_tot[tid / kWave] = fh;
-        __syncthreads();
-        fh = min(min(sm.wave_tot[0], sm.wave_tot[1]), min(sm.wave_tot[2], sm.wave_tot[3]));
-        __syncthreads();
-        int base = 0;
-        for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
-            const int p = p0 + tid;
-            const bool kept = p < n && flag_at(sm, p);
-            float sv = 0.f; int32_t iv = 0;
-            if (kept) { sv = scores[p]; iv = ids[p]; }
-            int incl = block_incl_scan(kept ? 1 : 0, sm);       // contains barriers: loads precede stores
-            const int rank = base + incl - 1;
-            if (kept && p > fh) {
-                scores[rank] = sv; ids[rank] = iv;
-                mv[2 * (rank - fh)] = a.sys_len + rank;
-                mv[2 * (rank - fh) + 1] = a.sys_len + p;
+            bool keep = false;
+            if (p < n && k > 0) keep = is_kept(sm.keys[p], ~(uint32_t)ids[p], thr, thr_id, all_ties);
+            unsigned long long bal = __ballot(keep);
+            if (tid % kWave == 0) {
+                sm.flags[(p >> 5)] = (uint32_t)bal;
+                sm.flags[(p >> 5) + 1] = (uint32_t)(bal >> 32);
             }
-            __syncthreads();
-            if (tid == kSelThreads - 1) sm.red = incl;
-            __syncthreads();
-            base += sm.red;
         }
-        m = k - fh;
-        for (int j = tid; j < r; j += kSelThreads) {
-            mv[2 * (m + j)] = a.sys_len + k + j;
-            mv[2 * (m + j) + 1] = a.sys_len + n + j;
+        __syncthreads();
+        const int g = n - k;                            // rows evicted
+        const int r = len - (a.sys_len + n);            // rows behind the visual segment
+        int m = 0;                                      // moves inside the visual segment
+        if (a.mode == ST3_HOLE_FILL) {
+            int base_h = 0, base_f = 0;
+            for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
+                const int p = p0 + tid;
+                const bool kept = p < n && flag_at(sm, p);
+                const bool hole = p < k && !kept;
+                const bool fill = p >= k && kept;
+                int packed = (hole ? 1 : 0) | (fill ? (1 << 16) : 0);
+                int incl = block_incl_scan(packed, sm);
+                if (hole) mv[2 * (base_h + (incl & 0xffff) - 1)] = a.sys_len + p;
+                if (fill) mv[2 * (base_f + (incl >> 16) - 1) + 1] = a.sys_len + p;
+                __syncthreads();
+                if (tid == kSelThreads - 1) sm.red = incl;
+                __syncthreads();
+                base_h += sm.red & 0xffff;
+                base_f += sm.red >> 16;
+            }
+            m = min(base_h, base_f);                    // equal when the ids are distinct
+            __syncthreads();                            // move list visible to the whole block
+            for (int i = tid; i < m; i += kSelThreads) {    // sources >= k, destinations < k: disjoint
+                int dst = mv[2 * i] - a.sys_len, src = mv[2 * i + 1] - a.sys_len;
+                scores[dst] = scores[src];
+                ids[dst] = ids[src];
+            }
+            // refill the vacated end of the segment [k, n): from the END of the cache when at least
+            // g rows follow the segment, else all r following rows move down.  Either way sources
+            // and destinations are disjoint: r >= g -> src >= len-g >= sys+n; r < g -> dst < sys+k+r < sys+n.
+            const int cnt = min(g, r);
+            const int src0 = (r >= g) ? len - g : a.sys_len + n;
+            for (int j = tid; j < cnt; j += kSelThreads) {
+                mv[2 * (m + j)] = a.sys_len + k + j;
+                mv[2 * (m + j) + 1] = src0 + j;
+            }
+            moves_left = m + cnt;
+            if (a.inline_apply) {
+                __syncthreads();
+                copy_rows_all_strips(a, b, mv, 0, m);       // holes <- surviving tail of the segment
+                __syncthreads();                            // those reads are done before [k, n) is overwritten
+                copy_rows_all_strips(a, b, mv, m, cnt);
+                moves_left = 0;
+            }
+        } else {
+            // first hole = number of leading kept positions
+            int fh = n;
+            for (int p = tid; p < n; p += kSelThreads)
+                if (!flag_at(sm, p)) { fh = p; break; }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) fh = min(fh, __shfl_xor(fh, off));
+            if (tid % kWave == 0) sm.wave_tot[tid / kWave] = fh;
+            __syncthreads();
+            fh = min(min(sm.wave_tot[0], sm.wave_tot[1]), min(sm.wave_tot[2], sm.wave_tot[3]));
+            __syncthreads();
+            int base = 0;
+            for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
+                const int p = p0 + tid;
+                const bool kept = p < n && flag_at(sm, p);
+                float sv = 0.f; int32_t iv = 0;
+                if (kept) { sv = scores[p]; iv = ids[p]; }
+                int incl = block_incl_scan(kept ? 1 : 0, sm);       // contains barriers: loads precede stores
+                const int rank = base + incl - 1;
+                if (kept && p > fh) {
+                    scores[rank] = sv; ids[rank] = iv;
+                    mv[2 * (rank - fh)] = a.sys_len + rank;
+                    mv[2 * (rank - fh) + 1] = a.sys_len + p;
+                }
+                __syncthreads();
+                if (tid == kSelThreads - 1) sm.red = incl;
+                __syncthreads();
+                base += sm.red;
+            }
+            m = k - fh;
+            for (int j = tid; j < r; j += kSelThreads) {
+                mv[2 * (m + j)] = a.sys_len + k + j;
+                mv[2 * (m + j) + 1] = a.sys_len + n + j;
+            }
+            moves_left = m + r;
         }
-        if (tid == 0) a.move_cnt[b] = m + r;
+        new_len = len - g;
+        if (tid == 0) a.vis_len[b] = k;
     }
-    if (tid == 0) { a.vis_len[b] = k; a.kv_len[b] = len - g; }
+    if (a.do_append && new_len < a.capacity) new_len += 1;
+    if (tid == 0) {
+        a.move_cnt[b] = moves_left;
+        a.kv_len[b] = new_len;
+    }
 }
 
 struct ApplyArgs {
@@ -395,30 +464,55 @@ __global__ __launch_bounds__(256) void evict_apply_kernel(ApplyArgs a) {
 
 st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
 
+// Eviction plan (+ optional append bookkeeping, deferred-mass finish and in-kernel row moves),
+// then the separate move kernel when the plan kernel does not move the rows itself.
+//   do_append:  kv_len[b] += 1 after the eviction (the attention kernel writes the row)
+//   mass_dst:   where a mass left pending by the previous attention call is finished (null: skip)
+// Rows are moved inside the plan kernel when the mode is HOLE_FILL and at most kInlineEvict rows
+// can be evicted per sequence (one workgroup then moves a few dozen rows per strip); larger
+// evictions and STABLE mode go through evict_apply_kernel, which has a workgroup per strip.
+constexpr int kInlineEvict = 8;
+
 st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                                   float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
-                                  int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st) {
+                                  int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st,
+                                  int do_append, float* mass_dst, int64_t mass_stride) {
     const int B = shape->batch, H = shape->heads, D = shape->head_dim;
     if (seg->max_vis_len > kSelLdsKeys) return ST3_ERR_UNSUPPORTED;
-    WorkspaceLayout wl = workspace_layout(B, H, D, seg->max_kv_len, seg->max_vis_len, 0, 1);
+    const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
     if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
     char* ws = reinterpret_cast<char*>(workspace);
+    const int eb = elem_bytes(shape->dtype);
+    const bool evicting = keep_count >= 0 && keep_count < seg->max_vis_len;
     EvictArgs ea{};
     ea.score_col = score_col; ea.id_col = id_col; ea.col_stride = col_stride;
     ea.vis_len = seg->vis_len; ea.kv_len = seg->kv_len;
     ea.sys_len = seg->sys_len; ea.max_vis = seg->max_vis_len; ea.max_kv = seg->max_kv_len;
-    ea.keep_count = keep_count; ea.mode = mode;
+    ea.keep_count = evicting ? keep_count : -1; ea.mode = mode;
     ea.move_cnt = reinterpret_cast<int32_t*>(ws + wl.moves_cnt);
     ea.moves = reinterpret_cast<int32_t*>(ws + wl.moves);
     ea.max_moves = wl.max_moves;
+    ea.do_append = do_append; ea.capacity = kv->capacity;
+    ea.inline_apply = evicting && mode == ST3_HOLE_FILL && (seg->max_vis_len - keep_count) <= kInlineEvict;
+    ea.k = reinterpret_cast<char*>(kv->k); ea.v = reinterpret_cast<char*>(kv->v);
+    ea.stride_b = kv->stride_b * eb; ea.stride_h = kv->stride_h * eb; ea.stride_t = kv->stride_t * eb;
+    ea.H = H; ea.vecs_per_row = D * eb / 16;
+    if (mass_dst != nullptr) {
+        ea.part_ml = reinterpret_cast<const float*>(ws + wl.part_ml);
+        ea.logits = reinterpret_cast<const float*>(ws + wl.logits);
+        ea.pending = reinterpret_cast<int32_t*>(ws + wl.pending);
+        ea.nsplit_cap = wl.nsplit_cap;
+        ea.mass_dst = mass_dst; ea.mass_stride = mass_stride;
+    }
     evict_plan_kernel<<<B, kSelThreads, 0, st>>>(ea);
-    const int eb = elem_bytes(shape->dtype);
-    ApplyArgs aa{};
-    aa.k = reinterpret_cast<char*>(kv->k); aa.v = reinterpret_cast<char*>(kv->v);
-    aa.stride_b = kv->stride_b * eb; aa.stride_h = kv->stride_h * eb; aa.stride_t = kv->stride_t * eb;
-    aa.move_cnt = ea.move_cnt; aa.moves = ea.moves; aa.max_moves = wl.max_moves; aa.H = H;
-    aa.vecs_per_row = D * eb / 16;
-    evict_apply_kernel<<<dim3(2 * H, B), 256, 0, st>>>(aa);
+    if (evicting && !ea.inline_apply) {
+        ApplyArgs aa{};
+        aa.k = ea.k; aa.v = ea.v;
+        aa.stride_b = ea.stride_b; aa.stride_h = ea.stride_h; aa.stride_t = ea.stride_t;
+        aa.move_cnt = ea.move_cnt; aa.moves = ea.moves; aa.max_moves = wl.max_moves; aa.H = H;
+        aa.vecs_per_row = ea.vecs_per_row;
+        evict_apply_kernel<<<dim3(2 * H, B), 256, 0, st>>>(aa);
+    }
     return check_launch();
 }
 
@@ -483,5 +577,5 @@ extern "C" st3_status st3_select_compact_layer(const st3_attn_shape* shape, cons
     if (mode != ST3_STABLE && mode != ST3_HOLE_FILL) return ST3_ERR_INVALID_ARG;
     if (!st3::aligned16(workspace)) return ST3_ERR_INVALID_ARG;
     return st3::enqueue_select_compact(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, workspace,
-                                       workspace_bytes, reinterpret_cast<hipStream_t>(stream));
+                                       workspace_bytes, reinterpret_cast<hipStream_t>(stream), 0, nullptr, 0);
 }

@@ -37,7 +37,7 @@ def keep_table_for(workload) -> List[List[int]]:
 
 
 class LayerCache:
-    def __init__(self, B, H, d, cap, cap_v, dtype, device):
+    def __init__(self, B, H, d, cap, cap_v, dtype, device, ws_bytes):
         self.k = torch.empty((B, H, cap, d), dtype=dtype, device=device)
         self.v = torch.empty((B, H, cap, d), dtype=dtype, device=device)
         self.score = torch.zeros((B, max(cap_v, 1)), dtype=torch.float32, device=device)
@@ -46,6 +46,8 @@ class LayerCache:
         self.vis_len = torch.zeros((B,), dtype=torch.int32, device=device)
         self.kv_len = torch.zeros((B,), dtype=torch.int32, device=device)
         self.kv = st3.kv_layer(self.k, self.v)
+        # a workspace of its own: a deferred mass keeps its logits here until the next step
+        self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         # host-side bounds (exact here, since every sequence follows the same table)
         self.h_vis = 0
         self.h_kv = 0
@@ -61,11 +63,12 @@ class Generation:
     def __init__(self, layers: int, heads: int, head_dim: int, dtype: torch.dtype, batch: int,
                  n_sys: int, n_vis: int, n_txt: int, steps: int, keep: Sequence[Sequence[int]],
                  window: int = 1, mode: str = "static", compact_mode: int = st3.ST3_HOLE_FILL,
-                 device: str = "cuda:0"):
+                 defer_mass: bool = False, device: str = "cuda:0"):
         self.L, self.H, self.d, self.B = layers, heads, head_dim, batch
         self.n_sys, self.n_vis, self.n_txt, self.T = n_sys, n_vis, n_txt, steps
         self.keep = [list(r) for r in keep]
         self.window, self.mode, self.compact_mode = window, mode, compact_mode
+        self.defer_mass = defer_mass
         self.dtype, self.device = dtype, device
         self.shape = st3.make_shape(batch, heads, head_dim, st3._dtype_code(torch.empty(0, dtype=dtype)))
         self.N0 = n_sys + n_vis + n_txt
@@ -73,9 +76,9 @@ class Generation:
         for l in range(layers):
             cap = n_sys + self.keep[l][0] + n_txt + steps
             cap = max(cap, self.N0)                 # the unpruned prompt is staged in the cache first
-            self.layers.append(LayerCache(batch, heads, head_dim, cap, n_vis, dtype, device))
-        ws_bytes = st3.st3_workspace_bytes(self.shape, self.N0 + steps, n_vis, self.N0, window)
-        self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
+            ws_bytes = st3.st3_workspace_bytes(self.shape, cap, n_vis, window)
+            self.layers.append(LayerCache(batch, heads, head_dim, cap, n_vis, dtype, device, ws_bytes))
+            st3.st3_workspace_init(self.shape, cap, self.layers[-1].ws)
         self.q_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
         self.out_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
         self.dec_out = torch.empty((batch, heads, head_dim), dtype=dtype, device=device)
@@ -132,7 +135,7 @@ class Generation:
                 self._compact_strips(t, lc.ids, alive, nv, nx)
         out = self.out_stage[:, :, :n_l]
         st3.st3_prefill_attention(self.shape, self.q_stage[:, :, :n_l], lc.k[:, :, :n_l], lc.v[:, :, :n_l],
-                                  n_l, ns, alive, self.window, out, lc.mass, self.ws)
+                                  n_l, ns, alive, self.window, out, lc.mass, lc.ws)
         # ranking column: scores of the most recent prune event, else the layer's own mass
         lc.score.copy_(lc.mass if self._inherit is None else self._inherit)
         lc.vis_len.fill_(alive)
@@ -144,7 +147,8 @@ class Generation:
     def decode_layer(self, l: int, t: int, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor):
         """q, k_new, v_new: device [B,H,d].  Alg. 3, VTA branch, layer l of step t >= 1.
 
-        Returns (out [B,H,d] (reused buffer), mass view [B, keep[l][t]]).
+        Returns (out [B,H,d] (reused buffer), mass view [B, keep[l][t]]).  With defer_mass the
+        mass view is filled by the layer's next step or by finalize_mass().
         """
         lc = self.layers[l]
         target = min(self.keep[l][t], lc.h_vis)
@@ -152,10 +156,18 @@ class Generation:
         seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len)
         mass_dst = lc.score if self.mode == "current" else lc.mass
         st3.st3_decode_layer_step(self.shape, lc.kv, seg, lc.score, lc.ids, keep_count, self.compact_mode,
-                                  q, k_new, v_new, self.dec_out, mass_dst, self.ws)
+                                  q, k_new, v_new, self.dec_out, mass_dst, lc.ws, defer_mass=self.defer_mass)
         lc.h_kv = lc.h_kv - (lc.h_vis - target) + 1
         lc.h_vis = target
         return self.dec_out, mass_dst[:, :target]
+
+    def finalize_mass(self, l: int):
+        """Finishes the mass a deferred step left pending for layer l."""
+        lc = self.layers[l]
+        seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len)
+        mass_dst = lc.score if self.mode == "current" else lc.mass
+        st3.st3_decode_mass_finalize(self.shape, lc.kv, seg, mass_dst, lc.ws)
+        return mass_dst[:, :lc.h_vis]
 
     def kv_lens(self) -> List[int]:
         return [lc.h_kv for lc in self.layers]

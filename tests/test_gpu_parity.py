@@ -14,10 +14,13 @@ pytestmark = pytest.mark.gpu
 CODE = {"f32": st3.ST3_F32, "bf16": st3.ST3_BF16}
 
 
-def _ws(shape, max_kv, max_vis, max_q=0, window=1):
-    n = st3.st3_workspace_bytes(shape, max_kv, max_vis, max_q, window)
+def _ws(shape, capacity, max_vis, window=1):
+    n = st3.st3_workspace_bytes(shape, capacity, max_vis, window)
     assert n > 0
-    return torch.empty((n,), dtype=torch.uint8, device=DEV)
+    ws = torch.empty((n,), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xAB)                                   # not zero-filled: st3_workspace_init must do what is needed
+    st3.st3_workspace_init(shape, capacity, ws)
+    return ws
 
 
 def _i32(x):
@@ -50,7 +53,7 @@ def test_decode_attention_matches_oracle(dtype, D, B, H, lens, ns, nv):
     mass = torch.full((B, nv + 3), -7.0, dtype=torch.float32, device=DEV)
     kv_len, vis_len = _i32(lens), _i32(vis)
     seg = st3.segments(ns, nv, max(lens), vis_len, kv_len)
-    st3.st3_decode_attention(shape, dq, st3.kv_layer(dK, dV), seg, out, mass, _ws(shape, max(lens), nv))
+    st3.st3_decode_attention(shape, dq, st3.kv_layer(dK, dV), seg, out, mass, _ws(shape, cap, nv))
     torch.cuda.synchronize()
     got_o, got_m = to_np64(out), to_np64(mass)
     for b in range(B):
@@ -242,7 +245,7 @@ def test_select_compact_layer(mode, dtype, D):
         vis_len, kv_len = _i32(vis), _i32(lens)
         seg = st3.segments(ns, max(vis), max(lens), vis_len, kv_len)
         st3.st3_select_compact_layer(shape, st3.kv_layer(dK, dV), seg, d_score, d_ids, keep_count, mode,
-                                     _ws(shape, max(lens), max(vis)))
+                                     _ws(shape, cap, max(vis)))
         torch.cuda.synchronize()
         gK, gV = dK.float().cpu().numpy(), dV.float().cpu().numpy()
         g_score, g_ids = d_score.cpu().numpy(), d_ids.cpu().numpy()
@@ -306,7 +309,7 @@ def test_prefill_attention_matches_oracle(dtype, D, B, H, n, ns, nv, W):
     out = torch.zeros((B, H, n, D), dtype=TORCH_DTYPE[dtype], device=DEV)
     mass = torch.full((B, nv + 2), -3.0, dtype=torch.float32, device=DEV)
     st3.st3_prefill_attention(shape, to_dev(Q, dtype), dK[:, :, :n], dV[:, :, :n], n, ns, nv, W, out, mass,
-                              _ws(shape, 1, nv, n, W))
+                              _ws(shape, cap, nv, W))
     torch.cuda.synchronize()
     O, m = orc.prefill_attention(Q, K, V, ns, nv, W)
     assert_attention_close(to_np64(out), O, dtype)

@@ -16,13 +16,14 @@ from workloads import decode_qkv, get_workload, prefill_qkv
 pytestmark = pytest.mark.gpu
 
 
-def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None):
+def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None, defer=False):
     T = w.steps if steps is None else steps
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
     keep_np = np.array(keep)
     assert np.array_equal(keep_np, orc.schedule_for(w)[:, :T + 1])
     gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt,
-                              T, keep, window=window, mode=mode, compact_mode=compact_mode, device=DEV)
+                              T, keep, window=window, mode=mode, compact_mode=compact_mode, defer_mass=defer,
+                              device=DEV)
     ref = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, keep_np, window=window, mode=mode)
     pre = [prefill_qkv(w, l, B) for l in range(w.layers)]
     r = ref.prefill(lambda l: pre[l])
@@ -61,6 +62,7 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
             assert_attention_close(got_o[b], r["out"][l][b], w.dtype, f"prefill out l={l} b={b}")
             assert_mass_close(got_m[b], r["mass"][l][b], f"prefill mass l={l} b={b}")
             assert_mass_close(lc.score[b, :lc.h_vis].double().cpu().numpy(), ref.rho[l][b], f"rho l={l} b={b}")
+    held = {}                                     # deferred mode: (ids, oracle mass) of the previous step per (l, b)
     for t in range(1, T + 1):
         if t % 16 == 1:
             print(f"{w.name} decode step {t}", flush=True)
@@ -87,7 +89,29 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
                 # mass comes back in cache order; map through the id column
                 ids = lc.ids[b, :lc.h_vis].cpu().numpy()
                 pos = np.searchsorted(s["ids"][l][b], ids)
-                assert_mass_close(got_m[b], s["mass"][l][b][pos], f"decode mass t={t} l={l} b={b}")
+                if not defer:
+                    assert_mass_close(got_m[b], s["mass"][l][b][pos], f"decode mass t={t} l={l} b={b}")
+                elif mode == "static":
+                    # this call finished the PREVIOUS step's mass (in that step's cache order)
+                    if (l, b) in held:
+                        pids, pmass = held[(l, b)]
+                        assert_mass_close(lc.mass[b, :len(pids)].double().cpu().numpy(), pmass,
+                                          f"deferred mass of t={t - 1} l={l} b={b}")
+                    held[(l, b)] = (ids, s["mass"][l][b][pos])
+    if defer:
+        for l in range(w.layers):
+            m = gen.finalize_mass(l)
+            torch.cuda.synchronize()
+            lc = gen.layers[l]
+            for b in range(B):
+                if diverged[l, b]:
+                    continue
+                ids = lc.ids[b, :lc.h_vis].cpu().numpy()
+                pos = np.searchsorted(s["ids"][l][b], ids)
+                if mode == "static":
+                    assert_mass_close(to_np64(m)[b], s["mass"][l][b][pos], f"finalized mass l={l} b={b}")
+                else:
+                    assert_mass_close(to_np64(m)[b], ref.rho[l][b][pos], f"finalized score column l={l} b={b}")
     # KV bytes actually held == closed form
     assert gen.kv_bytes() == orc.kv_bytes(B, w.heads, w.head_dim, 2 if w.dtype == "bf16" else 4, ref.cache_lens())
     return near_ties, diverged
@@ -99,6 +123,19 @@ def test_tiny_workload_full(mode, compact_mode):
     w = get_workload("tiny")
     near, div = _run_and_compare(w, 1, mode=mode, compact_mode=compact_mode)
     assert not div.any(), "tiny workload resolved a near-tie differently from the oracle"
+
+
+@pytest.mark.parametrize("mode", ["static", "current"])
+def test_tiny_workload_deferred_mass(mode):
+    w = get_workload("tiny")
+    near, div = _run_and_compare(w, 2, mode=mode, defer=True)
+    assert not div.any()
+
+
+def test_13b_shape_cut_down_deferred_current():
+    w = dataclasses.replace(get_workload("llava15_13b"), layers=4, heads=8, steps=10,
+                            step_schedule={"kind": "cos", "tau": 10})
+    _run_and_compare(w, 2, mode="current", defer=True)
 
 
 def test_tiny_workload_batched_window():

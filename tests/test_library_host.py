@@ -62,12 +62,12 @@ def test_kv_bytes_closed_form():
 
 def test_workspace_bytes_monotone_and_rejects_bad_shapes():
     sh = st3.make_shape(2, 4, 64, st3.ST3_F32)
-    a = st3.st3_workspace_bytes(sh, 100, 64, 100, 1)
-    b = st3.st3_workspace_bytes(sh, 1000, 64, 100, 1)
-    c = st3.st3_workspace_bytes(sh, 1000, 640, 100, 4)
+    a = st3.st3_workspace_bytes(sh, 100, 64, 1)
+    b = st3.st3_workspace_bytes(sh, 1000, 64, 1)
+    c = st3.st3_workspace_bytes(sh, 1000, 640, 4)
     assert 0 < a <= b <= c
-    assert st3.st3_workspace_bytes(st3.make_shape(2, 4, 96, st3.ST3_F32), 100, 64, 100, 1) == 0
-    assert st3.st3_workspace_bytes(st3.make_shape(0, 4, 64, st3.ST3_F32), 100, 64, 100, 1) == 0
+    assert st3.st3_workspace_bytes(st3.make_shape(2, 4, 96, st3.ST3_F32), 100, 64, 1) == 0
+    assert st3.st3_workspace_bytes(st3.make_shape(0, 4, 64, st3.ST3_F32), 100, 64, 1) == 0
 
 
 def test_argument_errors_are_reported_before_any_launch():
