@@ -66,9 +66,7 @@ class Job:
             q, k, v = self.pre[l]
             gen.prefill_layer(l, q, k, v)
         for t in range(1, self.T + 1):
-            d = self.dec[t - 1]
-            for l in range(w.layers):
-                gen.decode_layer(l, t, d[l, 0], d[l, 1], d[l, 2])
+            gen.decode_step(t, self.dec[t - 1])
         for l in range(w.layers):           # the last step's masses are still pending
             gen.finalize_mass(l)
 
@@ -157,10 +155,16 @@ def main():
     T = a.decode_steps or w.steps
     B = a.batch
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
-    job = Job(w, B, T, keep, torch, pipeline, st3)
+    def note(msg):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
+    note(f"generating inputs for {w.name} B={B} T={T}")
+    job = Job(w, B, T, keep, torch, pipeline, st3)
+    note("warmup")
     for _ in range(a.warmup):
         job.run()
+    torch.cuda.synchronize()
+    note("timed region")
     ms_job = timed(torch, job.run, a.steps) * 1e3
     tokens = B * T
     value = tokens / (ms_job * 1e-3)
@@ -182,7 +186,9 @@ def main():
     }
 
     # -- roofline of the dominant kernel (split-KV decode), from a second, instrumented pass ---------
+    note(f"job {ms_job:.1f} ms, prefill {ms_prefill:.1f} ms")
     if not a.no_profile_pass:
+        note("instrumented pass")
         launches = w.layers * T
         st3.st3_profile_enable(launches + 8)
         job.run()
@@ -200,6 +206,7 @@ def main():
 
     # -- the same kernels without pruning ---------------------------------------------------------------
     if not a.no_unpruned:
+        note("unpruned run")
         import dataclasses
         wu = dataclasses.replace(w, layer_schedule={"kind": "full"}, step_schedule={"kind": "none"})
         keep_u = [row[:T + 1] for row in pipeline.keep_table_for(wu)]
@@ -216,6 +223,7 @@ def main():
             result["kv_bytes_ratio_vs_unpruned"] = result["kv_bytes_after_last_step"] / job_u.gen.kv_bytes()
 
     if not a.no_cpu_baseline:
+        note("cpu baseline (oracle)")
         result["cpu_baseline"] = cpu_baseline(w, keep, T, a.cpu_seconds)
     result["context"] = "paper headline (A100, whole model): ~2x faster inference at ~30% KV cache vs LLaVA; not a target"
     print(json.dumps(result))

@@ -221,6 +221,35 @@ ST3_EXPORT st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
                                             int64_t mass_stride, int32_t defer_mass, void* workspace,
                                             size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * One whole decode step over `n_layers` layers from a single host call (Alg. 3, VTA branch, the
+ * loop over l).  `layers` is a HOST array; entry i carries exactly the arguments
+ * st3_decode_layer_step takes for that layer.  The result is the same as calling
+ * st3_decode_layer_step for i = 0 .. n_layers-1 in order, but the evictions of all layers are
+ * planned up front, several layers per launch: a layer's eviction at step t depends only on its
+ * own score column and keep_count, not on this step's activations, so this reordering is also
+ * valid inside a real decoder.  The per-layer attention kernels follow in layer order.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    st3_kv_layer kv;
+    st3_segments seg;
+    float*       score_col;
+    int32_t*     id_col;
+    int64_t      col_stride;
+    int32_t      keep_count;        /* < 0: no eviction at this step */
+    const void*  q;
+    const void*  k_new;
+    const void*  v_new;
+    void*        out;
+    float*       vis_mass;
+    int64_t      mass_stride;
+    void*        workspace;         /* this layer's own workspace */
+    size_t       workspace_bytes;
+} st3_layer_step;
+
+ST3_EXPORT st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
+                                      int32_t mode, int32_t defer_mass, void* stream);
+
 /* Finishes a visual mass that st3_decode_layer_step left pending in `workspace` (no effect when
  * none is pending).  `seg` must describe the cache as that call left it. */
 ST3_EXPORT st3_status st3_decode_mass_finalize(const st3_attn_shape* shape, const st3_kv_layer* kv,

@@ -27,8 +27,8 @@ ST3_ANNEAL_COS, ST3_ANNEAL_LINEAR, ST3_ANNEAL_EXP, ST3_ANNEAL_DROP, ST3_ANNEAL_N
 EXPORTED = [
     "st3_status_string", "st3_last_hip_error", "st3_version", "st3_workspace_bytes", "st3_workspace_init",
     "st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_select_topk",
-    "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_mass_finalize",
-    "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
+    "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
+    "st3_decode_mass_finalize", "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
     "st3_debug_set_prefill_path", "st3_profile_enable", "st3_profile_read",
 ]
 
@@ -60,6 +60,13 @@ class KvLayer(C.Structure):
 class Segments(C.Structure):
     _fields_ = [("sys_len", C.c_int32), ("max_vis_len", C.c_int32), ("max_kv_len", C.c_int32),
                 ("vis_len", C.c_void_p), ("kv_len", C.c_void_p)]
+
+
+class LayerStep(C.Structure):
+    _fields_ = [("kv", KvLayer), ("seg", Segments), ("score_col", C.c_void_p), ("id_col", C.c_void_p),
+                ("col_stride", C.c_int64), ("keep_count", C.c_int32), ("q", C.c_void_p), ("k_new", C.c_void_p),
+                ("v_new", C.c_void_p), ("out", C.c_void_p), ("vis_mass", C.c_void_p), ("mass_stride", C.c_int64),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
 
 _lib: Optional[C.CDLL] = None
@@ -97,6 +104,8 @@ def lib() -> C.CDLL:
         L.st3_decode_layer_step.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_void_p, C.c_int64,
                                             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.st3_decode_step.argtypes = [P(AttnShape), C.c_int32, P(LayerStep), C.c_int32, C.c_int32, C.c_void_p]
+        L.st3_decode_step.restype = C.c_int
         L.st3_decode_mass_finalize.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_int64,
                                                C.c_void_p, C.c_size_t, C.c_void_p]
         L.st3_schedule_pvtp.argtypes = [C.c_int32] * 6 + [C.c_void_p]
@@ -245,6 +254,12 @@ def st3_decode_layer_step(shape, kv: KvLayer, seg: Segments, score_col, id_col, 
                                        workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                        _stream(stream)),
            "st3_decode_layer_step")
+
+
+def st3_decode_step(shape, layer_steps, n_layers, mode, defer_mass=False, stream=None):
+    """layer_steps: a ctypes array of LayerStep (the caller keeps the tensors it points to alive)."""
+    _check(lib().st3_decode_step(C.byref(shape), n_layers, layer_steps, mode, 1 if defer_mass else 0,
+                                 _stream(stream)), "st3_decode_step")
 
 
 def st3_decode_mass_finalize(shape, kv: KvLayer, seg: Segments, vis_mass, workspace, stream=None):

@@ -37,6 +37,8 @@ st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_laye
                                   float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
                                   int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st,
                                   int do_append, float* mass_dst, int64_t mass_stride);
+st3_status enqueue_plan_layers(const st3_attn_shape* shape, int n, const st3_layer_step* layers, int32_t mode,
+                               hipStream_t st);
 
 }  // namespace st3
 
@@ -87,16 +89,15 @@ extern "C" st3_status st3_workspace_init(const st3_attn_shape* shape, int32_t kv
     return check_launch();
 }
 
-extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv,
-                                            const st3_segments* seg, float* score_col, int32_t* id_col,
-                                            int64_t col_stride, int32_t keep_count, int32_t mode, const void* q,
-                                            const void* k_new, const void* v_new, void* out, float* vis_mass,
-                                            int64_t mass_stride, int32_t defer_mass, void* workspace,
-                                            size_t workspace_bytes, void* stream) {
-    using namespace st3;
-    st3_status s = check_shape(shape);
-    if (s != ST3_OK) return s;
-    s = validate_kv(shape, kv, seg);
+namespace st3 {
+// Host-side checks of one layer's arguments for the fused step (shared by the per-layer and the
+// whole-step entry points).
+static st3_status check_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                                   const float* score_col, const int32_t* id_col, int64_t col_stride,
+                                   int32_t keep_count, int32_t mode, const void* q, const void* k_new,
+                                   const void* v_new, const void* out, const float* vis_mass, int64_t mass_stride,
+                                   const void* workspace, size_t workspace_bytes) {
+    st3_status s = validate_kv(shape, kv, seg);
     if (s != ST3_OK) return s;
     if (!q || !k_new || !v_new || !out || !workspace) return ST3_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(workspace))
@@ -107,9 +108,26 @@ extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
         if (!score_col || !id_col || col_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
         if (mode != ST3_STABLE && mode != ST3_HOLE_FILL) return ST3_ERR_INVALID_ARG;
     }
-    // all size checks before the first launch, so that an error enqueues nothing
     const DecodeWs wl = decode_ws(shape->batch, shape->heads, shape->head_dim, kv->capacity);
     if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
+    return ST3_OK;
+}
+
+}  // namespace st3
+
+extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv,
+                                            const st3_segments* seg, float* score_col, int32_t* id_col,
+                                            int64_t col_stride, int32_t keep_count, int32_t mode, const void* q,
+                                            const void* k_new, const void* v_new, void* out, float* vis_mass,
+                                            int64_t mass_stride, int32_t defer_mass, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+    using namespace st3;
+    st3_status s = check_shape(shape);
+    if (s != ST3_OK) return s;
+    // all checks before the first launch, so that an error enqueues nothing
+    s = check_layer_step(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, q, k_new, v_new, out,
+                         vis_mass, mass_stride, workspace, workspace_bytes);
+    if (s != ST3_OK) return s;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     // (1) one workgroup per sequence: finish a mass left pending by the previous step, rank, evict
     //     (rows moved in place), kv_len += 1 for the new token.  Runs even when nothing is evicted.
@@ -119,6 +137,30 @@ extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
     // (2) attention over the cache; the appended row is read from k_new/v_new and stored on the way
     return enqueue_decode(shape, q, kv, seg, seg->max_kv_len + 1, k_new, v_new, out, vis_mass, mass_stride,
                           vis_mass != nullptr, defer_mass != 0, workspace, workspace_bytes, st);
+}
+
+extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
+                                      int32_t mode, int32_t defer_mass, void* stream) {
+    using namespace st3;
+    st3_status s = check_shape(shape);
+    if (s != ST3_OK) return s;
+    if (n_layers <= 0 || !layers) return ST3_ERR_INVALID_ARG;
+    for (int i = 0; i < n_layers; ++i) {
+        const st3_layer_step& L = layers[i];
+        s = check_layer_step(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_count, mode, L.q,
+                             L.k_new, L.v_new, L.out, L.vis_mass, L.mass_stride, L.workspace, L.workspace_bytes);
+        if (s != ST3_OK) return s;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    s = enqueue_plan_layers(shape, n_layers, layers, mode, st);
+    if (s != ST3_OK) return s;
+    for (int i = 0; i < n_layers; ++i) {
+        const st3_layer_step& L = layers[i];
+        s = enqueue_decode(shape, L.q, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.k_new, L.v_new, L.out, L.vis_mass,
+                           L.mass_stride, L.vis_mass != nullptr, defer_mass != 0, L.workspace, L.workspace_bytes, st);
+        if (s != ST3_OK) return s;
+    }
+    return ST3_OK;
 }
 
 extern "C" st3_status st3_profile_enable(int32_t max_launches) {

@@ -285,8 +285,7 @@ __device__ __forceinline__ void copy_rows_all_strips(const EvictArgs& a, int b, 
     }
 }
 
-__global__ __launch_bounds__(kSelThreads) void evict_plan_kernel(EvictArgs a) {
-    __shared__ SelShared sm;
+__device__ __forceinline__ void evict_plan_body(const EvictArgs& a, SelShared& sm) {
     const int b = blockIdx.x, tid = threadIdx.x;
     const int n = max(0, min(a.vis_len[b], a.max_vis));
     const int len = max(0, min(a.kv_len[b], a.max_kv));
@@ -416,6 +415,24 @@ __global__ __launch_bounds__(kSelThreads) void evict_plan_kernel(EvictArgs a) {
     }
 }
 
+__global__ __launch_bounds__(kSelThreads) void evict_plan_kernel(EvictArgs a) {
+    __shared__ SelShared sm;
+    evict_plan_body(a, sm);
+}
+
+// The same plan for several layers in one launch: grid (B, layers).  The evictions of a decode
+// step depend only on each layer's own score column and the retention table, never on the
+// activations of that step, so they can all be planned before the first layer's attention runs.
+constexpr int kPlanBatch = 16;
+struct EvictBatch {
+    EvictArgs layer[kPlanBatch];
+};
+
+__global__ __launch_bounds__(kSelThreads) void evict_plan_batch_kernel(EvictBatch batch) {
+    __shared__ SelShared sm;
+    evict_plan_body(batch.layer[blockIdx.y], sm);
+}
+
 struct ApplyArgs {
     char* k;
     char* v;
@@ -464,19 +481,18 @@ __global__ __launch_bounds__(256) void evict_apply_kernel(ApplyArgs a) {
 
 st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
 
-// Eviction plan (+ optional append bookkeeping, deferred-mass finish and in-kernel row moves),
-// then the separate move kernel when the plan kernel does not move the rows itself.
-//   do_append:  kv_len[b] += 1 after the eviction (the attention kernel writes the row)
-//   mass_dst:   where a mass left pending by the previous attention call is finished (null: skip)
 // Rows are moved inside the plan kernel when the mode is HOLE_FILL and at most kInlineEvict rows
 // can be evicted per sequence (one workgroup then moves a few dozen rows per strip); larger
 // evictions and STABLE mode go through evict_apply_kernel, which has a workgroup per strip.
 constexpr int kInlineEvict = 8;
 
-st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
-                                  float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
-                                  int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st,
-                                  int do_append, float* mass_dst, int64_t mass_stride) {
+namespace {
+
+// Fills the plan-kernel arguments for one layer.  Returns false when the sizes are unsupported.
+st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                            float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count, int32_t mode,
+                            void* workspace, size_t workspace_bytes, int do_append, float* mass_dst,
+                            int64_t mass_stride, EvictArgs& ea, bool& needs_apply) {
     const int B = shape->batch, H = shape->heads, D = shape->head_dim;
     if (seg->max_vis_len > kSelLdsKeys) return ST3_ERR_UNSUPPORTED;
     const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
@@ -484,7 +500,7 @@ st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_laye
     char* ws = reinterpret_cast<char*>(workspace);
     const int eb = elem_bytes(shape->dtype);
     const bool evicting = keep_count >= 0 && keep_count < seg->max_vis_len;
-    EvictArgs ea{};
+    ea = EvictArgs{};
     ea.score_col = score_col; ea.id_col = id_col; ea.col_stride = col_stride;
     ea.vis_len = seg->vis_len; ea.kv_len = seg->kv_len;
     ea.sys_len = seg->sys_len; ea.max_vis = seg->max_vis_len; ea.max_kv = seg->max_kv_len;
@@ -504,14 +520,66 @@ st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_laye
         ea.nsplit_cap = wl.nsplit_cap;
         ea.mass_dst = mass_dst; ea.mass_stride = mass_stride;
     }
-    evict_plan_kernel<<<B, kSelThreads, 0, st>>>(ea);
-    if (evicting && !ea.inline_apply) {
-        ApplyArgs aa{};
-        aa.k = ea.k; aa.v = ea.v;
-        aa.stride_b = ea.stride_b; aa.stride_h = ea.stride_h; aa.stride_t = ea.stride_t;
-        aa.move_cnt = ea.move_cnt; aa.moves = ea.moves; aa.max_moves = wl.max_moves; aa.H = H;
-        aa.vecs_per_row = ea.vecs_per_row;
-        evict_apply_kernel<<<dim3(2 * H, B), 256, 0, st>>>(aa);
+    needs_apply = evicting && !ea.inline_apply;
+    return ST3_OK;
+}
+
+void launch_apply(const EvictArgs& ea, int B, hipStream_t st) {
+    ApplyArgs aa{};
+    aa.k = ea.k; aa.v = ea.v;
+    aa.stride_b = ea.stride_b; aa.stride_h = ea.stride_h; aa.stride_t = ea.stride_t;
+    aa.move_cnt = ea.move_cnt; aa.moves = ea.moves; aa.max_moves = ea.max_moves; aa.H = ea.H;
+    aa.vecs_per_row = ea.vecs_per_row;
+    evict_apply_kernel<<<dim3(2 * ea.H, B), 256, 0, st>>>(aa);
+}
+
+}  // namespace
+
+// Eviction plan (+ optional append bookkeeping, deferred-mass finish and in-kernel row moves),
+// then the separate move kernel when the plan kernel does not move the rows itself.
+//   do_append:  kv_len[b] += 1 after the eviction (the attention kernel writes the row)
+//   mass_dst:   where a mass left pending by the previous attention call is finished (null: skip)
+st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                                  float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
+                                  int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st,
+                                  int do_append, float* mass_dst, int64_t mass_stride) {
+    EvictArgs ea;
+    bool needs_apply = false;
+    st3_status s = build_evict_args(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, workspace,
+                                    workspace_bytes, do_append, mass_dst, mass_stride, ea, needs_apply);
+    if (s != ST3_OK) return s;
+    evict_plan_kernel<<<shape->batch, kSelThreads, 0, st>>>(ea);
+    if (needs_apply) launch_apply(ea, shape->batch, st);
+    return check_launch();
+}
+
+// Plans the evictions of `n` layers with one launch per kPlanBatch layers (then the move kernel
+// for the layers whose evictions are too large to be moved by the plan kernel itself).
+st3_status enqueue_plan_layers(const st3_attn_shape* shape, int n, const st3_layer_step* layers, int32_t mode,
+                               hipStream_t st) {
+    const int B = shape->batch;
+    // validate everything first: nothing is enqueued on an error
+    for (int i = 0; i < n; ++i) {
+        EvictArgs ea;
+        bool na;
+        st3_status s = build_evict_args(shape, &layers[i].kv, &layers[i].seg, layers[i].score_col, layers[i].id_col,
+                                        layers[i].col_stride, layers[i].keep_count, mode, layers[i].workspace,
+                                        layers[i].workspace_bytes, 1, layers[i].vis_mass, layers[i].mass_stride, ea, na);
+        if (s != ST3_OK) return s;
+    }
+    for (int i0 = 0; i0 < n; i0 += kPlanBatch) {
+        const int cnt = n - i0 < kPlanBatch ? n - i0 : kPlanBatch;
+        EvictBatch batch;
+        bool needs_apply[kPlanBatch];
+        for (int i = 0; i < cnt; ++i) {
+            const st3_layer_step& L = layers[i0 + i];
+            build_evict_args(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_count, mode,
+                             L.workspace, L.workspace_bytes, 1, L.vis_mass, L.mass_stride, batch.layer[i],
+                             needs_apply[i]);
+        }
+        evict_plan_batch_kernel<<<dim3(B, cnt), kSelThreads, 0, st>>>(batch);
+        for (int i = 0; i < cnt; ++i)
+            if (needs_apply[i]) launch_apply(batch.layer[i], B, st);
     }
     return check_launch();
 }

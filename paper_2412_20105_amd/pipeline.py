@@ -82,6 +82,8 @@ class Generation:
         self.q_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
         self.out_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
         self.dec_out = torch.empty((batch, heads, head_dim), dtype=dtype, device=device)
+        self.dec_out_all = torch.empty((layers, batch, heads, head_dim), dtype=dtype, device=device)
+        self._steps = None                  # ctypes array of LayerStep, built on first decode_step()
         self.keep_idx = torch.empty((batch, max(n_vis, 1)), dtype=torch.int32, device=device)
         self._alive = n_vis                 # visual tokens alive in the layer being prefetched
         self._inherit: Optional[torch.Tensor] = None
@@ -161,11 +163,44 @@ class Generation:
         lc.h_vis = target
         return self.dec_out, mass_dst[:, :target]
 
+    def _mass_dst(self, lc: LayerCache) -> torch.Tensor:
+        return lc.score if self.mode == "current" else lc.mass
+
+    def decode_step(self, t: int, qkv: torch.Tensor):
+        """All layers of decode step t from one library call.  qkv: device [L, 3, B, H, d]
+        (q, k_new, v_new per layer).  Returns dec_out_all [L, B, H, d] (reused buffer)."""
+        assert qkv.is_contiguous() and tuple(qkv.shape) == (self.L, 3, self.B, self.H, self.d)
+        if self._steps is None:
+            arr = (st3.LayerStep * self.L)()
+            for l, lc in enumerate(self.layers):
+                s = arr[l]
+                s.kv = lc.kv
+                s.seg = st3.segments(self.n_sys, 0, 0, lc.vis_len, lc.kv_len)
+                s.score_col, s.id_col, s.col_stride = lc.score.data_ptr(), lc.ids.data_ptr(), lc.score.stride(0)
+                md = self._mass_dst(lc)
+                s.vis_mass, s.mass_stride = md.data_ptr(), md.stride(0)
+                s.out = self.dec_out_all[l].data_ptr()
+                s.workspace, s.workspace_bytes = lc.ws.data_ptr(), lc.ws.numel()
+            self._steps = arr
+        arr = self._steps
+        base = qkv.data_ptr()
+        one = self.B * self.H * self.d * self._eb
+        for l, lc in enumerate(self.layers):
+            s = arr[l]
+            target = min(self.keep[l][t], lc.h_vis)
+            s.keep_count = target if target < lc.h_vis else -1
+            s.seg.max_vis_len, s.seg.max_kv_len = lc.h_vis, lc.h_kv
+            s.q, s.k_new, s.v_new = base + (3 * l) * one, base + (3 * l + 1) * one, base + (3 * l + 2) * one
+            lc.h_kv = lc.h_kv - (lc.h_vis - target) + 1
+            lc.h_vis = target
+        st3.st3_decode_step(self.shape, arr, self.L, self.compact_mode, self.defer_mass)
+        return self.dec_out_all
+
     def finalize_mass(self, l: int):
         """Finishes the mass a deferred step left pending for layer l."""
         lc = self.layers[l]
         seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len)
-        mass_dst = lc.score if self.mode == "current" else lc.mass
+        mass_dst = self._mass_dst(lc)
         st3.st3_decode_mass_finalize(self.shape, lc.kv, seg, mass_dst, lc.ws)
         return mass_dst[:, :lc.h_vis]
 

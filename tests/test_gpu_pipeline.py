@@ -16,7 +16,8 @@ from workloads import decode_qkv, get_workload, prefill_qkv
 pytestmark = pytest.mark.gpu
 
 
-def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None, defer=False):
+def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None, defer=False,
+                     whole_step=False):
     T = w.steps if steps is None else steps
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
     keep_np = np.array(keep)
@@ -70,12 +71,19 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
         rho_before = [[x.copy() for x in ref.rho[l]] for l in range(w.layers)]
         ids_before = [[x.copy() for x in ref.ids[l]] for l in range(w.layers)]
         s = ref.decode_step(lambda l: dec[l])
-        for l in range(w.layers):
-            q, k, v = (to_dev(x, w.dtype) for x in dec[l])
-            out, mass = gen.decode_layer(l, t, q, k, v)
+        if whole_step:                              # one library call for all layers of the step
+            qkv = torch.stack([torch.stack([to_dev(x, w.dtype) for x in dec[l]]) for l in range(w.layers)]).contiguous()
+            outs = gen.decode_step(t, qkv)
             torch.cuda.synchronize()
-            got_o, got_m = to_np64(out), to_np64(mass)
+        for l in range(w.layers):
             lc = gen.layers[l]
+            if whole_step:
+                out, mass = outs[l], gen._mass_dst(lc)[:, :lc.h_vis]
+            else:
+                q, k, v = (to_dev(x, w.dtype) for x in dec[l])
+                out, mass = gen.decode_layer(l, t, q, k, v)
+                torch.cuda.synchronize()
+            got_o, got_m = to_np64(out), to_np64(mass)
             assert lc.vis_len.cpu().tolist() == [keep[l][t]] * B
             assert lc.kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, keep[l][t], w.n_txt, t)] * B
             assert lc.h_kv == s["kv_len"][l][0]
@@ -136,6 +144,20 @@ def test_13b_shape_cut_down_deferred_current():
     w = dataclasses.replace(get_workload("llava15_13b"), layers=4, heads=8, steps=10,
                             step_schedule={"kind": "cos", "tau": 10})
     _run_and_compare(w, 2, mode="current", defer=True)
+
+
+@pytest.mark.parametrize("defer", [False, True])
+def test_tiny_workload_whole_step_call(defer):
+    w = get_workload("tiny")
+    near, div = _run_and_compare(w, 2, defer=defer, whole_step=True)
+    assert not div.any()
+
+
+def test_many_layers_whole_step_call_current_mode():
+    """More layers than one plan launch takes (16), deferred mass feeding the next step's ranking."""
+    w = dataclasses.replace(get_workload("llava15_7b"), layers=19, heads=2, steps=5, n_vis=120, n_txt=9,
+                            step_schedule={"kind": "cos", "tau": 6})
+    _run_and_compare(w, 2, mode="current", defer=True, whole_step=True)
 
 
 def test_tiny_workload_batched_window():
