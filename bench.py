@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--no-unpruned", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="short run for counter collection: prefill, one plain 1 GiB device copy of known size, "
+                         "then the decode steps; prints the algorithmic bytes of each attend launch")
     return ap.parse_args()
 
 
@@ -136,6 +139,34 @@ def cpu_baseline(w, keep, T, budget_s):
                       f"cost is linear in B"}
 
 
+def pmc_probe(a, w, B, T, keep, torch, pipeline, st3):
+    """For `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: the same decode launches as the
+    benchmark (first T steps), preceded by a device-to-device copy of exactly 1 GiB whose counter
+    reading calibrates the counter's unit."""
+    job = Job(w, B, T, keep, torch, pipeline, st3)
+    job.run_prefill_only()
+    n = 1 << 30
+    src = torch.empty((n,), dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    src.fill_(1)
+    torch.cuda.synchronize()
+    dst.copy_(src)                  # the calibration kernel: reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    for t in range(1, T + 1):
+        job.gen.decode_step(t, job.dec[t - 1])
+    torch.cuda.synchronize()
+    e = 2 if w.dtype == "bf16" else 4
+    per_launch = []
+    for t in range(1, T + 1):
+        for l in range(w.layers):
+            lkv = w.n_sys + keep[l][t] + w.n_txt + t
+            per_launch.append(B * (2 * w.heads * w.head_dim * e * lkv + 2 * w.heads * w.head_dim * e + 4 * keep[l][t]))
+    print(json.dumps({"probe": "pmc", "workload": w.name, "batch": B, "decode_steps": T,
+                      "copy_bytes_read": n, "copy_bytes_written": n,
+                      "attend_launches": len(per_launch), "alg_bytes_per_launch_mean": sum(per_launch) / len(per_launch),
+                      "alg_bytes_first_launches": per_launch[:8]}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -157,6 +188,9 @@ def main():
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
     def note(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    if a.pmc_probe:
+        return pmc_probe(a, w, B, T, keep, torch, pipeline, st3)
 
     note(f"generating inputs for {w.name} B={B} T={T}")
     job = Job(w, B, T, keep, torch, pipeline, st3)
@@ -198,7 +232,7 @@ def main():
         achieved = alg / (tot_ms * 1e-3) / 1e9 if tot_ms > 0 else 0.0
         result["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                              "kernel": "decode_split_kernel", "launches": cnt,
+                              "kernel": "decode_attend_kernel", "launches": cnt,
                               "avg_launch_us": tot_ms * 1e3 / max(cnt, 1), "min_us": mn * 1e3, "max_us": mx * 1e3,
                               "alg_bytes_per_launch": alg / max(cnt, 1),
                               "kernel_time_share_of_job": tot_ms / ms_job}

@@ -50,7 +50,10 @@ inline float scale_log2(const st3_attn_shape* s) {
 // starts behind it and depends on the call's own sizes.
 // ---------------------------------------------------------------------------------------------
 constexpr int kMaxWindow = 16;
-constexpr int kDecodeTargetWgs = 1024;     // split the KV range until about this many workgroups exist
+#ifndef ST3_DECODE_TARGET_WGS
+#define ST3_DECODE_TARGET_WGS 1024
+#endif
+constexpr int kDecodeTargetWgs = ST3_DECODE_TARGET_WGS;     // split the KV range until about this many workgroups exist
 constexpr int kDecodeMaxSplit = 64;
 constexpr int kDecodeMinChunk = 64;        // never cut a (b,h) strip into chunks shorter than this
 

@@ -19,8 +19,14 @@
 #ifndef ST3_DECODE_U
 #define ST3_DECODE_U 8              // 16-byte loads of K (and of V) in flight per lane and tile
 #endif
+#ifndef ST3_DECODE_PIPELINED
+#define ST3_DECODE_PIPELINED 1      // 1: issue the next tile's loads before consuming the current one
+#endif
+#ifndef ST3_DECODE_THREADS
+#define ST3_DECODE_THREADS 256      // threads per workgroup of the attend kernel
+#endif
 #ifndef ST3_DECODE_MIN_BLOCKS
-#define ST3_DECODE_MIN_BLOCKS 4     // workgroups per CU the register budget must allow
+#define ST3_DECODE_MIN_BLOCKS 2     // workgroups per CU the register budget must allow
 #endif
 
 namespace st3 {
@@ -29,7 +35,7 @@ void profile_mark(hipStream_t st, bool after);     // st3_api.hip
 
 namespace {
 
-constexpr int kDecodeThreads = 256;
+constexpr int kDecodeThreads = ST3_DECODE_THREADS;
 constexpr int kDecodeWaves = kDecodeThreads / kWave;
 
 struct DecodeArgs {
@@ -97,14 +103,19 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
     const bool has_new = a.k_new != nullptr && c1 == len;       // this workgroup owns the appended row
     const int c1_cached = has_new ? c1 - 1 : c1;
     // waves take the tiles of the chunk round-robin, so all four stay busy to the end
-    wave_attend<T, D, U>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0,
+#if ST3_DECODE_PIPELINED
+    wave_attend_pipelined<T, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
+                                   c0, a.scale_l2, lane, st, lg, vis_lo, vis_hi);
+#else
+    wave_attend<T, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0,
                          a.scale_l2, lane, st, lg, vis_lo, vis_hi);
+#endif
     if (has_new && wave == 0) {
         // address the new token's rows as if they were cache row len-1
         const int64_t shift = (int64_t)(len - 1) * a.stride_t;
         const T* kn = reinterpret_cast<const T*>(a.k_new) + bh * D;
         const T* vn = reinterpret_cast<const T*>(a.v_new) + bh * D;
-        wave_attend<T, D, 1>(qf, kn - shift, vn - shift, a.stride_t, len - 1, len, M::RPL, len - 1, a.scale_l2, lane,
+        wave_attend<T, D, 1, false>(qf, kn - shift, vn - shift, a.stride_t, len - 1, len, M::RPL, len - 1, a.scale_l2, lane,
                              st, lg, vis_lo, vis_hi);
         if (lane < 2 * LPR) {
             const int c = (lane % LPR) * EPL;

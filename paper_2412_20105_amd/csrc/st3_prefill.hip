@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillArgs a) {
     float* lg = nullptr;
     if (a.pre_logits && w_idx >= 0) lg = a.pre_logits + (bh * a.window + w_idx) * a.vis_len;
     // K and V may have different strides; wave_attend takes one stride, so require equality here
-    wave_attend<T, D, 4>(qf, kbase, vbase, a.k_st, 0, i + 1, 4 * M::RPL, 0, a.scale_l2, lane, st, lg, a.sys_len,
+    wave_attend<T, D, 4, false>(qf, kbase, vbase, a.k_st, 0, i + 1, 4 * M::RPL, 0, a.scale_l2, lane, st, lg, a.sys_len,
                          a.sys_len + a.vis_len);
     finish_wave<T, D>(st);
     if (lane < LPR) {
