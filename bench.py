@@ -230,8 +230,17 @@ def main():
         tot_ms, cnt, mn, mx = st3.st3_profile_read()
         alg = job.decode_kernel_bytes()
         achieved = alg / (tot_ms * 1e-3) / 1e9 if tot_ms > 0 else 0.0
+        traffic = None
+        try:        # HBM bytes per launch from the committed counter runs, when they cover this workload
+            with open(os.path.join(ROOT, "paper_2412_20105_amd", "measured_traffic.json")) as f:
+                mt = json.load(f)["decode_attend_kernel"]
+            if mt["workload"] == w.name and mt["batch"] == B:
+                # measured over the first decode steps: scale the ratio to this job's mean launch
+                traffic = mt["traffic_over_algorithmic"] * alg / max(cnt, 1)
+        except (OSError, KeyError, ValueError):
+            traffic = None
         result["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                              "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                               "kernel": "decode_attend_kernel", "launches": cnt,
                               "avg_launch_us": tot_ms * 1e3 / max(cnt, 1), "min_us": mn * 1e3, "max_us": mx * 1e3,
                               "alg_bytes_per_launch": alg / max(cnt, 1),

@@ -1,0 +1,94 @@
+// Streaming read / copy bandwidth of the device, for reference against the decode kernel.
+#include <hip/hip_runtime.h>
+#include <cstdio>
+#include <vector>
+#define CK(x) do { hipError_t e = (x); if (e != hipSuccess) { printf("err %s line %d\n", hipGetErrorString(e), __LINE__); return 1; } } while (0)
+
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+template <int U>
+__global__ __launch_bounds__(256) void read_nt_kernel(const u32x4_t* __restrict__ p, size_t nvec, uint32_t* sink) {
+    size_t i = (size_t)blockIdx.x * 256 * U + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * 256 * U;
+    uint32_t acc = 0;
+    for (; i + (size_t)256 * (U - 1) < nvec; i += stride) {
+        u32x4_t v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(p + i + (size_t)256 * u);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x12345678u) sink[0] = acc;
+}
+template <int U>
+__global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ p, size_t nvec, uint32_t* sink) {
+    size_t i = (size_t)blockIdx.x * 256 * U + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * 256 * U;
+    uint32_t acc = 0;
+    for (; i + (size_t)256 * (U - 1) < nvec; i += stride) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = p[i + (size_t)256 * u];
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x12345678u) sink[0] = acc;
+}
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ p, uint4* __restrict__ q, size_t nvec) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * 256;
+    for (; i < nvec; i += stride) q[i] = p[i];
+}
+int main() {
+    size_t bytes = (size_t)1 << 30;
+    uint4 *a, *b; uint32_t* sink;
+    CK(hipMalloc(&a, bytes)); CK(hipMalloc(&b, bytes)); CK(hipMalloc(&sink, 4));
+    CK(hipMemset(a, 1, bytes)); CK(hipMemset(b, 2, bytes));
+    size_t nvec = bytes / 16;
+    hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
+    int grids[] = {256 * 4, 256 * 8, 256 * 16, 256 * 32, 256 * 64, (int)(nvec / 256 / 8)};
+    for (int g : grids) {
+        for (int rep = 0; rep < 2; ++rep) read_kernel<8><<<g, 256>>>(a, nvec, sink);
+        hipEventRecord(e0);
+        for (int rep = 0; rep < 10; ++rep) read_kernel<8><<<g, 256>>>(a, nvec, sink);
+        hipEventRecord(e1); hipEventSynchronize(e1);
+        float ms; hipEventElapsedTime(&ms, e0, e1);
+        printf("read U=8 grid=%7d : %.1f GB/s\n", g, bytes * 10 / (ms * 1e-3) / 1e9);
+    }
+    for (int g : grids) {
+        hipEventRecord(e0);
+        for (int rep = 0; rep < 10; ++rep) read_kernel<4><<<g, 256>>>(a, nvec, sink);
+        hipEventRecord(e1); hipEventSynchronize(e1);
+        float ms; hipEventElapsedTime(&ms, e0, e1);
+        printf("read U=4 grid=%7d : %.1f GB/s\n", g, bytes * 10 / (ms * 1e-3) / 1e9);
+    }
+    for (int g : grids) {
+        hipEventRecord(e0);
+        for (int rep = 0; rep < 10; ++rep) read_nt_kernel<8><<<g, 256>>>((const u32x4_t*)a, nvec, sink);
+        hipEventRecord(e1); hipEventSynchronize(e1);
+        float ms; hipEventElapsedTime(&ms, e0, e1);
+        printf("read NT U=8 grid=%7d : %.1f GB/s\n", g, bytes * 10 / (ms * 1e-3) / 1e9);
+    }
+    // smaller working sets (like one decode launch: ~400 MB)
+    for (size_t mb : {100, 200, 400}) {
+        size_t nv = mb * 1024 * 1024 / 16;
+        int g = (int)(nv / 256 / 8);
+        hipEventRecord(e0);
+        for (int rep = 0; rep < 20; ++rep) read_kernel<8><<<g, 256>>>(a + (rep % 2) * nv, nv, sink);
+        hipEventRecord(e1); hipEventSynchronize(e1);
+        float ms; hipEventElapsedTime(&ms, e0, e1);
+        printf("read %zu MB per launch, one pass grid=%d : %.1f GB/s (%.1f us/launch)\n", mb, g, (double)nv * 16 * 20 / (ms * 1e-3) / 1e9, ms * 1e3 / 20);
+    }
+    for (int g : {256 * 8, 256 * 32, (int)(nvec / 256)}) {
+        hipEventRecord(e0);
+        for (int rep = 0; rep < 10; ++rep) copy_kernel<<<g, 256>>>(a, b, nvec);
+        hipEventRecord(e1); hipEventSynchronize(e1);
+        float ms; hipEventElapsedTime(&ms, e0, e1);
+        printf("copy grid=%7d : %.1f GB/s (read+write)\n", g, 2.0 * bytes * 10 / (ms * 1e-3) / 1e9);
+    }
+    hipEventRecord(e0);
+    for (int rep = 0; rep < 10; ++rep) hipMemcpyAsync(b, a, bytes, hipMemcpyDeviceToDevice, 0);
+    hipEventRecord(e1); hipEventSynchronize(e1);
+    float ms; hipEventElapsedTime(&ms, e0, e1);
+    printf("hipMemcpy D2D : %.1f GB/s (read+write)\n", 2.0 * bytes * 10 / (ms * 1e-3) / 1e9);
+    return 0;
+}
