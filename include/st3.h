@@ -280,10 +280,10 @@ ST3_EXPORT int64_t st3_kv_bytes(int32_t batch, int32_t heads, int32_t head_dim, 
                      int32_t L);
 
 /* ---------------------------------------------------------------------------------------------
- * Diagnostics: timing of the split-KV decode kernel (the kernel that streams K and V).
- * st3_profile_enable(n) creates (host-side) hipEvents for up to n launches and makes
- * st3_decode_attention / st3_decode_layer_step record one event right before and one right after
- * that kernel on the caller's stream; recording stops silently once n launches are used.
+ * Diagnostics: timing of the decode attention kernel (the kernel that streams K and V).
+ * st3_profile_enable(n) creates (host-side) hipEvents for up to n launches and makes the decode
+ * calls launch that kernel with an event pair attached that receives the kernel's own start and
+ * end on the caller's stream; this stops silently once n launches are used.
  * st3_profile_read waits for the recorded events, returns the summed / min / max kernel time in
  * milliseconds and the number of launches timed, and switches recording off.  HOST pointers, any
  * may be NULL.  Not thread-safe; intended for benchmarks.

@@ -11,8 +11,8 @@ static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 
 // ---------------------------------------------------------------------------------------------
-// Optional timing of the split-KV decode kernel: a pool of hipEvent pairs recorded on the
-// caller's stream right before and right after that kernel.  Off unless st3_profile_enable().
+// Optional timing of the decode attention kernel: a pool of hipEvent pairs attached to that
+// kernel's launches (start and stop of the kernel itself).  Off unless st3_profile_enable().
 // ---------------------------------------------------------------------------------------------
 struct DecodeProfiler {
     std::vector<hipEvent_t> ev;     // 2 per launch
@@ -21,11 +21,15 @@ struct DecodeProfiler {
 };
 static DecodeProfiler g_prof;
 
-void profile_mark(hipStream_t st, bool after) {
-    if (!g_prof.on) return;
-    if (!after && (g_prof.used + 1) * 2 > g_prof.ev.size()) { g_prof.on = false; return; }   // pool exhausted
-    (void)hipEventRecord(g_prof.ev[g_prof.used * 2 + (after ? 1 : 0)], st);
-    if (after) g_prof.used += 1;
+// Hands out the next event pair; the caller passes it to hipExtLaunchKernelGGL, which stamps the
+// two events with the kernel's own start and end.
+bool profile_take(hipEvent_t* start, hipEvent_t* stop) {
+    if (!g_prof.on) return false;
+    if ((g_prof.used + 1) * 2 > g_prof.ev.size()) { g_prof.on = false; return false; }      // pool exhausted
+    *start = g_prof.ev[g_prof.used * 2];
+    *stop = g_prof.ev[g_prof.used * 2 + 1];
+    g_prof.used += 1;
+    return true;
 }
 
 st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);

@@ -14,6 +14,8 @@
 //
 // No kernel here communicates between workgroups of one launch: device-scope fences cost a
 // write-back and invalidate of the XCD-private L2 on this part and were measured to be ruinous.
+#include <hip/hip_ext.h>
+
 #include "st3_decode.h"
 
 #ifndef ST3_DECODE_U
@@ -31,7 +33,7 @@
 
 namespace st3 {
 
-void profile_mark(hipStream_t st, bool after);     // st3_api.hip
+bool profile_take(hipEvent_t* start, hipEvent_t* stop);     // st3_api.hip
 
 namespace {
 
@@ -236,9 +238,12 @@ __global__ void bump_len_kernel(int32_t* kv_len, int32_t B, int32_t capacity) {
 
 template <typename T, int D>
 void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
-    profile_mark(st, false);
-    decode_attend_kernel<T, D, ST3_DECODE_U><<<dim3(da.nsplit, da.H, B), kDecodeThreads, 0, st>>>(da);
-    profile_mark(st, true);
+    hipEvent_t e0, e1;
+    if (profile_take(&e0, &e1))     // timed launch: the events receive the kernel's own start and end
+        hipExtLaunchKernelGGL((decode_attend_kernel<T, D, ST3_DECODE_U>), dim3(da.nsplit, da.H, B),
+                              dim3(kDecodeThreads), 0, st, e0, e1, 0, da);
+    else
+        decode_attend_kernel<T, D, ST3_DECODE_U><<<dim3(da.nsplit, da.H, B), kDecodeThreads, 0, st>>>(da);
 }
 
 template <typename T, int D>

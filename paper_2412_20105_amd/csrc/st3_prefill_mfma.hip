@@ -26,6 +26,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBM = 128;            // queries per workgroup
 constexpr int kBN = 64;             // keys per tile
@@ -33,17 +34,76 @@ constexpr int kVPad = kBN + 2;      // Vt row stride in elements: 33 words, so c
 
 union Frag {
     bf16x8 v;
-    uint4 u4;
+    u32x4 u4;
     uint32_t w[4];
 };
 
+template <int NK, int NV>
+struct TileRegs {
+    u32x4 k[NK], va[NV], vb[NV];
+};
+
+// Issues the global loads of the K/V tile that starts at key k0 (rows past n-1 are clamped).
+template <int D, int NK, int NV>
+__device__ __forceinline__ void fetch_tile(TileRegs<NK, NV>& t, const uint16_t* Kp, const uint16_t* Vp, int64_t k_st,
+                                           int64_t v_st, int k0, int n, int tid) {
+    constexpr int VPR = D / 8;
+#pragma unroll
+    for (int i = 0; i < NK; ++i) {
+        const int vec = tid + 256 * i;
+        const int key = min(k0 + vec / VPR, n - 1);
+        t.k[i] = *reinterpret_cast<const u32x4*>(Kp + (int64_t)key * k_st + (vec % VPR) * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int item = tid + 256 * i;
+        const int cv = item % VPR, kp = item / VPR;
+        const int key_a = min(k0 + 2 * kp, n - 1), key_b = min(k0 + 2 * kp + 1, n - 1);
+        t.va[i] = *reinterpret_cast<const u32x4*>(Vp + (int64_t)key_a * v_st + cv * 8);
+        t.vb[i] = *reinterpret_cast<const u32x4*>(Vp + (int64_t)key_b * v_st + cv * 8);
+    }
+}
+
+__device__ __forceinline__ void put_pair(uint16_t* Vt, int col, int kp, uint32_t wa, uint32_t wb) {
+    *reinterpret_cast<uint32_t*>(&Vt[col * kVPad + 2 * kp]) = (wa & 0xffffu) | (wb << 16);              // (key_a, key_b)
+    *reinterpret_cast<uint32_t*>(&Vt[(col + 1) * kVPad + 2 * kp]) = (wa >> 16) | (wb & 0xffff0000u);
+}
+
+// Writes the staged tile to LDS: K row-major (padded), V transposed (a thread holds 2 adjacent
+// keys x 8 columns and writes 8 words, one per column).
+template <int D, int NK, int NV>
+__device__ __forceinline__ void stage_tile(const TileRegs<NK, NV>& t, uint16_t* Ks, uint16_t* Vt, int tid) {
+    constexpr int VPR = D / 8, KPAD = D + 8;
+#pragma unroll
+    for (int i = 0; i < NK; ++i) {
+        const int vec = tid + 256 * i;
+        *reinterpret_cast<u32x4*>(&Ks[(vec / VPR) * KPAD + (vec % VPR) * 8]) = t.k[i];
+    }
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int item = tid + 256 * i;
+        const int cv = item % VPR, kp = item / VPR;
+        put_pair(Vt, cv * 8 + 0, kp, t.va[i].x, t.vb[i].x);
+        put_pair(Vt, cv * 8 + 2, kp, t.va[i].y, t.vb[i].y);
+        put_pair(Vt, cv * 8 + 4, kp, t.va[i].z, t.vb[i].z);
+        put_pair(Vt, cv * 8 + 6, kp, t.va[i].w, t.vb[i].w);
+    }
+}
+
 // grid (ceil(n/128), H, B); x reversed so the longest query tiles start first.
+// Register budget: two waves per SIMD (256 registers each), so that one wave's softmax VALU work
+// overlaps the other's MFMAs.  The 64-key LDS tile is consumed as two 32-key halves, each with its
+// own online-softmax update, which halves the live S/P registers; the accumulator is only rescaled
+// when some row's maximum actually moved.  The next tile's global loads are issued before the
+// current tile is consumed and written to LDS after it.
 template <int D>
-__global__ __launch_bounds__(256) void prefill_mfma_kernel(PrefillArgs a) {
+__global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
     constexpr int KS = D / 16;          // contraction steps of S^T
     constexpr int DT = D / 32;          // 32-row tiles of O^T
     constexpr int KPAD = D + 8;         // K row stride in LDS (elements)
     constexpr int VPR = D / 8;          // 16-byte vectors per row
+    constexpr int KV_K = kBN * VPR / 256;           // K vectors staged per thread and tile
+    constexpr int KV_V = (kBN / 2) * VPR / 256;     // V key-pair items per thread and tile
     __shared__ __attribute__((aligned(16))) uint16_t Ks[kBN * KPAD];
     __shared__ __attribute__((aligned(16))) uint16_t Vt[D * kVPad];
 
@@ -64,7 +124,7 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(PrefillArgs a) {
     {
         const uint16_t* qrow = Qp + (int64_t)min(myq, n - 1) * a.q_st;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) qf[s].u4 = *reinterpret_cast<const uint4*>(qrow + 16 * s + 8 * g);
+        for (int s = 0; s < KS; ++s) qf[s].u4 = *reinterpret_cast<const u32x4*>(qrow + 16 * s + 8 * g);
     }
     f32x16 oacc[DT];
 #pragma unroll
@@ -79,106 +139,75 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(PrefillArgs a) {
     const bool lane_in_window = wave_has_window && w_idx >= 0 && myq < n;
     float* lg_row = lane_in_window ? a.pre_logits + (bh * a.window + w_idx) * a.vis_len : nullptr;
 
+    // global -> register staging of one K/V tile (rows past the end are clamped and masked later)
+    TileRegs<KV_K, KV_V> tr;
     const int k_end = min(n, qt * kBM + kBM);           // keys this workgroup can see
+    fetch_tile<D>(tr, Kp, Vp, a.k_st, a.v_st, 0, n, tid);
     for (int k0 = 0; k0 < k_end; k0 += kBN) {
         __syncthreads();                                // previous tile fully consumed
-        // ---- stage K tile: kBN rows x D, 16 bytes per thread and step, coalesced -------------
-#pragma unroll
-        for (int i = 0; i < kBN * VPR / 256; ++i) {
-            const int vec = tid + 256 * i;
-            const int row = vec / VPR, cv = vec % VPR;
-            const int key = min(k0 + row, n - 1);
-            const uint4 val = *reinterpret_cast<const uint4*>(Kp + (int64_t)key * a.k_st + cv * 8);
-            *reinterpret_cast<uint4*>(&Ks[row * KPAD + cv * 8]) = val;
-        }
-        // ---- stage V tile transposed: a thread takes 2 adjacent keys x 8 columns --------------
-#pragma unroll
-        for (int i = 0; i < (kBN / 2) * VPR / 256; ++i) {
-            const int item = tid + 256 * i;
-            const int cv = item % VPR, kp = item / VPR;
-            const int key_a = min(k0 + 2 * kp, n - 1), key_b = min(k0 + 2 * kp + 1, n - 1);
-            const uint4 va = *reinterpret_cast<const uint4*>(Vp + (int64_t)key_a * a.v_st + cv * 8);
-            const uint4 vb = *reinterpret_cast<const uint4*>(Vp + (int64_t)key_b * a.v_st + cv * 8);
-            const uint32_t wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t lo = (wa[e] & 0xffffu) | (wb[e] << 16);          // column 2e:   (key_a, key_b)
-                const uint32_t hi = (wa[e] >> 16) | (wb[e] & 0xffff0000u);      // column 2e+1
-                *reinterpret_cast<uint32_t*>(&Vt[(cv * 8 + 2 * e) * kVPad + 2 * kp]) = lo;
-                *reinterpret_cast<uint32_t*>(&Vt[(cv * 8 + 2 * e + 1) * kVPad + 2 * kp]) = hi;
-            }
-        }
+        stage_tile<D>(tr, Ks, Vt, tid);
         __syncthreads();
+        if (k0 + kBN < k_end) fetch_tile<D>(tr, Kp, Vp, a.k_st, a.v_st, k0 + kBN, n, tid);   // in flight while this tile is consumed
         if (k0 > q0 + 31) continue;                     // tile entirely above this wave's diagonal
 
-        // ---- S^T = K Q^T ------------------------------------------------------------------------
-        f32x16 sacc[2];
-        const bool sub_live[2] = {true, k0 + 32 <= q0 + 31};
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
+            const int ks0 = k0 + 32 * sub;
+            if (ks0 > q0 + 31) break;                   // this half is above the diagonal too
+            // ---- S^T = K Q^T for 32 keys ------------------------------------------------------
+            f32x16 sacc;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
-            if (sub_live[sub]) {
+            for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
-                for (int s = 0; s < KS; ++s) {
-                    Frag ka;
-                    ka.u4 = *reinterpret_cast<const uint4*>(&Ks[(32 * sub + c) * KPAD + 16 * s + 8 * g]);
-                    sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, qf[s].v, sacc[sub], 0, 0, 0);
-                }
+            for (int s = 0; s < KS; ++s) {
+                Frag ka;
+                ka.u4 = *reinterpret_cast<const u32x4*>(&Ks[(32 * sub + c) * KPAD + 16 * s + 8 * g]);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, qf[s].v, sacc, 0, 0, 0);
             }
-        }
-        // ---- scale, causal / length mask, row maximum ---------------------------------------
-        float mx = -INFINITY;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+            // ---- scale, causal / length mask, row maximum -----------------------------------
+            float mx = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int key = k0 + 32 * sub + 8 * (r / 4) + 4 * g + (r % 4);
-                float s = sacc[sub][r] * a.scale_l2;
-                if (key > myq || key >= n || !sub_live[sub]) s = -INFINITY;
-                sacc[sub][r] = s;
+                const int key = ks0 + 8 * (r / 4) + 4 * g + (r % 4);
+                float s = sacc[r] * a.scale_l2;
+                if (key > myq || key >= n) s = -INFINITY;
+                sacc[r] = s;
                 mx = fmaxf(mx, s);
             }
-        if (wave_has_window) {
-            if (lg_row != nullptr) {
+            if (wave_has_window && lg_row != nullptr) {
 #pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = k0 + 32 * sub + 8 * (r / 4) + 4 * g + (r % 4);
-                        if (key >= a.sys_len && key < a.sys_len + a.vis_len && key <= myq)
-                            lg_row[key - a.sys_len] = sacc[sub][r];
-                    }
+                for (int r = 0; r < 16; ++r) {
+                    const int key = ks0 + 8 * (r / 4) + 4 * g + (r % 4);
+                    if (key >= a.sys_len && key < a.sys_len + a.vis_len && key <= myq) lg_row[key - a.sys_len] = sacc[r];
+                }
             }
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // every row sees key k0 (k0 <= q0 <= myq, k0 < n), so the maximum is finite
-        const float m_new = fmaxf(m_i, mx);
-        const float alpha = exp2_fast(m_i - m_new);
-        m_i = m_new;
-        float psum = 0.f;
-        Frag pb[2][2], pl[2][2];
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            // The first half of a tile always holds a visible key for every row (k0 <= q0 <= myq);
+            // the second half may be entirely masked for some rows, then mx = -inf and m stays.
+            const float m_new = fmaxf(m_i, mx);
+            const bool moved = m_new > m_i;
+            const float alpha = exp2_fast(m_i - m_new);     // m_i = -inf only before the first key: alpha = 0
+            m_i = m_new;
+            float psum = 0.f;
+            Frag pb[2], pl[2];
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const float p = exp2_fast(sacc[sub][8 * kk + j] - m_new);
+                    const float p = exp2_fast(sacc[8 * kk + j] - m_new);
                     psum += p;
                     const __bf16 hi = (__bf16)p;
-                    pb[sub][kk].v[j] = hi;
-                    pl[sub][kk].v[j] = (__bf16)(p - (float)hi);
+                    pb[kk].v[j] = hi;
+                    pl[kk].v[j] = (__bf16)(p - (float)hi);
                 }
-        l_i = l_i * alpha + psum;
+            l_i = l_i * alpha + psum;
+            if (__any(moved)) {                         // rescale only when some row's maximum moved
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+                for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-        // ---- O^T += V^T P^T ---------------------------------------------------------------------
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            if (!sub_live[sub]) continue;
+                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+            }
+            // ---- O^T += V^T P^T ---------------------------------------------------------------
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
                 const int base = 32 * sub + 16 * kk + 4 * g;
@@ -190,8 +219,8 @@ __global__ __launch_bounds__(256) void prefill_mfma_kernel(PrefillArgs a) {
                     va.w[1] = *reinterpret_cast<const uint32_t*>(row + 2);
                     va.w[2] = *reinterpret_cast<const uint32_t*>(row + 8);
                     va.w[3] = *reinterpret_cast<const uint32_t*>(row + 10);
-                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb[sub][kk].v, oacc[dt], 0, 0, 0);
-                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pl[sub][kk].v, oacc[dt], 0, 0, 0);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb[kk].v, oacc[dt], 0, 0, 0);
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pl[kk].v, oacc[dt], 0, 0, 0);
                 }
             }
         }
