@@ -35,6 +35,14 @@ def parse():
     ap.add_argument("--no-unpruned", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--layer-schedule", default="workload", choices=["workload", "linear", "pvtp", "full"],
+                    help="retention over layers: the workload's own, or the paper's strided PVTP (Alg. 1, Eq. 9)")
+    ap.add_argument("--stride", type=int, default=4, help="PVTP stride S")
+    ap.add_argument("--R-bp", type=int, default=500, help="PVTP ratio R removed per later event, basis points")
+    ap.add_argument("--P-bp", type=int, default=5000, help="PVTP ratio P removed at the first event, basis points")
+    ap.add_argument("--step-schedule", default="workload", choices=["workload", "cos", "linear", "exp", "none"],
+                    help="attenuation over decode steps (Eq. 8 / Sec. 4.4)")
+    ap.add_argument("--tau", type=float, default=0.0, help="tau (cos, linear) or sigma (exp); 0 = decode steps")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="short run for counter collection: prefill, one plain 1 GiB device copy of known size, "
                          "then the decode steps; prints the algorithmic bytes of each attend launch")
@@ -184,6 +192,19 @@ def main():
     st3.lib()                                   # fail loudly if the library is not built
     w = get_workload(a.workload)
     T = a.decode_steps or w.steps
+    import dataclasses
+    if a.layer_schedule == "pvtp":
+        w = dataclasses.replace(w, layer_schedule={"kind": "pvtp", "S": a.stride, "P_bp": a.P_bp, "R_bp": a.R_bp})
+    elif a.layer_schedule == "full":
+        w = dataclasses.replace(w, layer_schedule={"kind": "full"})
+    elif a.layer_schedule == "linear":
+        w = dataclasses.replace(w, layer_schedule={"kind": "linear", "last_full_layer": 2, "end_ratio_bp": 1000})
+    if a.step_schedule != "workload":
+        par = a.tau or float(T)
+        ss = {"cos": {"kind": "cos", "tau": par}, "linear": {"kind": "linear", "tau": par},
+              "exp": {"kind": "exp", "sigma": par}, "none": {"kind": "none"}}[a.step_schedule]
+        w = dataclasses.replace(w, step_schedule=ss)
+    w = dataclasses.replace(w, steps=T)
     B = a.batch
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
     def note(msg):
@@ -212,7 +233,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: L={w.layers} H={w.heads} d={w.head_dim} {w.dtype}, prompt "
                                f"{w.n_sys}+{w.n_vis}+{w.n_txt}, T={T} decode steps, batch {B}, "
-                               f"schedule {w.layer_schedule['kind']}/{w.step_schedule['kind']}",
+                               f"schedule {w.layer_schedule}/{w.step_schedule}",
                    "batch": B, "decode_steps": T, "step_definition": "prefill (all layers, PVTP) + T decode steps (VTA)"},
         "prefill_ms": ms_prefill,
         "decode_ms_per_token_step": (ms_job - ms_prefill) / T,
@@ -250,7 +271,6 @@ def main():
     # -- the same kernels without pruning ---------------------------------------------------------------
     if not a.no_unpruned:
         note("unpruned run")
-        import dataclasses
         wu = dataclasses.replace(w, layer_schedule={"kind": "full"}, step_schedule={"kind": "none"})
         keep_u = [row[:T + 1] for row in pipeline.keep_table_for(wu)]
         del job.gen

@@ -280,6 +280,28 @@ ST3_EXPORT int64_t st3_kv_bytes(int32_t batch, int32_t heads, int32_t head_dim, 
                      int32_t L);
 
 /* ---------------------------------------------------------------------------------------------
+ * Diagnostics on score (mass) vectors, as the paper uses them to motivate the method.
+ *
+ * st3_overlap_topk - Eq. 10: overlap[b] = |TopK(a) ^ TopK(b)| and topk_a[b] = |TopK(a)|, where
+ *   TopK(x) is the set of token ids of the k best entries of x under the order of st3_select_topk
+ *   (Overlap_n is their quotient).  a and b are score vectors with id columns (DEVICE, row b at
+ *   +b*stride, n_x_dev[b] valid entries or n_x when the pointer is NULL); they may hold different
+ *   token sets in different orders, e.g. the same layer's mass at two decode steps.
+ *   ids in [0, id_space), id_space <= 16384, n <= 8192.
+ * st3_cosine_similarity - Eq. 4-5: cosine[b] = <a,b> / (|a| |b|), entries matched by token id
+ *   (ids NULL: by position); a token missing on one side counts as zero there.  Zero vectors give 0.
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_overlap_topk(const float* score_a, const int32_t* ids_a, int64_t stride_a,
+                                       const int32_t* n_a_dev, int32_t n_a, const float* score_b,
+                                       const int32_t* ids_b, int64_t stride_b, const int32_t* n_b_dev, int32_t n_b,
+                                       int32_t batch, int32_t k, int32_t id_space, int32_t* overlap, int32_t* topk_a,
+                                       void* stream);
+ST3_EXPORT st3_status st3_cosine_similarity(const float* va, const int32_t* ids_a, int64_t stride_a,
+                                            const int32_t* n_a_dev, int32_t n_a, const float* vb,
+                                            const int32_t* ids_b, int64_t stride_b, const int32_t* n_b_dev,
+                                            int32_t n_b, int32_t batch, int32_t id_space, float* cosine, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Diagnostics: timing of the decode attention kernel (the kernel that streams K and V).
  * st3_profile_enable(n) creates (host-side) hipEvents for up to n launches and makes the decode
  * calls launch that kernel with an event pair attached that receives the kernel's own start and

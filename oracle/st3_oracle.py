@@ -23,6 +23,7 @@ What is defined here, and the passage each part follows:
 * `keep_linear`, `keep_anneal`            - the benchmark's linear-over-layers
   schedule and Eq. 7 (count = |V^{l,0}| * beta^t, floored).
 * `kv_bytes`                              - closed-form KV-cache size.
+* `overlap`, `cosine_similarity`          - Eq. 10 and Eq. 4-5 (diagnostics).
 * `Generation`                            - Alg. 3 end to end on given Q/K/V:
   prefill with progressive pruning, then decode steps with annealing.
 
@@ -147,6 +148,36 @@ def ranked_order(scores, ids) -> np.ndarray:
     scores = np.asarray(scores, F64)
     n = scores.shape[0]
     return np.array(sorted(range(n), key=lambda i: (-scores[i], int(ids[i]))), dtype=np.int64)
+
+
+# ---------------------------------------------------------------------------
+# Eq. 10 and Eq. 4-5: diagnostics on score vectors
+# ---------------------------------------------------------------------------
+def topk_id_set(scores, ids, k: int) -> set:
+    """Token ids of the k best entries (same total order as select_topk)."""
+    ids = np.asarray(ids)
+    return set(int(ids[p]) for p in select_topk(scores, ids, min(k, len(ids))))
+
+
+def overlap(scores_1, ids_1, scores_n, ids_n, k: int) -> float:
+    """Eq. 10: |TopK(T_1) & TopK(T_n)| / |TopK(T_1)|."""
+    a = topk_id_set(scores_1, ids_1, k)
+    b = topk_id_set(scores_n, ids_n, k)
+    return len(a & b) / len(a)
+
+
+def cosine_similarity(sa, ids_a, sb, ids_b) -> float:
+    """Eq. 4-5: cosine similarity of two score vectors, entries matched by token id; a token
+    present on one side only counts as zero on the other."""
+    sa = np.asarray(sa, F64); sb = np.asarray(sb, F64)
+    where_b = {int(t): j for j, t in enumerate(ids_b)}
+    dot = 0.0
+    for i, t in enumerate(ids_a):
+        j = where_b.get(int(t))
+        if j is not None:
+            dot += sa[i] * sb[j]
+    na, nb = math.sqrt(float(sa @ sa)), math.sqrt(float(sb @ sb))
+    return dot / (na * nb) if na > 0 and nb > 0 else 0.0
 
 
 # ---------------------------------------------------------------------------

@@ -29,7 +29,8 @@ EXPORTED = [
     "st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_select_topk",
     "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
     "st3_decode_mass_finalize", "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
-    "st3_debug_set_prefill_path", "st3_profile_enable", "st3_profile_read",
+    "st3_debug_set_prefill_path", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
+    "st3_cosine_similarity",
 ]
 
 
@@ -117,6 +118,14 @@ def lib() -> C.CDLL:
                      "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step",
                      "st3_decode_mass_finalize", "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal"):
             getattr(L, name).restype = C.c_int
+        L.st3_overlap_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                       C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                       C.c_void_p, C.c_void_p]
+        L.st3_overlap_topk.restype = C.c_int
+        L.st3_cosine_similarity.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p,
+                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                            C.c_void_p, C.c_void_p]
+        L.st3_cosine_similarity.restype = C.c_int
         L.st3_profile_enable.argtypes = [C.c_int32]
         L.st3_profile_enable.restype = C.c_int
         L.st3_profile_read.argtypes = [P(C.c_double), P(C.c_int64), P(C.c_double), P(C.c_double)]
@@ -293,6 +302,20 @@ def st3_schedule_anneal(kind, param, T, keep_l0):
 def st3_kv_bytes(batch, heads, head_dim, dtype, kv_lens):
     arr = (C.c_int32 * len(kv_lens))(*kv_lens)
     return lib().st3_kv_bytes(batch, heads, head_dim, dtype, arr, len(kv_lens))
+
+
+def st3_overlap_topk(score_a, ids_a, n_a, score_b, ids_b, n_b, k, id_space, overlap, topk_a, n_a_dev=None,
+                     n_b_dev=None, stream=None):
+    _check(lib().st3_overlap_topk(score_a.data_ptr(), ids_a.data_ptr(), score_a.stride(0), _ptr(n_a_dev), n_a,
+                                  score_b.data_ptr(), ids_b.data_ptr(), score_b.stride(0), _ptr(n_b_dev), n_b,
+                                  score_a.shape[0], k, id_space, overlap.data_ptr(), topk_a.data_ptr(),
+                                  _stream(stream)), "st3_overlap_topk")
+
+
+def st3_cosine_similarity(va, ids_a, n_a, vb, ids_b, n_b, id_space, cosine, n_a_dev=None, n_b_dev=None, stream=None):
+    _check(lib().st3_cosine_similarity(va.data_ptr(), _ptr(ids_a), va.stride(0), _ptr(n_a_dev), n_a, vb.data_ptr(),
+                                       _ptr(ids_b), vb.stride(0), _ptr(n_b_dev), n_b, va.shape[0], id_space,
+                                       cosine.data_ptr(), _stream(stream)), "st3_cosine_similarity")
 
 
 def st3_profile_enable(max_launches: int) -> None:

@@ -482,9 +482,9 @@ __global__ __launch_bounds__(256) void evict_apply_kernel(ApplyArgs a) {
 st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
 
 // Rows are moved inside the plan kernel when the mode is HOLE_FILL and at most kInlineEvict rows
-// can be evicted per sequence (one workgroup then moves a few dozen rows per strip); larger
+// can be evicted per sequence (one workgroup then moves at most ~100 rows on each strip); larger
 // evictions and STABLE mode go through evict_apply_kernel, which has a workgroup per strip.
-constexpr int kInlineEvict = 8;
+constexpr int kInlineEvict = 48;
 
 namespace {
 
@@ -584,7 +584,136 @@ st3_status enqueue_plan_layers(const st3_attn_shape* shape, int n, const st3_lay
     return check_launch();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Diagnostics on mass vectors: Overlap_n (Eq. 10) and cosine similarity (Eq. 4-5).
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int kDiagIdSpace = 16384;
+
+struct OverlapArgs {
+    const float* score_a; const int32_t* ids_a; int64_t stride_a; const int32_t* n_a_dev; int32_t n_a;
+    const float* score_b; const int32_t* ids_b; int64_t stride_b; const int32_t* n_b_dev; int32_t n_b;
+    int32_t k, id_space;
+    int32_t* overlap;       // [B] |TopK(a) ^ TopK(b)|
+    int32_t* topk_a;        // [B] |TopK(a)| = min(k, n_a[b])
+};
+
+// One workgroup per sequence.  TopK(a) is marked in an LDS bitmap indexed by token id; the
+// members of TopK(b) whose id is marked are counted.
+__global__ __launch_bounds__(kSelThreads) void overlap_topk_kernel(OverlapArgs a) {
+    __shared__ SelShared sm;
+    __shared__ uint32_t seen[kDiagIdSpace / 32];
+    __shared__ int sm_count;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    for (int i = tid; i < kDiagIdSpace / 32; i += kSelThreads) seen[i] = 0u;
+    if (tid == 0) sm_count = 0;
+    __syncthreads();
+    for (int side = 0; side < 2; ++side) {
+        const float* scores = (side ? a.score_b + b * a.stride_b : a.score_a + b * a.stride_a);
+        const int32_t* ids = (side ? a.ids_b + b * a.stride_b : a.ids_a + b * a.stride_a);
+        const int32_t* n_dev = side ? a.n_b_dev : a.n_a_dev;
+        int n = n_dev ? n_dev[b] : (side ? a.n_b : a.n_a);
+        n = max(0, min(n, side ? a.n_b : a.n_a));
+        const int k = min(a.k, n);
+        uint32_t thr = 0, thr_id = 0;
+        bool all_ties = true;
+        if (k > 0 && k < n) mark_topk(scores, ids, n, k, true, sm, thr, thr_id, all_ties);
+        else __syncthreads();
+        int local = 0;
+        for (int p = tid; p < n; p += kSelThreads) {
+            bool keep = k >= n;
+            if (!keep && k > 0) keep = is_kept(sm.keys[p], ~(uint32_t)ids[p], thr, thr_id, all_ties);
+            const int id = ids[p];
+            if (!keep || id < 0 || id >= a.id_space) continue;
+            if (side == 0) atomicOr(&seen[id >> 5], 1u << (id & 31));
+            else local += (seen[id >> 5] >> (id & 31)) & 1u;
+        }
+        if (side == 0 && tid == 0) a.topk_a[b] = k;
+        if (side == 1 && local) atomicAdd(&sm_count, local);
+        __syncthreads();
+    }
+    if (tid == 0) a.overlap[b] = sm_count;
+}
+
+struct CosineArgs {
+    const float* va; const int32_t* ids_a; int64_t stride_a; const int32_t* n_a_dev; int32_t n_a;
+    const float* vb; const int32_t* ids_b; int64_t stride_b; const int32_t* n_b_dev; int32_t n_b;
+    int32_t id_space;
+    float* cosine;          // [B]
+};
+
+__device__ __forceinline__ float block_sum(float v, float* sm4) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    __syncthreads();
+    if (threadIdx.x % kWave == 0) sm4[threadIdx.x / kWave] = v;
+    __syncthreads();
+    return (sm4[0] + sm4[1]) + (sm4[2] + sm4[3]);
+}
+
+// One workgroup per sequence.  Entries are matched by token id (ids_x == null: by position);
+// tokens present on one side only count as zero on the other.  fp32 sums in a fixed order.
+__global__ __launch_bounds__(kSelThreads) void cosine_kernel(CosineArgs a) {
+    __shared__ int16_t pos_b[kDiagIdSpace];
+    __shared__ float sm4[4];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const float* va = a.va + b * a.stride_a;
+    const float* vb = a.vb + b * a.stride_b;
+    const int32_t* ia = a.ids_a ? a.ids_a + b * a.stride_a : nullptr;
+    const int32_t* ib = a.ids_b ? a.ids_b + b * a.stride_b : nullptr;
+    const int na = max(0, min(a.n_a_dev ? a.n_a_dev[b] : a.n_a, a.n_a));
+    const int nb = max(0, min(a.n_b_dev ? a.n_b_dev[b] : a.n_b, a.n_b));
+    for (int i = tid; i < a.id_space; i += kSelThreads) pos_b[i] = -1;
+    __syncthreads();
+    float sbb = 0.f;
+    for (int p = tid; p < nb; p += kSelThreads) {
+        const int id = ib ? ib[p] : p;
+        if (id >= 0 && id < a.id_space) pos_b[id] = (int16_t)p;
+        sbb = fmaf(vb[p], vb[p], sbb);
+    }
+    __syncthreads();
+    float saa = 0.f, sab = 0.f;
+    for (int p = tid; p < na; p += kSelThreads) {
+        const int id = ia ? ia[p] : p;
+        const float x = va[p];
+        saa = fmaf(x, x, saa);
+        if (id >= 0 && id < a.id_space && pos_b[id] >= 0) sab = fmaf(x, vb[pos_b[id]], sab);
+    }
+    const float taa = block_sum(saa, sm4), tbb = block_sum(sbb, sm4), tab = block_sum(sab, sm4);
+    if (tid == 0) a.cosine[b] = (taa > 0.f && tbb > 0.f) ? tab / (sqrtf(taa) * sqrtf(tbb)) : 0.f;
+}
+
+}  // namespace
+
 }  // namespace st3
+
+extern "C" st3_status st3_overlap_topk(const float* score_a, const int32_t* ids_a, int64_t stride_a,
+                                       const int32_t* n_a_dev, int32_t n_a, const float* score_b,
+                                       const int32_t* ids_b, int64_t stride_b, const int32_t* n_b_dev, int32_t n_b,
+                                       int32_t batch, int32_t k, int32_t id_space, int32_t* overlap, int32_t* topk_a,
+                                       void* stream) {
+    if (!score_a || !ids_a || !score_b || !ids_b || !overlap || !topk_a) return ST3_ERR_INVALID_ARG;
+    if (batch <= 0 || n_a < 0 || n_b < 0 || k < 0 || stride_a < n_a || stride_b < n_b) return ST3_ERR_INVALID_ARG;
+    if (n_a > st3::kSelLdsKeys || n_b > st3::kSelLdsKeys || id_space <= 0 || id_space > st3::kDiagIdSpace)
+        return ST3_ERR_UNSUPPORTED;
+    st3::OverlapArgs a{score_a, ids_a, stride_a, n_a_dev, n_a, score_b, ids_b, stride_b, n_b_dev, n_b, k, id_space,
+                       overlap, topk_a};
+    st3::overlap_topk_kernel<<<batch, st3::kSelThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(a);
+    return st3::check_launch();
+}
+
+extern "C" st3_status st3_cosine_similarity(const float* va, const int32_t* ids_a, int64_t stride_a,
+                                            const int32_t* n_a_dev, int32_t n_a, const float* vb,
+                                            const int32_t* ids_b, int64_t stride_b, const int32_t* n_b_dev,
+                                            int32_t n_b, int32_t batch, int32_t id_space, float* cosine, void* stream) {
+    if (!va || !vb || !cosine) return ST3_ERR_INVALID_ARG;
+    if (batch <= 0 || n_a < 0 || n_b < 0 || stride_a < n_a || stride_b < n_b) return ST3_ERR_INVALID_ARG;
+    if (id_space <= 0 || id_space > st3::kDiagIdSpace || n_a > 32767 || n_b > 32767) return ST3_ERR_UNSUPPORTED;
+    st3::CosineArgs a{va, ids_a, stride_a, n_a_dev, n_a, vb, ids_b, stride_b, n_b_dev, n_b, id_space, cosine};
+    st3::cosine_kernel<<<batch, st3::kSelThreads, 0, reinterpret_cast<hipStream_t>(stream)>>>(a);
+    return st3::check_launch();
+}
 
 extern "C" st3_status st3_select_topk(const float* scores, int64_t score_stride, const int32_t* tie_ids,
                                       int64_t id_stride, int32_t batch, const int32_t* n_dev, int32_t n, int32_t k,

@@ -315,3 +315,83 @@ def test_prefill_attention_matches_oracle(dtype, D, B, H, n, ns, nv, W):
     assert_attention_close(to_np64(out), O, dtype)
     assert_mass_close(to_np64(mass)[:, :nv], m)
     assert np.all(to_np64(mass)[:, nv:] == -3.0)
+
+
+# ---------------------------------------------------------------------------
+# diagnostics: Overlap_n (Eq. 10), cosine similarity (Eq. 4-5)
+# ---------------------------------------------------------------------------
+def test_overlap_topk_matches_oracle():
+    rng = np.random.default_rng(11)
+    B = 5
+    for n_a, n_b, k, id_space in [(576, 576, 288, 576), (300, 200, 100, 1000), (64, 64, 64, 64), (40, 90, 0, 128),
+                                  (2880, 2000, 1440, 4096)]:
+        print(f"overlap n_a={n_a} n_b={n_b} k={k}", flush=True)
+        sa = rng.standard_normal((B, n_a)).astype(np.float32); sb = rng.standard_normal((B, n_b)).astype(np.float32)
+        sa[1] = np.round(sa[1] * 2) / 2; sb[1] = np.round(sb[1] * 2) / 2          # ties decided by id
+        ia = np.stack([rng.permutation(id_space)[:n_a] for _ in range(B)]).astype(np.int32)
+        ib = np.stack([rng.permutation(id_space)[:n_b] for _ in range(B)]).astype(np.int32)
+        na = [n_a, n_a // 2, n_a, 1, n_a]; nb = [n_b, n_b, n_b // 3, n_b, 1]
+        ov = torch.full((B,), -1, dtype=torch.int32, device=DEV); ta = torch.full((B,), -1, dtype=torch.int32, device=DEV)
+        st3.st3_overlap_topk(torch.from_numpy(sa).to(DEV), torch.from_numpy(ia).to(DEV), n_a,
+                             torch.from_numpy(sb).to(DEV), torch.from_numpy(ib).to(DEV), n_b, k, id_space, ov, ta,
+                             n_a_dev=_i32(na), n_b_dev=_i32(nb))
+        torch.cuda.synchronize()
+        for b in range(B):
+            A = orc.topk_id_set(sa[b, :na[b]].astype(np.float64), ia[b, :na[b]], k)
+            Bs = orc.topk_id_set(sb[b, :nb[b]].astype(np.float64), ib[b, :nb[b]], k)
+            assert int(ta[b]) == len(A) and int(ov[b]) == len(A & Bs), (b, n_a, n_b, k)
+            if len(A):
+                assert int(ov[b]) / int(ta[b]) == orc.overlap(sa[b, :na[b]].astype(np.float64), ia[b, :na[b]],
+                                                               sb[b, :nb[b]].astype(np.float64), ib[b, :nb[b]], k)
+
+
+def test_cosine_similarity_matches_oracle():
+    rng = np.random.default_rng(12)
+    B = 4
+    for n_a, n_b, id_space, with_ids in [(576, 576, 576, True), (300, 450, 1024, True), (739, 739, 739, False), (1, 5, 8, True)]:
+        va = np.abs(rng.standard_normal((B, n_a))).astype(np.float32); vb = np.abs(rng.standard_normal((B, n_b))).astype(np.float32)
+        va[2] = 0.0
+        ia = np.stack([rng.permutation(id_space)[:n_a] for _ in range(B)]).astype(np.int32)
+        ib = np.stack([rng.permutation(id_space)[:n_b] for _ in range(B)]).astype(np.int32)
+        cs = torch.full((B,), 9.0, dtype=torch.float32, device=DEV)
+        st3.st3_cosine_similarity(torch.from_numpy(va).to(DEV), torch.from_numpy(ia).to(DEV) if with_ids else None, n_a,
+                                  torch.from_numpy(vb).to(DEV), torch.from_numpy(ib).to(DEV) if with_ids else None, n_b,
+                                  id_space, cs)
+        torch.cuda.synchronize()
+        for b in range(B):
+            want = orc.cosine_similarity(va[b].astype(np.float64), ia[b] if with_ids else np.arange(n_a),
+                                         vb[b].astype(np.float64), ib[b] if with_ids else np.arange(n_b))
+            assert abs(float(cs[b]) - want) <= 2e-6, (b, float(cs[b]), want)
+
+
+def test_overlap_of_decode_mass_across_steps_current_mode():
+    """The paper's use of Eq. 10: top-50 % sets of the same layer's visual mass at step 1 and step n."""
+    import dataclasses
+    from paper_2412_20105_amd import pipeline
+    from workloads import decode_qkv, get_workload, prefill_qkv
+    w = dataclasses.replace(get_workload("llava15_7b"), layers=1, heads=4, steps=4, n_vis=96, n_txt=8,
+                            layer_schedule={"kind": "full"}, step_schedule={"kind": "none"})
+    keep = pipeline.keep_table_for(w)
+    gen = pipeline.Generation(1, w.heads, w.head_dim, torch.bfloat16, 2, w.n_sys, w.n_vis, w.n_txt, w.steps, keep, device=DEV)
+    ref = orc.Generation(1, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, np.array(keep))
+    pre = prefill_qkv(w, 0, 2)
+    ref.prefill(lambda l: pre)
+    gen.prefill_layer(0, *(to_dev(x, "bf16") for x in pre))
+    masses, ref_masses = [], []
+    for t in range(1, w.steps + 1):
+        d = decode_qkv(w, 0, t, 2)
+        s = ref.decode_step(lambda l: d)
+        out, mass = gen.decode_layer(0, t, *(to_dev(x, "bf16") for x in d))
+        masses.append(mass.clone()); ref_masses.append(s["mass"][0])
+    ids = gen.layers[0].ids
+    ov = torch.zeros((2,), dtype=torch.int32, device=DEV); ta = torch.zeros((2,), dtype=torch.int32, device=DEV)
+    k = w.n_vis // 2
+    for n in range(w.steps):
+        st3.st3_overlap_topk(masses[0], ids, w.n_vis, masses[n], ids, w.n_vis, k, w.n_vis, ov, ta)
+        torch.cuda.synchronize()
+        for b in range(2):
+            want = orc.overlap(ref_masses[0][b], np.arange(w.n_vis), ref_masses[n][b], np.arange(w.n_vis), k)
+            # the GPU ranks its own fp32 mass: allow one token to flip on a near-tie
+            assert abs(int(ov[b]) / int(ta[b]) - want) <= 1.0 / k + 1e-12
+        if n == 0:
+            assert ov.cpu().tolist() == [k, k]
