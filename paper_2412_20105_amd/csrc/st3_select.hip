@@ -258,30 +258,37 @@ __device__ __forceinline__ bool flag_at(const SelShared& sm, int p) { return (sm
 
 // Copies `count` rows (dst_i <- src_i, from the move list starting at entry `first`) on all 2*H
 // strips of sequence b.  Callers guarantee that no destination of the batch is a source of it.
+typedef uint32_t u32x4_v __attribute__((ext_vector_type(4)));
+
+// Address of 16-byte vector `idx` of a batch of row moves: idx enumerates (move, strip, vector).
+__device__ __forceinline__ char* move_addr(const EvictArgs& a, int b, const int32_t* mv, int first, int idx, int which) {
+    const int strips = (a.k ? 2 : 1) * a.H;             // K may be absent (layers that keep V only)
+    const int per_move = strips * a.vecs_per_row;
+    const int i = first + idx / per_move;
+    const int rem = idx % per_move;
+    const int strip = rem / a.vecs_per_row, vec = rem % a.vecs_per_row;
+    char* base = ((a.k && strip < a.H) ? a.k : a.v) + b * a.stride_b + (int64_t)(strip % a.H) * a.stride_h +
+                 (int64_t)vec * 16;
+    return base + mv[2 * i + which] * a.stride_t;
+}
+
+// Copies `count` rows (dst_i <- src_i, from the move list starting at entry `first`) on all
+// strips of sequence b.  Callers guarantee that no destination of the batch is a source of it.
 __device__ __forceinline__ void copy_rows_all_strips(const EvictArgs& a, int b, const int32_t* mv, int first, int count) {
-    constexpr int UR = 8;                               // independent 16-byte loads in flight per thread
-    const int per_move = 2 * a.H * a.vecs_per_row;
-    const int total = count * per_move;
+    constexpr int UR = 16;                              // independent 16-byte loads in flight per thread
+    const int total = count * (a.k ? 2 : 1) * a.H * a.vecs_per_row;
     for (int base = 0; base < total; base += UR * kSelThreads) {
-        uint4 tmp[UR];
-        char* dst[UR];
+        u32x4_v tmp[UR];
 #pragma unroll
         for (int u = 0; u < UR; ++u) {
             const int idx = base + u * kSelThreads + (int)threadIdx.x;
-            dst[u] = nullptr;
-            if (idx < total) {
-                const int i = first + idx / per_move;
-                const int rem = idx % per_move;
-                const int strip = rem / a.vecs_per_row, vec = rem % a.vecs_per_row;
-                char* p = (strip < a.H ? a.k : a.v) + b * a.stride_b + (int64_t)(strip % a.H) * a.stride_h +
-                          (int64_t)vec * 16;
-                tmp[u] = *reinterpret_cast<const uint4*>(p + mv[2 * i + 1] * a.stride_t);
-                dst[u] = p + mv[2 * i] * a.stride_t;
-            }
+            if (idx < total) tmp[u] = *reinterpret_cast<const u32x4_v*>(move_addr(a, b, mv, first, idx, 1));
         }
 #pragma unroll
-        for (int u = 0; u < UR; ++u)
-            if (dst[u]) *reinterpret_cast<uint4*>(dst[u]) = tmp[u];
+        for (int u = 0; u < UR; ++u) {
+            const int idx = base + u * kSelThreads + (int)threadIdx.x;
+            if (idx < total) *reinterpret_cast<u32x4_v*>(move_addr(a, b, mv, first, idx, 0)) = tmp[u];
+        }
     }
 }
 
