@@ -68,7 +68,7 @@ class Job:
         self.pre = [tuple(randn(shape_p) for _ in range(3)) for _ in range(w.layers)]
         self.dec = [randn(shape_d) for _ in range(T)]
         self.gen = pipeline.Generation(w.layers, w.heads, w.head_dim, dt, B, w.n_sys, w.n_vis, w.n_txt, T, keep,
-                                       defer_mass=True, device=dev)
+                                       device=dev)
 
     def run(self):
         gen, w = self.gen, self.w
@@ -78,8 +78,6 @@ class Job:
             gen.prefill_layer(l, q, k, v)
         for t in range(1, self.T + 1):
             gen.decode_step(t, self.dec[t - 1])
-        for l in range(w.layers):           # the last step's masses are still pending
-            gen.finalize_mass(l)
 
     def run_prefill_only(self):
         gen, w = self.gen, self.w

@@ -95,8 +95,7 @@ ST3_EXPORT uint32_t st3_version(void);                 /* major<<16 | minor<<8 |
 /* Bytes of DEVICE workspace (256-byte aligned base expected) that any call below needs for a
  * layer whose cache has `kv_capacity` rows per (b,h), prefill sequences with at most max_vis_len
  * visual tokens and a score window of at most `score_window` rows.  The decode-path calls lay the
- * workspace out from the cache capacity alone; a layer that defers its visual mass
- * (st3_decode_layer_step with defer_mass) must keep a workspace of its own between steps. */
+ * workspace out from the cache capacity alone. */
 ST3_EXPORT size_t st3_workspace_bytes(const st3_attn_shape* shape, int32_t kv_capacity, int32_t max_vis_len,
                                       int32_t score_window);
 
@@ -197,38 +196,35 @@ ST3_EXPORT st3_status st3_select_compact_layer(const st3_attn_shape* shape, cons
                                     int32_t mode, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * One layer of one decode step, in the order of Alg. 3's VTA branch:
- *   (1) select-and-compact to keep_count (no eviction when keep_count < 0),
- *   (2) append k_new/v_new,
- *   (3) decode attention of q over the resulting cache, with visual mass.
- * Two kernels: one workgroup per sequence does (1), moving the few evicted rows itself, and bumps
- * kv_len; the attention kernel reads the new token's row from k_new/v_new and stores it into
- * the cache while streaming K and V once.  max_* in `seg` bound the lengths before the call;
- * host check: max_kv_len < capacity.
- * vis_mass (may be NULL: no mass) and defer_mass:
- *   defer_mass == 0: vis_mass holds this call's mass once the stream is synchronised.
- *   defer_mass != 0: the head reduction of this call's mass is postponed: the logits stay in
- *     `workspace`, and the NEXT st3_decode_layer_step on the same workspace (or
- *     st3_decode_mass_finalize) writes the finished mass to the vis_mass it is given, before it
- *     ranks anything.  This saves one launch per layer and step; with vis_mass == score_col the
- *     next step then ranks by the latest mass.  The workspace must not be used for another layer
- *     in between.
+ * One layer of one decode step (Alg. 3, VTA branch):
+ *   (1) append k_new/v_new and attend: q over the cache plus the new token, with visual mass;
+ *   (2) count the appended row (kv_len[b] += 1) and select-and-compact down to `keep_after`
+ *       visual rows, i.e. the eviction Alg. 3 performs at the START of the layer's NEXT step is
+ *       done here, right after this step's attention (the cache is not touched in between, so
+ *       the result is the same; keep_after < 0: no eviction).  The eviction that precedes the
+ *       very first decode step is a stand-alone st3_select_compact_layer call.
+ * Two kernels: the attention kernel reads the new token's row from k_new/v_new and stores it
+ * into the cache while streaming K and V once; then one workgroup per sequence finishes the visual
+ * mass (head reduction), ranks, evicts (moving the few affected rows itself) and publishes the
+ * lengths.  max_* in `seg` bound the lengths BEFORE the call; host check: max_kv_len < capacity.
+ * vis_mass (may be NULL: no mass) holds this step's mass, in the cache order the attention saw,
+ * once the stream is synchronised.  With vis_mass == score_col the eviction ranks by that mass
+ * (and compacts it along with id_col).  The workspace must be the layer's own (st3_workspace_init).
  * ------------------------------------------------------------------------------------------- */
 ST3_EXPORT st3_status st3_decode_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv,
                                             const st3_segments* seg, float* score_col, int32_t* id_col,
-                                            int64_t col_stride, int32_t keep_count, int32_t mode, const void* q,
+                                            int64_t col_stride, int32_t keep_after, int32_t mode, const void* q,
                                             const void* k_new, const void* v_new, void* out, float* vis_mass,
-                                            int64_t mass_stride, int32_t defer_mass, void* workspace,
-                                            size_t workspace_bytes, void* stream);
+                                            int64_t mass_stride, void* workspace, size_t workspace_bytes,
+                                            void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * One whole decode step over `n_layers` layers from a single host call (Alg. 3, VTA branch, the
  * loop over l).  `layers` is a HOST array; entry i carries exactly the arguments
  * st3_decode_layer_step takes for that layer.  The result is the same as calling
- * st3_decode_layer_step for i = 0 .. n_layers-1 in order, but the evictions of all layers are
- * planned up front, several layers per launch: a layer's eviction at step t depends only on its
- * own score column and keep_count, not on this step's activations, so this reordering is also
- * valid inside a real decoder.  The per-layer attention kernels follow in layer order.
+ * st3_decode_layer_step for i = 0 .. n_layers-1 in order.  Step (2) of layer i-1 does not depend
+ * on layer i's attention (nor the other way round), so it runs in spare workgroups of layer i's
+ * attention launch instead of a launch of its own: one launch per layer plus one at the end.
  * ------------------------------------------------------------------------------------------- */
 typedef struct {
     st3_kv_layer kv;
@@ -236,7 +232,7 @@ typedef struct {
     float*       score_col;
     int32_t*     id_col;
     int64_t      col_stride;
-    int32_t      keep_count;        /* < 0: no eviction at this step */
+    int32_t      keep_after;        /* visual rows to keep after this step's attention; < 0: all */
     const void*  q;
     const void*  k_new;
     const void*  v_new;
@@ -248,13 +244,7 @@ typedef struct {
 } st3_layer_step;
 
 ST3_EXPORT st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
-                                      int32_t mode, int32_t defer_mass, void* stream);
-
-/* Finishes a visual mass that st3_decode_layer_step left pending in `workspace` (no effect when
- * none is pending).  `seg` must describe the cache as that call left it. */
-ST3_EXPORT st3_status st3_decode_mass_finalize(const st3_attn_shape* shape, const st3_kv_layer* kv,
-                                               const st3_segments* seg, float* vis_mass, int64_t mass_stride,
-                                               void* workspace, size_t workspace_bytes, void* stream);
+                                      int32_t mode, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Retention schedules: HOST-only pure functions that fill integer tables.

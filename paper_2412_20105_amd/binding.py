@@ -28,7 +28,7 @@ EXPORTED = [
     "st3_status_string", "st3_last_hip_error", "st3_version", "st3_workspace_bytes", "st3_workspace_init",
     "st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_select_topk",
     "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
-    "st3_decode_mass_finalize", "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
+    "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
     "st3_debug_set_prefill_path", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
     "st3_cosine_similarity",
 ]
@@ -65,7 +65,7 @@ class Segments(C.Structure):
 
 class LayerStep(C.Structure):
     _fields_ = [("kv", KvLayer), ("seg", Segments), ("score_col", C.c_void_p), ("id_col", C.c_void_p),
-                ("col_stride", C.c_int64), ("keep_count", C.c_int32), ("q", C.c_void_p), ("k_new", C.c_void_p),
+                ("col_stride", C.c_int64), ("keep_after", C.c_int32), ("q", C.c_void_p), ("k_new", C.c_void_p),
                 ("v_new", C.c_void_p), ("out", C.c_void_p), ("vis_mass", C.c_void_p), ("mass_stride", C.c_int64),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
@@ -104,11 +104,9 @@ def lib() -> C.CDLL:
                                                C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         L.st3_decode_layer_step.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_void_p, C.c_int64,
                                             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                            C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
-        L.st3_decode_step.argtypes = [P(AttnShape), C.c_int32, P(LayerStep), C.c_int32, C.c_int32, C.c_void_p]
+                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.st3_decode_step.argtypes = [P(AttnShape), C.c_int32, P(LayerStep), C.c_int32, C.c_void_p]
         L.st3_decode_step.restype = C.c_int
-        L.st3_decode_mass_finalize.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_int64,
-                                               C.c_void_p, C.c_size_t, C.c_void_p]
         L.st3_schedule_pvtp.argtypes = [C.c_int32] * 6 + [C.c_void_p]
         L.st3_schedule_linear.argtypes = [C.c_int32] * 4 + [C.c_void_p]
         L.st3_schedule_anneal.argtypes = [C.c_int32, C.c_double, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
@@ -116,7 +114,7 @@ def lib() -> C.CDLL:
         L.st3_kv_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32]
         for name in ("st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_select_topk",
                      "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step",
-                     "st3_decode_mass_finalize", "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal"):
+                     "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal"):
             getattr(L, name).restype = C.c_int
         L.st3_overlap_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                        C.c_int64, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
@@ -253,29 +251,20 @@ def st3_select_compact_layer(shape, kv: KvLayer, seg: Segments, score_col, id_co
                                           _stream(stream)), "st3_select_compact_layer")
 
 
-def st3_decode_layer_step(shape, kv: KvLayer, seg: Segments, score_col, id_col, keep_count, mode, q, k_new, v_new,
-                          out, vis_mass, workspace, defer_mass=False, stream=None):
+def st3_decode_layer_step(shape, kv: KvLayer, seg: Segments, score_col, id_col, keep_after, mode, q, k_new, v_new,
+                          out, vis_mass, workspace, stream=None):
     ms = 0 if vis_mass is None else vis_mass.stride(0)
     cs = 0 if score_col is None else score_col.stride(0)
     _check(lib().st3_decode_layer_step(C.byref(shape), C.byref(kv), C.byref(seg), _ptr(score_col), _ptr(id_col), cs,
-                                       keep_count, mode, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
-                                       out.data_ptr(), _ptr(vis_mass), ms, 1 if defer_mass else 0,
-                                       workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                                       _stream(stream)),
+                                       keep_after, mode, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                       out.data_ptr(), _ptr(vis_mass), ms, workspace.data_ptr(),
+                                       workspace.numel() * workspace.element_size(), _stream(stream)),
            "st3_decode_layer_step")
 
 
-def st3_decode_step(shape, layer_steps, n_layers, mode, defer_mass=False, stream=None):
+def st3_decode_step(shape, layer_steps, n_layers, mode, stream=None):
     """layer_steps: a ctypes array of LayerStep (the caller keeps the tensors it points to alive)."""
-    _check(lib().st3_decode_step(C.byref(shape), n_layers, layer_steps, mode, 1 if defer_mass else 0,
-                                 _stream(stream)), "st3_decode_step")
-
-
-def st3_decode_mass_finalize(shape, kv: KvLayer, seg: Segments, vis_mass, workspace, stream=None):
-    _check(lib().st3_decode_mass_finalize(C.byref(shape), C.byref(kv), C.byref(seg), vis_mass.data_ptr(),
-                                          vis_mass.stride(0), workspace.data_ptr(),
-                                          workspace.numel() * workspace.element_size(), _stream(stream)),
-           "st3_decode_mass_finalize")
+    _check(lib().st3_decode_step(C.byref(shape), n_layers, layer_steps, mode, _stream(stream)), "st3_decode_step")
 
 
 # -- host-only schedule helpers ---------------------------------------------------------------

@@ -3,7 +3,7 @@
 #include <cmath>
 #include <vector>
 
-#include "st3_common.h"
+#include "st3_evict.h"
 
 namespace st3 {
 
@@ -37,12 +37,6 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
                           const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
                           void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
                           void* workspace, size_t workspace_bytes, hipStream_t st);
-st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
-                                  float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
-                                  int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st,
-                                  int do_append, float* mass_dst, int64_t mass_stride);
-st3_status enqueue_plan_layers(const st3_attn_shape* shape, int n, const st3_layer_step* layers, int32_t mode,
-                               hipStream_t st);
 
 }  // namespace st3
 
@@ -98,7 +92,7 @@ namespace st3 {
 // whole-step entry points).
 static st3_status check_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                                    const float* score_col, const int32_t* id_col, int64_t col_stride,
-                                   int32_t keep_count, int32_t mode, const void* q, const void* k_new,
+                                   int32_t keep_after, int32_t mode, const void* q, const void* k_new,
                                    const void* v_new, const void* out, const float* vis_mass, int64_t mass_stride,
                                    const void* workspace, size_t workspace_bytes) {
     st3_status s = validate_kv(shape, kv, seg);
@@ -108,7 +102,7 @@ static st3_status check_layer_step(const st3_attn_shape* shape, const st3_kv_lay
         return ST3_ERR_INVALID_ARG;
     if (seg->max_kv_len >= kv->capacity) return ST3_ERR_INVALID_ARG;
     if (vis_mass && mass_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
-    if (keep_count >= 0) {
+    if (keep_after >= 0) {
         if (!score_col || !id_col || col_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
         if (mode != ST3_STABLE && mode != ST3_HOLE_FILL) return ST3_ERR_INVALID_ARG;
     }
@@ -121,50 +115,66 @@ static st3_status check_layer_step(const st3_attn_shape* shape, const st3_kv_lay
 
 extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv,
                                             const st3_segments* seg, float* score_col, int32_t* id_col,
-                                            int64_t col_stride, int32_t keep_count, int32_t mode, const void* q,
+                                            int64_t col_stride, int32_t keep_after, int32_t mode, const void* q,
                                             const void* k_new, const void* v_new, void* out, float* vis_mass,
-                                            int64_t mass_stride, int32_t defer_mass, void* workspace,
-                                            size_t workspace_bytes, void* stream) {
+                                            int64_t mass_stride, void* workspace, size_t workspace_bytes,
+                                            void* stream) {
     using namespace st3;
     st3_status s = check_shape(shape);
     if (s != ST3_OK) return s;
     // all checks before the first launch, so that an error enqueues nothing
-    s = check_layer_step(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, q, k_new, v_new, out,
+    s = check_layer_step(shape, kv, seg, score_col, id_col, col_stride, keep_after, mode, q, k_new, v_new, out,
                          vis_mass, mass_stride, workspace, workspace_bytes);
     if (s != ST3_OK) return s;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    // (1) one workgroup per sequence: finish a mass left pending by the previous step, rank, evict
-    //     (rows moved in place), kv_len += 1 for the new token.  Runs even when nothing is evicted.
-    s = enqueue_select_compact(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, workspace,
-                               workspace_bytes, st, 1, vis_mass, mass_stride);
+    EvictArgs ea;
+    bool needs_apply = false;
+    s = build_evict_args(shape, kv, seg, score_col, id_col, col_stride, keep_after, mode, workspace, workspace_bytes,
+                         1, vis_mass, mass_stride, ea, needs_apply);
     if (s != ST3_OK) return s;
-    // (2) attention over the cache; the appended row is read from k_new/v_new and stored on the way
-    return enqueue_decode(shape, q, kv, seg, seg->max_kv_len + 1, k_new, v_new, out, vis_mass, mass_stride,
-                          vis_mass != nullptr, defer_mass != 0, workspace, workspace_bytes, st);
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    // (1) attention over the cache plus the new token, whose row is read from k_new/v_new and stored on the way
+    s = enqueue_decode(shape, q, kv, seg, seg->max_kv_len + 1, k_new, v_new, out, vis_mass, mass_stride,
+                       vis_mass != nullptr, true, workspace, workspace_bytes, st);
+    if (s != ST3_OK) return s;
+    // (2) one workgroup per sequence: finish the mass, count the appended row, rank and evict for the next step
+    launch_evict_plan(ea, shape->batch, st);
+    if (needs_apply) launch_evict_apply(ea, shape->batch, st);
+    return check_launch();
 }
 
 extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
-                                      int32_t mode, int32_t defer_mass, void* stream) {
+                                      int32_t mode, void* stream) {
     using namespace st3;
     st3_status s = check_shape(shape);
     if (s != ST3_OK) return s;
     if (n_layers <= 0 || !layers) return ST3_ERR_INVALID_ARG;
+    std::vector<EvictArgs> plan((size_t)n_layers);
+    std::vector<char> needs_apply((size_t)n_layers, 0);
     for (int i = 0; i < n_layers; ++i) {
         const st3_layer_step& L = layers[i];
-        s = check_layer_step(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_count, mode, L.q,
+        s = check_layer_step(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_after, mode, L.q,
                              L.k_new, L.v_new, L.out, L.vis_mass, L.mass_stride, L.workspace, L.workspace_bytes);
         if (s != ST3_OK) return s;
+        bool na = false;
+        s = build_evict_args(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_after, mode,
+                             L.workspace, L.workspace_bytes, 1, L.vis_mass, L.mass_stride, plan[i], na);
+        if (s != ST3_OK) return s;
+        needs_apply[i] = na ? 1 : 0;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    s = enqueue_plan_layers(shape, n_layers, layers, mode, st);
-    if (s != ST3_OK) return s;
+    const int B = shape->batch;
     for (int i = 0; i < n_layers; ++i) {
         const st3_layer_step& L = layers[i];
         s = enqueue_decode(shape, L.q, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.k_new, L.v_new, L.out, L.vis_mass,
-                           L.mass_stride, L.vis_mass != nullptr, defer_mass != 0, L.workspace, L.workspace_bytes, st);
+                           L.mass_stride, L.vis_mass != nullptr, true, L.workspace, L.workspace_bytes, st);
         if (s != ST3_OK) return s;
     }
-    return ST3_OK;
+    // every layer's plan (finish the mass, count the new row, rank, evict) in one launch per 16
+    // layers: a plan workgroup is latency bound, so the layers' plans are best run side by side
+    launch_evict_plan_batch(plan.data(), n_layers, B, st);
+    for (int i = 0; i < n_layers; ++i)
+        if (needs_apply[i]) launch_evict_apply(plan[i], B, st);
+    return check_launch();
 }
 
 extern "C" st3_status st3_profile_enable(int32_t max_launches) {

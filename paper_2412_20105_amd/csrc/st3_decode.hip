@@ -7,15 +7,21 @@
 // un-normalised partials that decode_finish_kernel merges in chunk order.  For the visual mass the
 // attend kernel saves the scaled logits of the visual keys and every chunk's (max, sum); turning
 // them into probabilities and adding them over heads - in head order, so the sum is the same on
-// every run - is done by finish_mass(), either in decode_finish_kernel right away or, when the
-// caller defers it, at the start of the layer's next select-and-compact kernel.
-// When a token is appended in the same call its row is read from k_new/v_new by the workgroup
-// that owns the end of the strip, which also stores it into the cache.
+// every run - is done by finish_mass(): in decode_finish_kernel for the stand-alone call, and by
+// the layer's eviction-plan workgroup in the fused step (it needs the scores only then).
+// The token being appended is read from k_new/v_new as cache row kv_len[b] by the workgroup that
+// owns the end of the strip, which also stores it into the cache; kv_len itself is bumped by the
+// eviction plan that follows the attention.
+// (Letting that plan ride in spare workgroups of the next layer's attend launch was measured and
+// dropped: a plan workgroup is a chain of dependent memory round trips that outlasts the attend
+// launch and halves the streaming rate of the compute unit it sits on.)
 //
 // No kernel here communicates between workgroups of one launch: device-scope fences cost a
 // write-back and invalidate of the XCD-private L2 on this part and were measured to be ruinous.
 #include <hip/hip_ext.h>
 
+#include "st3_common.h"
+#include "st3_attend.h"
 #include "st3_decode.h"
 
 #ifndef ST3_DECODE_U
@@ -47,7 +53,7 @@ struct DecodeArgs {
     int64_t stride_b, stride_h, stride_t;
     const int32_t* kv_len;
     const int32_t* vis_len;
-    int32_t sys_len, max_vis, max_kv, H, nsplit, nsplit_cap, chunk, capacity;
+    int32_t B, sys_len, max_vis, max_kv, H, nsplit, nsplit_cap, chunk, capacity;
     int32_t defer;          // 1: the mass of this call is finished later; mark it pending
     float scale_l2;
     float* part_o;          // [B,H,nsplit_cap,D]   (nsplit > 1 only)
@@ -55,7 +61,7 @@ struct DecodeArgs {
     float* logits;          // [B,H,capacity]; null when no mass is wanted
     int32_t* pending;       // [B][4]: {valid, nsplit, chunk, -} of a mass still to be finished (null: none)
     const void* k_new;      // [B,H,D] rows of the token being appended (null: none); the cache row
-    const void* v_new;      //         kv_len[b]-1 is then taken from here and written to the cache
+    const void* v_new;      //         kv_len[b] is then taken from here and written to the cache
     void* out;              // [B,H,D]
 };
 
@@ -71,7 +77,8 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
     using M = RowMap<T, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, TILE = U * M::RPL;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int len = min(a.kv_len[b], a.max_kv);      // never trust a device length past the host bound
+    // the row being appended sits at index kv_len[b]; never trust a device length past the host bound
+    const int len = min(a.kv_len[b] + (a.k_new != nullptr ? 1 : 0), a.max_kv);
     const int c0 = split * a.chunk;
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int64_t bh = (int64_t)b * a.H + h;
@@ -161,11 +168,10 @@ struct FinishArgs {
     const int32_t* kv_len;
     const int32_t* vis_len;
     int32_t H, nsplit, nsplit_cap, chunk, capacity, max_vis, max_kv;
+    int32_t appended;       // 1: the attend kernel took one more row than kv_len[b] says (the token being appended)
     void* out;              // null: outputs already written (nsplit == 1)
     float* mass;            // null: no mass
     int64_t mass_stride;
-    const int32_t* pending; // descriptor left by the attend kernel
-    int32_t from_pending;   // 1: take nsplit/chunk from the descriptor, do nothing if none is pending
 };
 
 // grid (out_blocks + mass_blocks, B), 256 threads.  Blocks x < H (when out != null) merge the
@@ -173,14 +179,8 @@ struct FinishArgs {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_finish_kernel(FinishArgs a) {
     const int b = blockIdx.y, tid = threadIdx.x;
-    const int len = min(a.kv_len[b], a.max_kv);
-    int nsplit = a.nsplit, chunk = a.chunk;
-    if (a.from_pending) {
-        if (a.pending[b * 4] == 0) return;
-        nsplit = min(a.pending[b * 4 + 1], a.nsplit_cap);
-        chunk = max(a.pending[b * 4 + 2], 32);
-    }
-    const int ns = len > 0 ? min((len + chunk - 1) / chunk, nsplit) : 0;
+    const int len = min(a.kv_len[b] + a.appended, a.max_kv);
+    const int ns = len > 0 ? min((len + a.chunk - 1) / a.chunk, a.nsplit) : 0;
     const int out_blocks = a.out ? a.H : 0;
     if ((int)blockIdx.x < out_blocks) {
         const int h = blockIdx.x;
@@ -238,12 +238,13 @@ __global__ void bump_len_kernel(int32_t* kv_len, int32_t B, int32_t capacity) {
 
 template <typename T, int D>
 void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
+    const dim3 grid(da.nsplit, da.H, B);
     hipEvent_t e0, e1;
     if (profile_take(&e0, &e1))     // timed launch: the events receive the kernel's own start and end
-        hipExtLaunchKernelGGL((decode_attend_kernel<T, D, ST3_DECODE_U>), dim3(da.nsplit, da.H, B),
-                              dim3(kDecodeThreads), 0, st, e0, e1, 0, da);
+        hipExtLaunchKernelGGL((decode_attend_kernel<T, D, ST3_DECODE_U>), grid, dim3(kDecodeThreads), 0, st, e0, e1, 0,
+                              da);
     else
-        decode_attend_kernel<T, D, ST3_DECODE_U><<<dim3(da.nsplit, da.H, B), kDecodeThreads, 0, st>>>(da);
+        decode_attend_kernel<T, D, ST3_DECODE_U><<<grid, kDecodeThreads, 0, st>>>(da);
 }
 
 template <typename T, int D>
@@ -283,10 +284,9 @@ st3_status check_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_s
 
 }  // namespace
 
-// Enqueues attention (+ the finish kernel when it is needed).  max_kv_len bounds kv_len[] as the
-// kernels will see it.  k_new/v_new non-null: row kv_len[b]-1 is the token being appended.
-// defer_mass: leave the head reduction of the mass to the layer's next select-and-compact call
-// (or to st3_decode_mass_finalize); the logits stay in the workspace until then.
+// Enqueues attention (+ the finish kernel when it is needed).  max_kv_len bounds the length the
+// kernels will see (kv_len[b], plus one when a token is appended: k_new/v_new non-null).
+// defer_mass: leave the head reduction of the mass to the eviction plan that follows.
 st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
                           const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
                           void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
@@ -300,7 +300,7 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     da.q = q; da.k = kv->k; da.v = kv->v;
     da.stride_b = kv->stride_b; da.stride_h = kv->stride_h; da.stride_t = kv->stride_t;
     da.kv_len = seg->kv_len; da.vis_len = seg->vis_len;
-    da.sys_len = seg->sys_len; da.max_vis = seg->max_vis_len; da.max_kv = max_kv_len; da.H = H;
+    da.B = B; da.sys_len = seg->sys_len; da.max_vis = seg->max_vis_len; da.max_kv = max_kv_len; da.H = H;
     da.nsplit = decode_nsplit(B, H, max_kv_len);
     if (da.nsplit > wl.nsplit_cap) da.nsplit = wl.nsplit_cap;
     da.nsplit_cap = wl.nsplit_cap;
@@ -322,9 +322,9 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
         fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len;
         fa.H = H; fa.nsplit = da.nsplit; fa.nsplit_cap = wl.nsplit_cap; fa.chunk = da.chunk;
         fa.capacity = kv->capacity; fa.max_vis = seg->max_vis_len; fa.max_kv = max_kv_len;
+        fa.appended = k_new != nullptr ? 1 : 0;
         fa.out = da.nsplit > 1 ? out : nullptr;
         fa.mass = mass_now ? vis_mass : nullptr; fa.mass_stride = mass_stride;
-        fa.pending = da.pending;
         ST3_DISPATCH(launch_finish, shape, fa, B, st);
     }
     return check_launch();
@@ -338,27 +338,6 @@ st3_status enqueue_append(const st3_attn_shape* shape, const st3_kv_layer* kv, c
     aa.stride_b = kv->stride_b; aa.stride_h = kv->stride_h; aa.stride_t = kv->stride_t;
     aa.k_new = k_new; aa.v_new = v_new; aa.kv_len = seg->kv_len; aa.H = H; aa.capacity = kv->capacity;
     ST3_DISPATCH(launch_append, shape, aa, B, seg->kv_len, st);
-    return check_launch();
-}
-
-// Finishes a deferred mass, if one is pending in this workspace.
-st3_status enqueue_mass_finalize(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
-                                 float* vis_mass, int64_t mass_stride, void* workspace, size_t workspace_bytes,
-                                 hipStream_t st) {
-    const int B = shape->batch, H = shape->heads, D = shape->head_dim;
-    const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
-    if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
-    if (seg->max_vis_len == 0) return ST3_OK;
-    char* ws = reinterpret_cast<char*>(workspace);
-    FinishArgs fa{};
-    fa.part_ml = reinterpret_cast<float*>(ws + wl.part_ml);
-    fa.logits = reinterpret_cast<float*>(ws + wl.logits);
-    fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len;
-    fa.H = H; fa.nsplit = wl.nsplit_cap; fa.nsplit_cap = wl.nsplit_cap; fa.chunk = 32;
-    fa.capacity = kv->capacity; fa.max_vis = seg->max_vis_len; fa.max_kv = seg->max_kv_len;
-    fa.out = nullptr; fa.mass = vis_mass; fa.mass_stride = mass_stride;
-    fa.pending = reinterpret_cast<int32_t*>(ws + wl.pending); fa.from_pending = 1;
-    ST3_DISPATCH(launch_finish, shape, fa, B, st);
     return check_launch();
 }
 
@@ -381,19 +360,6 @@ extern "C" st3_status st3_decode_attention(const st3_attn_shape* shape, const vo
     return st3::enqueue_decode(shape, q, kv, seg, seg->max_kv_len, nullptr, nullptr, out, vis_mass, mass_stride,
                                vis_mass != nullptr, false, workspace, workspace_bytes,
                                reinterpret_cast<hipStream_t>(stream));
-}
-
-extern "C" st3_status st3_decode_mass_finalize(const st3_attn_shape* shape, const st3_kv_layer* kv,
-                                               const st3_segments* seg, float* vis_mass, int64_t mass_stride,
-                                               void* workspace, size_t workspace_bytes, void* stream) {
-    st3_status s = st3::check_shape(shape);
-    if (s != ST3_OK) return s;
-    s = st3::validate_kv(shape, kv, seg);
-    if (s != ST3_OK) return s;
-    if (!vis_mass || !workspace || !st3::aligned16(workspace)) return ST3_ERR_INVALID_ARG;
-    if (mass_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
-    return st3::enqueue_mass_finalize(shape, kv, seg, vis_mass, mass_stride, workspace, workspace_bytes,
-                                      reinterpret_cast<hipStream_t>(stream));
 }
 
 extern "C" st3_status st3_kv_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,

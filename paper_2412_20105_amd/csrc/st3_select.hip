@@ -6,108 +6,12 @@
 // (4 passes of 8 bits, histogram in LDS), followed - only when the k-th score is shared - by a
 // second radix select on the tie ids, so that the result is the unique top-k set under the total
 // order (score descending, id ascending).  One workgroup per sequence.
-#include "st3_decode.h"
+#include "st3_evict.h"
 
 namespace st3 {
 
 namespace {
 
-constexpr int kSelThreads = 256;
-constexpr int kSelWaves = kSelThreads / kWave;
-constexpr int kSelLdsKeys = 8192;
-
-__device__ __forceinline__ uint32_t score_key(float f) {
-    uint32_t u = __float_as_uint(f);
-    if (u == 0x80000000u) u = 0u;                       // -0.0 ranks with +0.0
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // larger float <-> larger key
-}
-
-struct SelShared {
-    uint32_t keys[kSelLdsKeys];
-    uint32_t flags[kSelLdsKeys / 32];
-    int hist[256];
-    int wave_tot[kSelWaves];
-    int sel_bin, sel_want, sel_cnt;
-    int red;
-};
-
-// Inclusive scan of one int per thread over the 256 threads of the block, in thread order.
-__device__ __forceinline__ int block_incl_scan(int v, SelShared& sm) {
-    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        int t = __shfl_up(v, off);
-        if (lane >= off) v += t;
-    }
-    __syncthreads();                                    // protects wave_tot from the previous use
-    if (lane == kWave - 1) sm.wave_tot[wave] = v;
-    __syncthreads();
-    int base = 0;
-#pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) base += (w < wave) ? sm.wave_tot[w] : 0;
-    return v + base;
-}
-
-// Finds, among the elements i in [0,n) for which f(i, key) is true, the key of rank `want`
-// (1-based, descending).  Returns it; `want` becomes the number of elements equal to that key
-// that still belong to the top set, `ties` the number of elements equal to it.
-template <class F>
-__device__ __forceinline__ uint32_t radix_select_desc(F f, int n, int& want, int& ties, SelShared& sm) {
-    uint32_t prefix = 0, pmask = 0;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        sm.hist[threadIdx.x] = 0;
-        __syncthreads();
-        for (int i = threadIdx.x; i < n; i += kSelThreads) {
-            uint32_t key;
-            if (f(i, key) && (key & pmask) == prefix) atomicAdd(&sm.hist[(key >> shift) & 255u], 1);
-        }
-        __syncthreads();
-        int v = sm.hist[255 - threadIdx.x];             // thread order = descending bin order
-        int incl = block_incl_scan(v, sm);
-        if (incl >= want && incl - v < want) {
-            sm.sel_bin = 255 - threadIdx.x;
-            sm.sel_want = want - (incl - v);
-            sm.sel_cnt = v;
-        }
-        __syncthreads();
-        prefix |= (uint32_t)sm.sel_bin << shift;
-        pmask |= 255u << shift;
-        want = sm.sel_want;
-        ties = sm.sel_cnt;
-        __syncthreads();
-    }
-    return prefix;
-}
-
-// Marks the top-k entries of one row in sm.flags (bit p of word p/32).  Requires n <= kSelLdsKeys
-// when `staged`; otherwise keys are recomputed from global memory on every pass.
-// ids == nullptr: the position is the id.
-__device__ void mark_topk(const float* scores, const int32_t* ids, int n, int k, bool staged, SelShared& sm,
-                          uint32_t& thr, uint32_t& thr_id, bool& all_ties) {
-    auto key_at = [&](int i) -> uint32_t { return staged ? sm.keys[i] : score_key(scores[i]); };
-    if (staged) {
-        for (int i = threadIdx.x; i < n; i += kSelThreads) sm.keys[i] = score_key(scores[i]);
-        __syncthreads();
-    }
-    int want = k, ties = 0;
-    thr = radix_select_desc([&](int i, uint32_t& key) { key = key_at(i); return true; }, n, want, ties, sm);
-    all_ties = (want == ties);
-    thr_id = 0;
-    if (!all_ties) {
-        const uint32_t t = thr;
-        int want2 = want, ties2 = 0;
-        thr_id = radix_select_desc(
-            [&](int i, uint32_t& key) {
-                key = ~(uint32_t)(ids ? ids[i] : i);    // descending on ~id == ascending on id
-                return key_at(i) == t;
-            },
-            n, want2, ties2, sm);
-    }
-}
-
-__device__ __forceinline__ bool is_kept(uint32_t key, uint32_t idkey, uint32_t thr, uint32_t thr_id, bool all_ties) {
-    return key > thr || (key == thr && (all_ties || idkey >= thr_id));
-}
 
 // ---------------------------------------------------------------------------------------------
 // st3_select_topk
@@ -227,217 +131,9 @@ __global__ __launch_bounds__(256) void compact_rows_kernel(CompactArgs a) {
 // Decode-time eviction: ranking + move list + column update (one workgroup per sequence), then
 // a second kernel that applies the move list to every (b,h) strip of K and V.
 // ---------------------------------------------------------------------------------------------
-struct EvictArgs {
-    float* score_col;
-    int32_t* id_col;
-    int64_t col_stride;
-    int32_t* vis_len;
-    int32_t* kv_len;
-    int32_t sys_len, max_vis, max_kv, keep_count, mode;
-    int32_t* move_cnt;          // [B]
-    int32_t* moves;             // [B][max_moves][2] = (dst row, src row)
-    int32_t max_moves;
-    // extras used by the fused per-layer decode step
-    int32_t do_append;          // 1: after eviction, kv_len[b] += 1 (room for the new token's row)
-    int32_t capacity;
-    int32_t inline_apply;       // 1: HOLE_FILL moves are applied to K and V by this kernel
-    char* k;
-    char* v;
-    int64_t stride_b, stride_h, stride_t;   // bytes
-    int32_t H, vecs_per_row;
-    // deferred visual mass of the previous attention call on this workspace (all null: none)
-    const float* part_ml;
-    const float* logits;
-    int32_t* pending;           // [B][4] descriptor written by the attend kernel
-    int32_t nsplit_cap;
-    float* mass_dst;
-    int64_t mass_stride;
-};
-
-__device__ __forceinline__ bool flag_at(const SelShared& sm, int p) { return (sm.flags[p >> 5] >> (p & 31)) & 1u; }
-
-// Copies `count` rows (dst_i <- src_i, from the move list starting at entry `first`) on all 2*H
-// strips of sequence b.  Callers guarantee that no destination of the batch is a source of it.
-typedef uint32_t u32x4_v __attribute__((ext_vector_type(4)));
-
-// Address of 16-byte vector `idx` of a batch of row moves: idx enumerates (move, strip, vector).
-__device__ __forceinline__ char* move_addr(const EvictArgs& a, int b, const int32_t* mv, int first, int idx, int which) {
-    const int strips = (a.k ? 2 : 1) * a.H;             // K may be absent (layers that keep V only)
-    const int per_move = strips * a.vecs_per_row;
-    const int i = first + idx / per_move;
-    const int rem = idx % per_move;
-    const int strip = rem / a.vecs_per_row, vec = rem % a.vecs_per_row;
-    char* base = ((a.k && strip < a.H) ? a.k : a.v) + b * a.stride_b + (int64_t)(strip % a.H) * a.stride_h +
-                 (int64_t)vec * 16;
-    return base + mv[2 * i + which] * a.stride_t;
-}
-
-// Copies `count` rows (dst_i <- src_i, from the move list starting at entry `first`) on all
-// strips of sequence b.  Callers guarantee that no destination of the batch is a source of it.
-__device__ __forceinline__ void copy_rows_all_strips(const EvictArgs& a, int b, const int32_t* mv, int first, int count) {
-    constexpr int UR = 16;                              // independent 16-byte loads in flight per thread
-    const int total = count * (a.k ? 2 : 1) * a.H * a.vecs_per_row;
-    for (int base = 0; base < total; base += UR * kSelThreads) {
-        u32x4_v tmp[UR];
-#pragma unroll
-        for (int u = 0; u < UR; ++u) {
-            const int idx = base + u * kSelThreads + (int)threadIdx.x;
-            if (idx < total) tmp[u] = *reinterpret_cast<const u32x4_v*>(move_addr(a, b, mv, first, idx, 1));
-        }
-#pragma unroll
-        for (int u = 0; u < UR; ++u) {
-            const int idx = base + u * kSelThreads + (int)threadIdx.x;
-            if (idx < total) *reinterpret_cast<u32x4_v*>(move_addr(a, b, mv, first, idx, 0)) = tmp[u];
-        }
-    }
-}
-
-__device__ __forceinline__ void evict_plan_body(const EvictArgs& a, SelShared& sm) {
-    const int b = blockIdx.x, tid = threadIdx.x;
-    const int n = max(0, min(a.vis_len[b], a.max_vis));
-    const int len = max(0, min(a.kv_len[b], a.max_kv));
-    const int k = a.keep_count < 0 ? n : min(a.keep_count, n);
-    int new_len = len, moves_left = 0;
-    if (a.pending != nullptr && a.mass_dst != nullptr) {
-        // finish the mass the previous attention call left pending: lengths are still the ones it saw
-        __shared__ float sm_hm[1024], sm_hrl[1024];
-        const int valid = a.pending[b * 4];
-        if (valid) {
-            const int nsplit = min(a.pending[b * 4 + 1], a.nsplit_cap);
-            const int chunk = max(a.pending[b * 4 + 2], 32);
-            const int ns = len > 0 ? min((len + chunk - 1) / chunk, nsplit) : 0;
-            head_norms(a.part_ml, b, a.H, ns, a.nsplit_cap, sm_hm, sm_hrl);
-            finish_mass(a.logits, b, a.H, a.capacity, sm_hm, sm_hrl, 0, n, a.mass_dst + b * a.mass_stride);
-            __syncthreads();                            // the ranking below may read these scores
-            if (tid == 0) a.pending[b * 4] = 0;
-        }
-    }
-    if (k < n && a.sys_len + n <= len) {                // something to evict, lengths consistent
-        float* scores = a.score_col + b * a.col_stride;
-        int32_t* ids = a.id_col + b * a.col_stride;
-        int32_t* mv = a.moves + (int64_t)b * a.max_moves * 2;
-        uint32_t thr = 0, thr_id = 0;
-        bool all_ties = true;
-        if (k > 0) mark_topk(scores, ids, n, k, true, sm, thr, thr_id, all_ties);
-        // flags -> LDS bitmap (one 32-bit word per 32 positions, built from wave ballots)
-        const int n_pad = (n + kSelThreads - 1) / kSelThreads * kSelThreads;
-        for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
-            const int p = p0 + tid;
-            bool keep = false;
-            if (p < n && k > 0) keep = is_kept(sm.keys[p], ~(uint32_t)ids[p], thr, thr_id, all_ties);
-            unsigned long long bal = __ballot(keep);
-            if (tid % kWave == 0) {
-                sm.flags[(p >> 5)] = (uint32_t)bal;
-                sm.flags[(p >> 5) + 1] = (uint32_t)(bal >> 32);
-            }
-        }
-        __syncthreads();
-        const int g = n - k;                            // rows evicted
-        const int r = len - (a.sys_len + n);            // rows behind the visual segment
-        int m = 0;                                      // moves inside the visual segment
-        if (a.mode == ST3_HOLE_FILL) {
-            int base_h = 0, base_f = 0;
-            for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
-                const int p = p0 + tid;
-                const bool kept = p < n && flag_at(sm, p);
-                const bool hole = p < k && !kept;
-                const bool fill = p >= k && kept;
-                int packed = (hole ? 1 : 0) | (fill ? (1 << 16) : 0);
-                int incl = block_incl_scan(packed, sm);
-                if (hole) mv[2 * (base_h + (incl & 0xffff) - 1)] = a.sys_len + p;
-                if (fill) mv[2 * (base_f + (incl >> 16) - 1) + 1] = a.sys_len + p;
-                __syncthreads();
-                if (tid == kSelThreads - 1) sm.red = incl;
-                __syncthreads();
-                base_h += sm.red & 0xffff;
-                base_f += sm.red >> 16;
-            }
-            m = min(base_h, base_f);                    // equal when the ids are distinct
-            __syncthreads();                            // move list visible to the whole block
-            for (int i = tid; i < m; i += kSelThreads) {    // sources >= k, destinations < k: disjoint
-                int dst = mv[2 * i] - a.sys_len, src = mv[2 * i + 1] - a.sys_len;
-                scores[dst] = scores[src];
-                ids[dst] = ids[src];
-            }
-            // refill the vacated end of the segment [k, n): from the END of the cache when at least
-            // g rows follow the segment, else all r following rows move down.  Either way sources
-            // and destinations are disjoint: r >= g -> src >= len-g >= sys+n; r < g -> dst < sys+k+r < sys+n.
-            const int cnt = min(g, r);
-            const int src0 = (r >= g) ? len - g : a.sys_len + n;
-            for (int j = tid; j < cnt; j += kSelThreads) {
-                mv[2 * (m + j)] = a.sys_len + k + j;
-                mv[2 * (m + j) + 1] = src0 + j;
-            }
-            moves_left = m + cnt;
-            if (a.inline_apply) {
-                __syncthreads();
-                copy_rows_all_strips(a, b, mv, 0, m);       // holes <- surviving tail of the segment
-                __syncthreads();                            // those reads are done before [k, n) is overwritten
-                copy_rows_all_strips(a, b, mv, m, cnt);
-                moves_left = 0;
-            }
-        } else {
-            // first hole = number of leading kept positions
-            int fh = n;
-            for (int p = tid; p < n; p += kSelThreads)
-                if (!flag_at(sm, p)) { fh = p; break; }
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) fh = min(fh, __shfl_xor(fh, off));
-            if (tid % kWave == 0) sm.wave_tot[tid / kWave] = fh;
-            __syncthreads();
-            fh = min(min(sm.wave_tot[0], sm.wave_tot[1]), min(sm.wave_tot[2], sm.wave_tot[3]));
-            __syncthreads();
-            int base = 0;
-            for (int p0 = 0; p0 < n_pad; p0 += kSelThreads) {
-                const int p = p0 + tid;
-                const bool kept = p < n && flag_at(sm, p);
-                float sv = 0.f; int32_t iv = 0;
-                if (kept) { sv = scores[p]; iv = ids[p]; }
-                int incl = block_incl_scan(kept ? 1 : 0, sm);       // contains barriers: loads precede stores
-                const int rank = base + incl - 1;
-                if (kept && p > fh) {
-                    scores[rank] = sv; ids[rank] = iv;
-                    mv[2 * (rank - fh)] = a.sys_len + rank;
-                    mv[2 * (rank - fh) + 1] = a.sys_len + p;
-                }
-                __syncthreads();
-                if (tid == kSelThreads - 1) sm.red = incl;
-                __syncthreads();
-                base += sm.red;
-            }
-            m = k - fh;
-            for (int j = tid; j < r; j += kSelThreads) {
-                mv[2 * (m + j)] = a.sys_len + k + j;
-                mv[2 * (m + j) + 1] = a.sys_len + n + j;
-            }
-            moves_left = m + r;
-        }
-        new_len = len - g;
-        if (tid == 0) a.vis_len[b] = k;
-    }
-    if (a.do_append && new_len < a.capacity) new_len += 1;
-    if (tid == 0) {
-        a.move_cnt[b] = moves_left;
-        a.kv_len[b] = new_len;
-    }
-}
-
 __global__ __launch_bounds__(kSelThreads) void evict_plan_kernel(EvictArgs a) {
     __shared__ SelShared sm;
-    evict_plan_body(a, sm);
-}
-
-// The same plan for several layers in one launch: grid (B, layers).  The evictions of a decode
-// step depend only on each layer's own score column and the retention table, never on the
-// activations of that step, so they can all be planned before the first layer's attention runs.
-constexpr int kPlanBatch = 16;
-struct EvictBatch {
-    EvictArgs layer[kPlanBatch];
-};
-
-__global__ __launch_bounds__(kSelThreads) void evict_plan_batch_kernel(EvictBatch batch) {
-    __shared__ SelShared sm;
-    evict_plan_body(batch.layer[blockIdx.y], sm);
+    evict_plan_body(a, blockIdx.x, sm);
 }
 
 struct ApplyArgs {
@@ -493,12 +189,9 @@ st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st
 // evictions and STABLE mode go through evict_apply_kernel, which has a workgroup per strip.
 constexpr int kInlineEvict = 48;
 
-namespace {
-
-// Fills the plan-kernel arguments for one layer.  Returns false when the sizes are unsupported.
 st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                             float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count, int32_t mode,
-                            void* workspace, size_t workspace_bytes, int do_append, float* mass_dst,
+                            void* workspace, size_t workspace_bytes, int appended, float* mass_dst,
                             int64_t mass_stride, EvictArgs& ea, bool& needs_apply) {
     const int B = shape->batch, H = shape->heads, D = shape->head_dim;
     if (seg->max_vis_len > kSelLdsKeys) return ST3_ERR_UNSUPPORTED;
@@ -515,7 +208,7 @@ st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv,
     ea.move_cnt = reinterpret_cast<int32_t*>(ws + wl.moves_cnt);
     ea.moves = reinterpret_cast<int32_t*>(ws + wl.moves);
     ea.max_moves = wl.max_moves;
-    ea.do_append = do_append; ea.capacity = kv->capacity;
+    ea.appended = appended; ea.capacity = kv->capacity;
     ea.inline_apply = evicting && mode == ST3_HOLE_FILL && (seg->max_vis_len - keep_count) <= kInlineEvict;
     ea.k = reinterpret_cast<char*>(kv->k); ea.v = reinterpret_cast<char*>(kv->v);
     ea.stride_b = kv->stride_b * eb; ea.stride_h = kv->stride_h * eb; ea.stride_t = kv->stride_t * eb;
@@ -531,7 +224,33 @@ st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv,
     return ST3_OK;
 }
 
-void launch_apply(const EvictArgs& ea, int B, hipStream_t st) {
+void launch_evict_plan(const EvictArgs& ea, int B, hipStream_t st) {
+    evict_plan_kernel<<<B, kSelThreads, 0, st>>>(ea);
+}
+
+// Up to kPlanBatch plans travel by value in the kernel arguments; grid (B, layers of the batch).
+constexpr int kPlanBatch = 16;
+struct EvictBatch {
+    EvictArgs layer[kPlanBatch];
+};
+static_assert(sizeof(EvictBatch) <= 4000, "plans of one batch must fit the kernel argument segment");
+
+__global__ __launch_bounds__(kSelThreads) void evict_plan_batch_kernel(EvictBatch batch) {
+    __shared__ SelShared sm;
+    evict_plan_body(batch.layer[blockIdx.y], blockIdx.x, sm);
+}
+
+void launch_evict_plan_batch(const EvictArgs* plans, int n, int B, hipStream_t st) {
+    for (int i0 = 0; i0 < n; i0 += kPlanBatch) {
+        const int cnt = n - i0 < kPlanBatch ? n - i0 : kPlanBatch;
+        EvictBatch batch;
+        for (int i = 0; i < cnt; ++i) batch.layer[i] = plans[i0 + i];
+        for (int i = cnt; i < kPlanBatch; ++i) batch.layer[i] = EvictArgs{};
+        evict_plan_batch_kernel<<<dim3(B, cnt), kSelThreads, 0, st>>>(batch);
+    }
+}
+
+void launch_evict_apply(const EvictArgs& ea, int B, hipStream_t st) {
     ApplyArgs aa{};
     aa.k = ea.k; aa.v = ea.v;
     aa.stride_b = ea.stride_b; aa.stride_h = ea.stride_h; aa.stride_t = ea.stride_t;
@@ -540,54 +259,22 @@ void launch_apply(const EvictArgs& ea, int B, hipStream_t st) {
     evict_apply_kernel<<<dim3(2 * ea.H, B), 256, 0, st>>>(aa);
 }
 
-}  // namespace
 
 // Eviction plan (+ optional append bookkeeping, deferred-mass finish and in-kernel row moves),
 // then the separate move kernel when the plan kernel does not move the rows itself.
-//   do_append:  kv_len[b] += 1 after the eviction (the attention kernel writes the row)
+//   appended:   the attention kernel has just written one row beyond kv_len[b]; it is counted here
 //   mass_dst:   where a mass left pending by the previous attention call is finished (null: skip)
 st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                                   float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
                                   int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st,
-                                  int do_append, float* mass_dst, int64_t mass_stride) {
+                                  int appended, float* mass_dst, int64_t mass_stride) {
     EvictArgs ea;
     bool needs_apply = false;
     st3_status s = build_evict_args(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, workspace,
-                                    workspace_bytes, do_append, mass_dst, mass_stride, ea, needs_apply);
+                                    workspace_bytes, appended, mass_dst, mass_stride, ea, needs_apply);
     if (s != ST3_OK) return s;
-    evict_plan_kernel<<<shape->batch, kSelThreads, 0, st>>>(ea);
-    if (needs_apply) launch_apply(ea, shape->batch, st);
-    return check_launch();
-}
-
-// Plans the evictions of `n` layers with one launch per kPlanBatch layers (then the move kernel
-// for the layers whose evictions are too large to be moved by the plan kernel itself).
-st3_status enqueue_plan_layers(const st3_attn_shape* shape, int n, const st3_layer_step* layers, int32_t mode,
-                               hipStream_t st) {
-    const int B = shape->batch;
-    // validate everything first: nothing is enqueued on an error
-    for (int i = 0; i < n; ++i) {
-        EvictArgs ea;
-        bool na;
-        st3_status s = build_evict_args(shape, &layers[i].kv, &layers[i].seg, layers[i].score_col, layers[i].id_col,
-                                        layers[i].col_stride, layers[i].keep_count, mode, layers[i].workspace,
-                                        layers[i].workspace_bytes, 1, layers[i].vis_mass, layers[i].mass_stride, ea, na);
-        if (s != ST3_OK) return s;
-    }
-    for (int i0 = 0; i0 < n; i0 += kPlanBatch) {
-        const int cnt = n - i0 < kPlanBatch ? n - i0 : kPlanBatch;
-        EvictBatch batch;
-        bool needs_apply[kPlanBatch];
-        for (int i = 0; i < cnt; ++i) {
-            const st3_layer_step& L = layers[i0 + i];
-            build_evict_args(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_count, mode,
-                             L.workspace, L.workspace_bytes, 1, L.vis_mass, L.mass_stride, batch.layer[i],
-                             needs_apply[i]);
-        }
-        evict_plan_batch_kernel<<<dim3(B, cnt), kSelThreads, 0, st>>>(batch);
-        for (int i = 0; i < cnt; ++i)
-            if (needs_apply[i]) launch_apply(batch.layer[i], B, st);
-    }
+    launch_evict_plan(ea, shape->batch, st);
+    if (needs_apply) launch_evict_apply(ea, shape->batch, st);
     return check_launch();
 }
 

@@ -63,12 +63,11 @@ class Generation:
     def __init__(self, layers: int, heads: int, head_dim: int, dtype: torch.dtype, batch: int,
                  n_sys: int, n_vis: int, n_txt: int, steps: int, keep: Sequence[Sequence[int]],
                  window: int = 1, mode: str = "static", compact_mode: int = st3.ST3_HOLE_FILL,
-                 defer_mass: bool = False, device: str = "cuda:0"):
+                 device: str = "cuda:0"):
         self.L, self.H, self.d, self.B = layers, heads, head_dim, batch
         self.n_sys, self.n_vis, self.n_txt, self.T = n_sys, n_vis, n_txt, steps
         self.keep = [list(r) for r in keep]
         self.window, self.mode, self.compact_mode = window, mode, compact_mode
-        self.defer_mass = defer_mass
         self.dtype, self.device = dtype, device
         self.shape = st3.make_shape(batch, heads, head_dim, st3._dtype_code(torch.empty(0, dtype=dtype)))
         self.N0 = n_sys + n_vis + n_txt
@@ -143,33 +142,58 @@ class Generation:
         lc.vis_len.fill_(alive)
         lc.kv_len.fill_(n_l)
         lc.h_vis, lc.h_kv = alive, n_l
+        self._decoding = False
         return out, lc.mass[:, :alive]
 
     # ------------------------------------------------------------------------------------
-    def decode_layer(self, l: int, t: int, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor):
-        """q, k_new, v_new: device [B,H,d].  Alg. 3, VTA branch, layer l of step t >= 1.
+    def begin_decode(self):
+        """The eviction that precedes the FIRST decode step (Alg. 3 truncates a layer's cache before
+        its attention at every step; later steps do it right after the previous step's attention)."""
+        for l, lc in enumerate(self.layers):
+            target = min(self.keep[l][1], lc.h_vis) if self.T >= 1 else lc.h_vis
+            if target < lc.h_vis:
+                seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len)
+                st3.st3_select_compact_layer(self.shape, lc.kv, seg, lc.score, lc.ids, target, self.compact_mode,
+                                             lc.ws)
+                lc.h_kv -= lc.h_vis - target
+                lc.h_vis = target
+        self._decoding = True
 
-        Returns (out [B,H,d] (reused buffer), mass view [B, keep[l][t]]).  With defer_mass the
-        mass view is filled by the layer's next step or by finalize_mass().
-        """
+    def _keep_after(self, l: int, t: int) -> int:
+        """Visual rows layer l holds after step t's attention = what step t+1 attends over."""
         lc = self.layers[l]
-        target = min(self.keep[l][t], lc.h_vis)
-        keep_count = target if target < lc.h_vis else -1
-        seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len)
-        mass_dst = lc.score if self.mode == "current" else lc.mass
-        st3.st3_decode_layer_step(self.shape, lc.kv, seg, lc.score, lc.ids, keep_count, self.compact_mode,
-                                  q, k_new, v_new, self.dec_out, mass_dst, lc.ws, defer_mass=self.defer_mass)
-        lc.h_kv = lc.h_kv - (lc.h_vis - target) + 1
-        lc.h_vis = target
-        return self.dec_out, mass_dst[:, :target]
+        return min(self.keep[l][t + 1], lc.h_vis) if t + 1 <= self.T else lc.h_vis
 
     def _mass_dst(self, lc: LayerCache) -> torch.Tensor:
         return lc.score if self.mode == "current" else lc.mass
+
+    def decode_layer(self, l: int, t: int, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor):
+        """q, k_new, v_new: device [B,H,d].  Alg. 3, VTA branch, layer l of step t >= 1: append, attend,
+        then evict down to what step t+1 keeps.
+
+        Returns (out [B,H,d] (reused buffer), mass view [B, keep[l][t]] in the cache order the
+        attention saw; in "current" mode the mass lives in the score column, which the eviction
+        compacts, so only its first keep[l][t+1] entries (the survivors) remain meaningful).
+        """
+        if not getattr(self, "_decoding", False):
+            self.begin_decode()
+        lc = self.layers[l]
+        n_attn = lc.h_vis
+        target = self._keep_after(l, t)
+        seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len)
+        mass_dst = self._mass_dst(lc)
+        st3.st3_decode_layer_step(self.shape, lc.kv, seg, lc.score, lc.ids, target if target < lc.h_vis else -1,
+                                  self.compact_mode, q, k_new, v_new, self.dec_out, mass_dst, lc.ws)
+        lc.h_kv = lc.h_kv + 1 - (lc.h_vis - target)
+        lc.h_vis = target
+        return self.dec_out, mass_dst[:, :n_attn]
 
     def decode_step(self, t: int, qkv: torch.Tensor):
         """All layers of decode step t from one library call.  qkv: device [L, 3, B, H, d]
         (q, k_new, v_new per layer).  Returns dec_out_all [L, B, H, d] (reused buffer)."""
         assert qkv.is_contiguous() and tuple(qkv.shape) == (self.L, 3, self.B, self.H, self.d)
+        if not getattr(self, "_decoding", False):
+            self.begin_decode()
         if self._steps is None:
             arr = (st3.LayerStep * self.L)()
             for l, lc in enumerate(self.layers):
@@ -187,22 +211,14 @@ class Generation:
         one = self.B * self.H * self.d * self._eb
         for l, lc in enumerate(self.layers):
             s = arr[l]
-            target = min(self.keep[l][t], lc.h_vis)
-            s.keep_count = target if target < lc.h_vis else -1
+            target = self._keep_after(l, t)
+            s.keep_after = target if target < lc.h_vis else -1
             s.seg.max_vis_len, s.seg.max_kv_len = lc.h_vis, lc.h_kv
             s.q, s.k_new, s.v_new = base + (3 * l) * one, base + (3 * l + 1) * one, base + (3 * l + 2) * one
-            lc.h_kv = lc.h_kv - (lc.h_vis - target) + 1
+            lc.h_kv = lc.h_kv + 1 - (lc.h_vis - target)
             lc.h_vis = target
-        st3.st3_decode_step(self.shape, arr, self.L, self.compact_mode, self.defer_mass)
+        st3.st3_decode_step(self.shape, arr, self.L, self.compact_mode)
         return self.dec_out_all
-
-    def finalize_mass(self, l: int):
-        """Finishes the mass a deferred step left pending for layer l."""
-        lc = self.layers[l]
-        seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len)
-        mass_dst = self._mass_dst(lc)
-        st3.st3_decode_mass_finalize(self.shape, lc.kv, seg, mass_dst, lc.ws)
-        return mass_dst[:, :lc.h_vis]
 
     def kv_lens(self) -> List[int]:
         return [lc.h_kv for lc in self.layers]

@@ -1,7 +1,7 @@
 """Parity at the full sizes of the BASELINE workloads, in the launch configuration bench.py times.
 
 Each workload runs at its full shape and batch through the same calls bench.py uses (prefill per
-layer, then st3_decode_step with deferred mass).  The oracle cannot afford the whole batch, so it
+layer, then st3_decode_step).  The oracle cannot afford the whole batch, so it
 replays ONE sampled sequence from the original inputs - every head of the first `oracle_layers`
 layers, prefill and the first decode steps - and everything the GPU produced for that sequence
 and those layers is compared with it.  (Layers only interact through the selection chain of the
@@ -57,7 +57,7 @@ def test_full_shape_one_sequence_replayed_by_oracle(name, batch, sample_b, oracl
     assert np.array_equal(np.array(keep_full), orc.schedule_for(w))
     keep = [row[:T + 1] for row in keep_full[:oracle_layers]]
     gen = pipeline.Generation(w.layers, w.heads, w.head_dim, torch.bfloat16, batch, w.n_sys, w.n_vis, w.n_txt,
-                              w.steps, keep_full, defer_mass=True, device=DEV)
+                              w.steps, keep_full, device=DEV)
     g = torch.Generator(device=DEV)
     g.manual_seed(20241227)
     shape_p = (batch, w.heads, w.n_prompt, w.head_dim)
@@ -85,19 +85,21 @@ def test_full_shape_one_sequence_replayed_by_oracle(name, batch, sample_b, oracl
         for d in dec_dev:
             d[:, 0] = (d[:, 0].float() + ud).to(torch.bfloat16)
     dec_host = [d[:LO, :, sample_b:sample_b + 1].float().cpu().numpy() for d in dec_dev]
-    step_out, step_ids, step_mass_prev = [], [], []
+    step_out, step_ids, step_mass = [], [], []
+    gen.begin_decode()
     for t in range(1, T + 1):
+        # the rows step t attends over are in place before the call (evicted after step t-1's attention)
+        step_ids.append([gen.layers[l].ids[sample_b, :gen.layers[l].h_vis].cpu().numpy() for l in range(LO)])
+        for l in range(w.layers):
+            assert gen.layers[l].vis_len.cpu().tolist() == [keep_full[l][t]] * batch
         outs = gen.decode_step(t, dec_dev[t - 1])
         torch.cuda.synchronize()
         step_out.append(to_np64(outs[:LO, sample_b]))
-        step_ids.append([gen.layers[l].ids[sample_b, :gen.layers[l].h_vis].cpu().numpy() for l in range(LO)])
-        # with deferred mass, lc.mass now holds the PREVIOUS step's mass (in that step's order)
-        step_mass_prev.append([to_np64(gen.layers[l].mass[sample_b]) for l in range(LO)])
-    final_mass = [to_np64(gen.finalize_mass(l)[sample_b]) for l in range(LO)]
-    torch.cuda.synchronize()
+        step_mass.append([to_np64(gen.layers[l].mass[sample_b]) for l in range(LO)])   # in the order attended
     for l in range(w.layers):
-        assert gen.layers[l].kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, keep_full[l][T], w.n_txt, T)] * batch
-        assert gen.layers[l].vis_len.cpu().tolist() == [keep_full[l][T]] * batch
+        k_end = keep_full[l][T + 1] if T < w.steps else keep_full[l][T]
+        assert gen.layers[l].kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, k_end, w.n_txt, T)] * batch
+        assert gen.layers[l].vis_len.cpu().tolist() == [k_end] * batch
 
     # ---- the oracle replays the sampled sequence from the original inputs -----------------------
     print(f"{name}: oracle replay of sequence {sample_b} ({LO} layers, prefill + {T} decode steps)", flush=True)
@@ -120,28 +122,19 @@ def test_full_shape_one_sequence_replayed_by_oracle(name, batch, sample_b, oracl
         assert n_alive == LO, "prefill selection diverged on a near-tie; pick another sampled sequence"
     ok = np.zeros(LO, bool)
     ok[:n_alive] = True
-    prev = None
     for t in range(1, T + 1):
         rho_before = [ref.rho[l][0].copy() for l in range(LO)]
         ids_before = [ref.ids[l][0].copy() for l in range(LO)]
         s = ref.decode_step(lambda l: (dec_host[t - 1][l, 0], dec_host[t - 1][l, 1], dec_host[t - 1][l, 2]))
-        cur = []
         for l in range(LO):
             ids = step_ids[t - 1][l]
             if ok[l]:
                 ok[l] = assert_selection_matches(ids, rho_before[l], ids_before[l], keep[l][t], f"t={t} l={l}")
             if not ok[l]:
-                cur.append(None)
                 continue
             assert_attention_close(step_out[t - 1][l], s["out"][l][0], "bf16", f"decode out t={t} l={l}")
             pos = np.searchsorted(s["ids"][l][0], ids)
-            cur.append(s["mass"][l][0][pos])
-            if prev is not None and prev[l] is not None:
-                assert_mass_close(step_mass_prev[t - 1][l][:len(prev[l])], prev[l], f"deferred mass t={t - 1} l={l}")
-        prev = cur
-    for l in range(LO):
-        if prev[l] is not None:
-            assert_mass_close(final_mass[l][:len(prev[l])], prev[l], f"final mass l={l}")
+            assert_mass_close(step_mass[t - 1][l][:len(ids)], s["mass"][l][0][pos], f"decode mass t={t} l={l}")
     if not w.planted:
         assert ok.mean() > 0.8
     del gen

@@ -286,6 +286,73 @@ def test_select_compact_layer(mode, dtype, D):
 
 
 # ---------------------------------------------------------------------------
+# fused layer step: append + attention + mass, then the eviction for the next step (Alg. 3)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("mode", [st3.ST3_STABLE, st3.ST3_HOLE_FILL])
+@pytest.mark.parametrize("dtype,D,H,lens,keep_after", [
+    ("bf16", 128, 4, [192, 191, 193, 64], 20),     # the appended row opens a chunk of its own / closes one
+    ("bf16", 128, 4, [256, 255, 128, 97], -1),     # no eviction: lengths only grow
+    ("f32", 64, 3, [300, 33, 128, 257], 0),        # everything visual goes
+    ("bf16", 128, 2, [420, 419, 300, 389], 7),     # more than the in-kernel row-move limit is evicted
+])
+def test_decode_layer_step(mode, dtype, D, H, lens, keep_after):
+    print(f"layer_step mode={mode} dtype={dtype} lens={lens} keep_after={keep_after}", flush=True)
+    rng = np.random.default_rng(zlib.crc32(repr((dtype, D, H, lens, keep_after)).encode()))
+    B, ns = len(lens), 6
+    cap = max(lens) + 3
+    vis = [min(L - ns - 2, 100 + 40 * b) for b, L in enumerate(lens)]
+    nv = max(vis)
+    sigma = 1.0 if dtype == "f32" else 1.43
+    K = rand_values(rng, (B, H, cap, D), dtype, sigma); V = rand_values(rng, (B, H, cap, D), dtype, sigma)
+    q, kn, vn = (rand_values(rng, (B, H, D), dtype, sigma) for _ in range(3))
+    score = rng.standard_normal((B, nv)).astype(np.float32)
+    ids = np.stack([rng.permutation(2000)[:nv] for _ in range(B)]).astype(np.int32)
+    shape = st3.make_shape(B, H, D, CODE[dtype])
+    dK, dV = to_dev(K, dtype), to_dev(V, dtype)
+    d_score, d_ids = torch.from_numpy(score.copy()).to(DEV), torch.from_numpy(ids.copy()).to(DEV)
+    out = torch.zeros((B, H, D), dtype=TORCH_DTYPE[dtype], device=DEV)
+    mass = torch.full((B, nv + 2), -7.0, dtype=torch.float32, device=DEV)
+    vis_len, kv_len = _i32(vis), _i32(lens)
+    seg = st3.segments(ns, nv, max(lens), vis_len, kv_len)
+    st3.st3_decode_layer_step(shape, st3.kv_layer(dK, dV), seg, d_score, d_ids, keep_after, mode, to_dev(q, dtype),
+                              to_dev(kn, dtype), to_dev(vn, dtype), out, mass, _ws(shape, cap, nv))
+    torch.cuda.synchronize()
+    got_o, got_m = to_np64(out), to_np64(mass)
+    gK, gV = dK.float().cpu().numpy(), dV.float().cpu().numpy()
+    g_ids, g_score = d_ids.cpu().numpy(), d_score.cpu().numpy()
+    for b in range(B):
+        L, nb = lens[b], vis[b]
+        Kb = np.concatenate([K[b, :, :L], kn[b][:, None]], axis=1)      # what the attention must see
+        Vb = np.concatenate([V[b, :, :L], vn[b][:, None]], axis=1)
+        o, m, _ = orc.decode_attention(q[b:b + 1], Kb[None], Vb[None], ns, nb)
+        assert_attention_close(got_o[b], o[0], dtype, f"b={b}")
+        assert_mass_close(got_m[b, :nb], m[0], f"b={b}")
+        assert np.all(got_m[b, nb:] == -7.0)
+        kb = nb if keep_after < 0 else min(keep_after, nb)
+        assert vis_len[b].item() == kb and kv_len[b].item() == L + 1 - (nb - kb), b
+        pos = orc.select_topk(score[b, :nb].astype(np.float64), ids[b, :nb], kb)
+        got_ids = g_ids[b, :kb]
+        if mode == st3.ST3_STABLE or kb == nb:
+            assert np.array_equal(got_ids, ids[b, pos])
+        else:
+            assert sorted(got_ids.tolist()) == sorted(ids[b, pos].tolist())
+        where = {int(t): p for p, t in enumerate(ids[b, :nb])}
+        order = np.array([where[int(t)] for t in got_ids], dtype=np.int64)
+        assert np.array_equal(g_score[b, :kb], score[b, order])
+        assert np.array_equal(gK[b][:, :ns], K[b][:, :ns])
+        assert np.array_equal(gK[b][:, ns:ns + kb], Kb[:, ns + order]) and np.array_equal(gV[b][:, ns:ns + kb], Vb[:, ns + order])
+        # rows behind the segment (text, generated, the new token): the same rows, K and V moved together
+        tail_src = np.arange(ns + nb, L + 1)
+        got_tail_K, got_tail_V = gK[b][:, ns + kb:kv_len[b].item()], gV[b][:, ns + kb:kv_len[b].item()]
+        key = {Kb[0, r].tobytes(): int(r) for r in tail_src}
+        srcs = [key[got_tail_K[0, j].tobytes()] for j in range(got_tail_K.shape[1])]
+        assert sorted(srcs) == tail_src.tolist()
+        if mode == st3.ST3_STABLE:
+            assert srcs == tail_src.tolist()
+        assert np.array_equal(got_tail_K, Kb[:, srcs]) and np.array_equal(got_tail_V, Vb[:, srcs])
+
+
+# ---------------------------------------------------------------------------
 # prefill attention + mass
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype,D,B,H,n,ns,nv,W", [

@@ -16,15 +16,13 @@ from workloads import decode_qkv, get_workload, prefill_qkv
 pytestmark = pytest.mark.gpu
 
 
-def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None, defer=False,
-                     whole_step=False):
+def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None, whole_step=False):
     T = w.steps if steps is None else steps
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
     keep_np = np.array(keep)
     assert np.array_equal(keep_np, orc.schedule_for(w)[:, :T + 1])
     gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt,
-                              T, keep, window=window, mode=mode, compact_mode=compact_mode, defer_mass=defer,
-                              device=DEV)
+                              T, keep, window=window, mode=mode, compact_mode=compact_mode, device=DEV)
     ref = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, keep_np, window=window, mode=mode)
     pre = [prefill_qkv(w, l, B) for l in range(w.layers)]
     r = ref.prefill(lambda l: pre[l])
@@ -63,7 +61,8 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
             assert_attention_close(got_o[b], r["out"][l][b], w.dtype, f"prefill out l={l} b={b}")
             assert_mass_close(got_m[b], r["mass"][l][b], f"prefill mass l={l} b={b}")
             assert_mass_close(lc.score[b, :lc.h_vis].double().cpu().numpy(), ref.rho[l][b], f"rho l={l} b={b}")
-    held = {}                                     # deferred mode: (ids, oracle mass) of the previous step per (l, b)
+    gen.begin_decode()                            # the eviction ahead of the first step (Alg. 3)
+    torch.cuda.synchronize()
     for t in range(1, T + 1):
         if t % 16 == 1:
             print(f"{w.name} decode step {t}", flush=True)
@@ -71,6 +70,17 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
         rho_before = [[x.copy() for x in ref.rho[l]] for l in range(w.layers)]
         ids_before = [[x.copy() for x in ref.ids[l]] for l in range(w.layers)]
         s = ref.decode_step(lambda l: dec[l])
+        # the rows each layer attends over at step t are already in place: the kept set of step t
+        ids_attn = []
+        for l in range(w.layers):
+            lc = gen.layers[l]
+            assert lc.vis_len.cpu().tolist() == [keep[l][t]] * B
+            assert lc.kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, keep[l][t], w.n_txt, t) - 1] * B
+            assert lc.h_kv + 1 == s["kv_len"][l][0]
+            for b in range(B):
+                if not diverged[l, b]:
+                    check_sets(l, b, rho_before[l][b], ids_before[l][b], keep[l][t], f"t={t} l={l} b={b}")
+            ids_attn.append(lc.ids[:, :lc.h_vis].cpu().numpy())
         if whole_step:                              # one library call for all layers of the step
             qkv = torch.stack([torch.stack([to_dev(x, w.dtype) for x in dec[l]]) for l in range(w.layers)]).contiguous()
             outs = gen.decode_step(t, qkv)
@@ -78,48 +88,32 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
         for l in range(w.layers):
             lc = gen.layers[l]
             if whole_step:
-                out, mass = outs[l], gen._mass_dst(lc)[:, :lc.h_vis]
+                out = outs[l]
             else:
                 q, k, v = (to_dev(x, w.dtype) for x in dec[l])
-                out, mass = gen.decode_layer(l, t, q, k, v)
+                out, _ = gen.decode_layer(l, t, q, k, v)
                 torch.cuda.synchronize()
-            got_o, got_m = to_np64(out), to_np64(mass)
-            assert lc.vis_len.cpu().tolist() == [keep[l][t]] * B
-            assert lc.kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, keep[l][t], w.n_txt, t)] * B
-            assert lc.h_kv == s["kv_len"][l][0]
+            got_o = to_np64(out)
+            k_next = keep[l][t + 1] if t < T else keep[l][t]
+            assert lc.h_vis == k_next
+            assert lc.vis_len.cpu().tolist() == [k_next] * B
+            assert lc.kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, k_next, w.n_txt, t)] * B
+            ids_after = lc.ids[:, :lc.h_vis].cpu().numpy()
             for b in range(B):
-                if diverged[l, b]:
-                    continue
-                check_sets(l, b, rho_before[l][b], ids_before[l][b], keep[l][t], f"t={t} l={l} b={b}")
                 if diverged[l, b]:
                     continue
                 assert_attention_close(got_o[b], s["out"][l][b], w.dtype, f"decode out t={t} l={l} b={b}")
-                # mass comes back in cache order; map through the id column
-                ids = lc.ids[b, :lc.h_vis].cpu().numpy()
-                pos = np.searchsorted(s["ids"][l][b], ids)
-                if not defer:
-                    assert_mass_close(got_m[b], s["mass"][l][b][pos], f"decode mass t={t} l={l} b={b}")
-                elif mode == "static":
-                    # this call finished the PREVIOUS step's mass (in that step's cache order)
-                    if (l, b) in held:
-                        pids, pmass = held[(l, b)]
-                        assert_mass_close(lc.mass[b, :len(pids)].double().cpu().numpy(), pmass,
-                                          f"deferred mass of t={t - 1} l={l} b={b}")
-                    held[(l, b)] = (ids, s["mass"][l][b][pos])
-    if defer:
-        for l in range(w.layers):
-            m = gen.finalize_mass(l)
-            torch.cuda.synchronize()
-            lc = gen.layers[l]
-            for b in range(B):
-                if diverged[l, b]:
-                    continue
-                ids = lc.ids[b, :lc.h_vis].cpu().numpy()
-                pos = np.searchsorted(s["ids"][l][b], ids)
                 if mode == "static":
-                    assert_mass_close(to_np64(m)[b], s["mass"][l][b][pos], f"finalized mass l={l} b={b}")
+                    # the mass comes back in the cache order the attention saw; map through those ids
+                    pos = np.searchsorted(s["ids"][l][b], ids_attn[l][b])
+                    assert_mass_close(to_np64(lc.mass[b, :len(pos)]), s["mass"][l][b][pos],
+                                      f"decode mass t={t} l={l} b={b}")
                 else:
-                    assert_mass_close(to_np64(m)[b], ref.rho[l][b][pos], f"finalized score column l={l} b={b}")
+                    # the mass became the ranking column, which the eviction compacted with the rows
+                    pos = np.searchsorted(s["ids"][l][b], ids_after[b])
+                    assert np.array_equal(s["ids"][l][b][pos], ids_after[b])
+                    assert_mass_close(to_np64(lc.score[b, :lc.h_vis]), s["mass"][l][b][pos],
+                                      f"ranking column after t={t} l={l} b={b}")
     # KV bytes actually held == closed form
     assert gen.kv_bytes() == orc.kv_bytes(B, w.heads, w.head_dim, 2 if w.dtype == "bf16" else 4, ref.cache_lens())
     return near_ties, diverged
@@ -133,31 +127,32 @@ def test_tiny_workload_full(mode, compact_mode):
     assert not div.any(), "tiny workload resolved a near-tie differently from the oracle"
 
 
-@pytest.mark.parametrize("mode", ["static", "current"])
-def test_tiny_workload_deferred_mass(mode):
-    w = get_workload("tiny")
-    near, div = _run_and_compare(w, 2, mode=mode, defer=True)
-    assert not div.any()
-
-
-def test_13b_shape_cut_down_deferred_current():
+def test_13b_shape_cut_down_current_mode():
     w = dataclasses.replace(get_workload("llava15_13b"), layers=4, heads=8, steps=10,
                             step_schedule={"kind": "cos", "tau": 10})
-    _run_and_compare(w, 2, mode="current", defer=True)
+    _run_and_compare(w, 2, mode="current")
 
 
-@pytest.mark.parametrize("defer", [False, True])
-def test_tiny_workload_whole_step_call(defer):
+@pytest.mark.parametrize("mode", ["static", "current"])
+def test_tiny_workload_whole_step_call(mode):
     w = get_workload("tiny")
-    near, div = _run_and_compare(w, 2, defer=defer, whole_step=True)
+    near, div = _run_and_compare(w, 2, mode=mode, whole_step=True)
     assert not div.any()
 
 
 def test_many_layers_whole_step_call_current_mode():
-    """More layers than one plan launch takes (16), deferred mass feeding the next step's ranking."""
+    """Every layer's eviction rides in the next layer's launch; each step's mass feeds the next ranking."""
     w = dataclasses.replace(get_workload("llava15_7b"), layers=19, heads=2, steps=5, n_vis=120, n_txt=9,
                             step_schedule={"kind": "cos", "tau": 6})
-    _run_and_compare(w, 2, mode="current", defer=True, whole_step=True)
+    _run_and_compare(w, 2, mode="current", whole_step=True)
+
+
+def test_large_evictions_whole_step_call():
+    """Evictions above the in-kernel row-move threshold: the separate row-move launch after a plan
+    that rode in the next layer's attention launch."""
+    w = dataclasses.replace(get_workload("llava15_13b"), layers=5, heads=4, steps=3, n_txt=20,
+                            step_schedule={"kind": "cos", "tau": 3})
+    _run_and_compare(w, 2, whole_step=True)
 
 
 def test_tiny_workload_batched_window():
