@@ -222,9 +222,9 @@ ST3_EXPORT st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
  * One whole decode step over `n_layers` layers from a single host call (Alg. 3, VTA branch, the
  * loop over l).  `layers` is a HOST array; entry i carries exactly the arguments
  * st3_decode_layer_step takes for that layer.  The result is the same as calling
- * st3_decode_layer_step for i = 0 .. n_layers-1 in order.  Step (2) of layer i-1 does not depend
- * on layer i's attention (nor the other way round), so it runs in spare workgroups of layer i's
- * attention launch instead of a launch of its own: one launch per layer plus one at the end.
+ * st3_decode_layer_step for i = 0 .. n_layers-1 in order.  Step (2) of a layer depends on that
+ * layer's attention only, so all layers attend first (one launch each) and their steps (2) then
+ * run side by side, 16 layers per launch.  Every layer needs buffers and a workspace of its own.
  * ------------------------------------------------------------------------------------------- */
 typedef struct {
     st3_kv_layer kv;
