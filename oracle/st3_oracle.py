@@ -26,12 +26,17 @@ What is defined here, and the passage each part follows:
 * `overlap`, `cosine_similarity`          - Eq. 10 and Eq. 4-5 (diagnostics).
 * `Generation`                            - Alg. 3 end to end on given Q/K/V:
   prefill with progressive pruning, then decode steps with annealing.
+* `heredity_attention` and `Generation(lazy=...)` - Eq. 6 / Alg. 2 (QK
+  heredity): a lazy layer l computes Self-attn(Q^{l-n}, K^{l-n}, V^l), i.e. the
+  source layer's probabilities applied to its own values.
 
 Pins (tests/test_oracle_*.py): full attention at keep ratio 1 against a
 library SDPA in float64; softmax rows sum to 1; all-equal keys; permutation
 invariance; mass sums; brute-force top-k on all small cases; nestedness; the
 60 printed (L,S,R,P)->C rows of the paper's stride tables; beta closed forms;
-KV bytes against the paper's Table 2 baseline rows.  Accuracy/CIDEr/A100
+KV bytes against the paper's Table 2 baseline rows; QK heredity: equal values
+give back the source layer's output, the result is linear in V, one-hot values
+return the probabilities themselves.  Accuracy/CIDEr/A100
 latency figures of the paper are parity unpinned (they need datasets, trained
 weights and other systems).
 """
@@ -127,6 +132,13 @@ def decode_attention(q, K, V, n_sys: int, n_vis: int, scale: Optional[float] = N
             o[b, h] = ph @ V[b, h]
     mass = p[:, :, n_sys:n_sys + n_vis].mean(axis=1)
     return o, mass, p
+
+
+def heredity_attention(Q_src, K_src, V, scale: Optional[float] = None) -> np.ndarray:
+    """Eq. 6: the attention of a lazy layer, Self-attn(Q^{l-n}, K^{l-n}, V^l): the causal
+    probabilities of the source layer's queries and keys, applied to this layer's values.
+    Q_src, K_src, V: [B, H, n, d] -> [B, H, n, d]."""
+    return causal_attention(Q_src, K_src, V, scale)[0]
 
 
 # ---------------------------------------------------------------------------
@@ -295,9 +307,12 @@ def kv_len(n_sys: int, keep_lt: int, n_txt: int, t: int) -> int:
     return n_sys + keep_lt + n_txt + t
 
 
-def kv_bytes(B: int, H: int, d: int, elem_bytes: int, lens: Sequence[int]) -> int:
-    """KV-cache bytes: K and V, every layer, `lens[l]` keys each."""
-    return B * sum(2 * H * d * elem_bytes * int(n) for n in lens)
+def kv_bytes(B: int, H: int, d: int, elem_bytes: int, lens: Sequence[int],
+             value_only: Sequence[int] = ()) -> int:
+    """KV-cache bytes: K and V, every layer, `lens[l]` keys each.  Layers listed in
+    `value_only` (lazy layers of Alg. 2, which never form K) hold V alone."""
+    vo = set(int(l) for l in value_only)
+    return B * sum((1 if l in vo else 2) * H * d * elem_bytes * int(n) for l, n in enumerate(lens))
 
 
 # ---------------------------------------------------------------------------
@@ -313,16 +328,29 @@ class Generation:
                   system | alive visual (ascending id) | text | generated
     mode "static": rho is fixed at prefill (Alg. 3's top-index cache T[l]).
     mode "current": rho is replaced by the layer's own mass after every step.
+    lazy (Eq. 6, Alg. 2): {l: src} makes layer l a lazy layer of source layer src < l.  Its
+      Q and K inputs are ignored; its attention is Self-attn(Q^src, K^src, V^l), at prefill
+      and at every decode step, so its probabilities, mass, kept set and ranking are the
+      source's.  Lazy layers follow their source directly (src+1 .. src+n, the paper's
+      "28 -> 29~31") and share its row of the keep table; K[l] stays None for them.
     """
 
     def __init__(self, L: int, H: int, d: int, n_sys: int, n_vis: int, n_txt: int,
                  keep: np.ndarray, window: int = 1, mode: str = "static",
-                 scale: Optional[float] = None):
+                 scale: Optional[float] = None, lazy: Optional[Dict[int, int]] = None):
         self.L, self.H, self.d = L, H, d
         self.n_sys, self.n_vis, self.n_txt = n_sys, n_vis, n_txt
         self.keep = np.asarray(keep)
         assert self.keep.shape[0] == L
         self.window, self.mode, self.scale = window, mode, scale
+        self.lazy = dict(lazy or {})
+        for l, src in self.lazy.items():
+            if not (0 <= src < l < L) or src in self.lazy:
+                raise ValueError("a lazy layer needs a non-lazy source layer before it")
+            if any(m not in self.lazy or self.lazy[m] != src for m in range(src + 1, l)):
+                raise ValueError("lazy layers must follow their source directly")
+            if not np.array_equal(self.keep[l], self.keep[src]):
+                raise ValueError("a lazy layer keeps what its source keeps")
         self.ids: List[List[np.ndarray]] = []
         self.rho: List[List[np.ndarray]] = []
         self.K: List[List[np.ndarray]] = []
@@ -341,8 +369,13 @@ class Generation:
         res = {"out": [], "mass": [], "ids": [], "selected": []}
         prev_ids = prev_mass = None
         inherited = None      # per b: scores of the most recent prune event, cut to the alive set
+        src_QK = {}           # source layer -> its (Q, K) inputs, for the lazy layers behind it
         for l in range(L):
             Q, K, V = (np.asarray(x, F64) for x in qkv_of_layer(l))
+            if l in self.lazy:
+                Q, K = src_QK[self.lazy[l]]           # Eq. 6: Q^{l-n}, K^{l-n}
+            elif l in self.lazy.values():
+                src_QK[l] = (Q, K)
             B = Q.shape[0]
             if l == 0:
                 prev_ids = [np.arange(nv, dtype=np.int64) for _ in range(B)]
@@ -366,7 +399,8 @@ class Generation:
                                          V[b:b + 1][:, :, rows], ns, len(ids_l[b]),
                                          self.window, self.scale)
                 out_l.append(o[0]); mass_l.append(m[0])
-                Kc.append(K[b][:, rows].copy()); Vc.append(V[b][:, rows].copy())
+                Kc.append(None if l in self.lazy else K[b][:, rows].copy())
+                Vc.append(V[b][:, rows].copy())
                 # ranking column: the scores that last decided membership; a
                 # layer that precedes every prune event ranks by its own mass
                 rho_l.append(m[0].copy() if inherited[b] is None else inherited[b].copy())
@@ -384,8 +418,14 @@ class Generation:
         t = self.t
         ns = self.n_sys
         res = {"out": [], "mass": [], "ids": [], "kv_len": []}
+        src_q = {}
         for l in range(self.L):
             q, k, v = (np.asarray(x, F64) for x in qkv_of_layer(l))
+            src = self.lazy.get(l)
+            if src is not None:
+                q = src_q[src]                        # Eq. 6: the source layer's query ...
+            elif l in self.lazy.values():
+                src_q[l] = q
             B = q.shape[0]
             k_lt = int(self.keep[l, t])
             out_l, mass_l, len_l = [], [], []
@@ -395,16 +435,20 @@ class Generation:
                 if k_lt < nv:                  # Eq. 7: evict before this layer's attention
                     pos = select_topk(rho, ids, k_lt)
                     rows = np.concatenate([np.arange(ns), ns + pos,
-                                           np.arange(ns + nv, self.K[l][b].shape[1])])
-                    self.K[l][b] = self.K[l][b][:, rows]
+                                           np.arange(ns + nv, self.V[l][b].shape[1])])
+                    if src is None:
+                        self.K[l][b] = self.K[l][b][:, rows]
                     self.V[l][b] = self.V[l][b][:, rows]
                     self.ids[l][b] = ids = ids[pos]
                     self.rho[l][b] = rho = rho[pos]
-                self.K[l][b] = np.concatenate([self.K[l][b], k[b][:, None, :]], axis=1)
+                if src is None:
+                    self.K[l][b] = np.concatenate([self.K[l][b], k[b][:, None, :]], axis=1)
                 self.V[l][b] = np.concatenate([self.V[l][b], v[b][:, None, :]], axis=1)
-                o, m, _ = decode_attention(q[b:b + 1], self.K[l][b][None], self.V[l][b][None],
+                # ... and keys (its cache holds the same rows in the same order), this layer's values
+                Kb = self.K[l][b] if src is None else self.K[src][b]
+                o, m, _ = decode_attention(q[b:b + 1], Kb[None], self.V[l][b][None],
                                            ns, len(ids), self.scale)
-                out_l.append(o[0]); mass_l.append(m[0]); len_l.append(self.K[l][b].shape[1])
+                out_l.append(o[0]); mass_l.append(m[0]); len_l.append(self.V[l][b].shape[1])
                 if self.mode == "current":
                     self.rho[l][b] = m[0].copy()
             res["out"].append(out_l); res["mass"].append(mass_l)
@@ -412,4 +456,4 @@ class Generation:
         return res
 
     def cache_lens(self) -> List[int]:
-        return [self.K[l][0].shape[1] for l in range(self.L)]
+        return [self.V[l][0].shape[1] for l in range(self.L)]
