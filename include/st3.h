@@ -125,6 +125,8 @@ ST3_EXPORT st3_status st3_prefill_attention(const st3_attn_shape* shape, const s
  * KV append (KV-cache use of Sec. 4.3): writes k_new/v_new (DEVICE, contiguous [B,H,d]) at row
  * kv_len[b] of the layer's cache, then kv_len[b] += 1.  Host check: max_kv_len < capacity.
  * A sequence with kv_len[b] >= capacity is left unchanged (device-side guard).
+ * A layer that caches values only (a lazy layer of Alg. 2, which never forms K) passes
+ * kv->k == NULL and k_new == NULL.
  * ------------------------------------------------------------------------------------------- */
 ST3_EXPORT st3_status st3_kv_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                          const void* k_new, const void* v_new, void* stream);
@@ -140,10 +142,29 @@ ST3_EXPORT st3_status st3_kv_append(const st3_attn_shape* shape, const st3_kv_la
  * workgroups whose partial results a second kernel merges in a fixed order, so results are
  * reproducible run to run.
  * A sequence with kv_len[b] == 0 gets out = 0.
+ * The call leaves the scaled logit of every cached key and the softmax normalisers in the
+ * workspace (Alg. 2's attention cache U): st3_decode_attention_inherit reads them from there.
  * ------------------------------------------------------------------------------------------- */
 ST3_EXPORT st3_status st3_decode_attention(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
                                 const st3_segments* seg, void* out, float* vis_mass, int64_t mass_stride,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Decode attention of a lazy layer (QK heredity, Eq. 6 and Alg. 2): the layer inherits the softmax
+ * probabilities of its source layer l-n and applies them to its own values,
+ *   out[b,h,:] = sum_{j<kv_len[b]} p^{src}_j v_j .
+ * `src_workspace` is the workspace of the source layer's most recent st3_decode_attention (or
+ * fused step) call, made with the same shape and for the same step; `src_kv_capacity` is the
+ * capacity of the source layer's cache.  The lazy layer's cache must hold the same tokens in the
+ * same row order as the source's did during that call (same lengths, same evictions applied
+ * with the same ranking column).  Only kv->v is read (kv->k may be NULL): half the bytes of
+ * st3_decode_attention.  The visual mass of a lazy layer is its source's and is not recomputed.
+ * A sequence whose source call saw no keys gets out = 0.
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_decode_attention_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv,
+                                                   const st3_segments* seg, const void* src_workspace,
+                                                   size_t src_workspace_bytes, int32_t src_kv_capacity, void* out,
+                                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Top-k selection (Eq. 3: indices of the G highest scores).  Total order: higher score first,
@@ -190,6 +211,9 @@ ST3_EXPORT st3_status st3_compact_rows(void* rows, int32_t batch, int32_t inner,
  *                       at most 2*(evicted) rows move.  Valid for decode only, where softmax
  *                       attention does not depend on the order of cached keys.
  * max_vis_len / max_kv_len in `seg` must bound the lengths BEFORE the call.
+ * kv->k may be NULL for a layer that caches values only (lazy layer, Alg. 2).  The rearrangement
+ * is a function of (score_col, id_col, lengths, keep_count, mode) alone, so layers that hold
+ * equal columns end up with equal row orders.
  * ------------------------------------------------------------------------------------------- */
 ST3_EXPORT st3_status st3_select_compact_layer(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                                     float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
@@ -225,6 +249,8 @@ ST3_EXPORT st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
  * st3_decode_layer_step for i = 0 .. n_layers-1 in order.  Step (2) of a layer depends on that
  * layer's attention only, so all layers attend first (one launch each) and their steps (2) then
  * run side by side, 16 layers per launch.  Every layer needs buffers and a workspace of its own.
+ * Lazy layers (inherit_from >= 0) are available through this call only: a group's evictions must
+ * wait until its last lazy layer has attended, which the per-layer call cannot arrange.
  * ------------------------------------------------------------------------------------------- */
 typedef struct {
     st3_kv_layer kv;
@@ -233,6 +259,14 @@ typedef struct {
     int32_t*     id_col;
     int64_t      col_stride;
     int32_t      keep_after;        /* visual rows to keep after this step's attention; < 0: all */
+    int32_t      inherit_from;      /* < 0: ordinary layer.  Else this is a lazy layer (Eq. 6, Alg. 2) and the
+                                       value is the index, in the same array and before this entry, of its
+                                       source layer: q and k_new are ignored, kv.k may be NULL, the attention
+                                       applies the source's probabilities of this step to kv.v and v_new.
+                                       The source must be an ordinary layer with the same sys_len, max_*
+                                       bounds and keep_after; score_col/id_col/lengths are this layer's own
+                                       copies and must equal the source's, so that both evict alike.
+                                       vis_mass (may be NULL) receives the source's mass. */
     const void*  q;
     const void*  k_new;
     const void*  v_new;

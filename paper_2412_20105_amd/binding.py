@@ -26,7 +26,8 @@ ST3_ANNEAL_COS, ST3_ANNEAL_LINEAR, ST3_ANNEAL_EXP, ST3_ANNEAL_DROP, ST3_ANNEAL_N
 
 EXPORTED = [
     "st3_status_string", "st3_last_hip_error", "st3_version", "st3_workspace_bytes", "st3_workspace_init",
-    "st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_select_topk",
+    "st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_decode_attention_inherit",
+    "st3_select_topk",
     "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
     "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
     "st3_debug_set_prefill_path", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
@@ -65,7 +66,8 @@ class Segments(C.Structure):
 
 class LayerStep(C.Structure):
     _fields_ = [("kv", KvLayer), ("seg", Segments), ("score_col", C.c_void_p), ("id_col", C.c_void_p),
-                ("col_stride", C.c_int64), ("keep_after", C.c_int32), ("q", C.c_void_p), ("k_new", C.c_void_p),
+                ("col_stride", C.c_int64), ("keep_after", C.c_int32), ("inherit_from", C.c_int32), ("q", C.c_void_p),
+                ("k_new", C.c_void_p),
                 ("v_new", C.c_void_p), ("out", C.c_void_p), ("vis_mass", C.c_void_p), ("mass_stride", C.c_int64),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
@@ -96,6 +98,9 @@ def lib() -> C.CDLL:
         L.st3_kv_append.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_void_p, C.c_void_p]
         L.st3_decode_attention.argtypes = [P(AttnShape), C.c_void_p, P(KvLayer), P(Segments), C.c_void_p, C.c_void_p,
                                            C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.st3_decode_attention_inherit.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_size_t,
+                                                   C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.st3_decode_attention_inherit.restype = C.c_int
         L.st3_select_topk.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.st3_compact_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int32,
@@ -112,7 +117,8 @@ def lib() -> C.CDLL:
         L.st3_schedule_anneal.argtypes = [C.c_int32, C.c_double, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
         L.st3_kv_bytes.restype = C.c_int64
         L.st3_kv_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32]
-        for name in ("st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_select_topk",
+        for name in ("st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_decode_attention_inherit",
+    "st3_select_topk",
                      "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step",
                      "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal"):
             getattr(L, name).restype = C.c_int
@@ -156,9 +162,11 @@ def tensor4(t: torch.Tensor) -> Tensor4:
     return s
 
 
-def kv_layer(k: torch.Tensor, v: torch.Tensor) -> KvLayer:
-    assert k.dim() == 4 and k.stride() == v.stride() and k.stride(3) == 1 and k.is_cuda and v.is_cuda
-    s = KvLayer(k.data_ptr(), v.data_ptr(), k.stride(0), k.stride(1), k.stride(2), k.shape[2])
+def kv_layer(k: Optional[torch.Tensor], v: torch.Tensor) -> KvLayer:
+    """k is None for a layer that caches values only (lazy layer of QK heredity)."""
+    assert v.dim() == 4 and v.stride(3) == 1 and v.is_cuda
+    assert k is None or (k.stride() == v.stride() and k.shape == v.shape and k.is_cuda)
+    s = KvLayer(None if k is None else k.data_ptr(), v.data_ptr(), v.stride(0), v.stride(1), v.stride(2), v.shape[2])
     s._refs = (k, v)
     return s
 
@@ -214,7 +222,7 @@ def st3_prefill_attention(shape, q, k, v, n, sys_len, vis_len, score_window, out
 
 
 def st3_kv_append(shape, kv: KvLayer, seg: Segments, k_new, v_new, stream=None):
-    _check(lib().st3_kv_append(C.byref(shape), C.byref(kv), C.byref(seg), k_new.data_ptr(), v_new.data_ptr(),
+    _check(lib().st3_kv_append(C.byref(shape), C.byref(kv), C.byref(seg), _ptr(k_new), v_new.data_ptr(),
                                _stream(stream)), "st3_kv_append")
 
 
@@ -224,6 +232,15 @@ def st3_decode_attention(shape, q, kv: KvLayer, seg: Segments, out, vis_mass, wo
                                       _ptr(vis_mass), ms, workspace.data_ptr(),
                                       workspace.numel() * workspace.element_size(), _stream(stream)),
            "st3_decode_attention")
+
+
+def st3_decode_attention_inherit(shape, kv: KvLayer, seg: Segments, src_workspace, src_kv_capacity, out, workspace,
+                                 stream=None):
+    _check(lib().st3_decode_attention_inherit(C.byref(shape), C.byref(kv), C.byref(seg), src_workspace.data_ptr(),
+                                              src_workspace.numel() * src_workspace.element_size(), src_kv_capacity,
+                                              out.data_ptr(), workspace.data_ptr(),
+                                              workspace.numel() * workspace.element_size(), _stream(stream)),
+           "st3_decode_attention_inherit")
 
 
 def st3_select_topk(scores, tie_ids, n_dev, n, k, keep_mask, keep_idx, stream=None):

@@ -33,10 +33,15 @@ bool profile_take(hipEvent_t* start, hipEvent_t* stop) {
 }
 
 st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
+st3_status validate_kv_value_only(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
+st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                           int32_t max_kv_len, const void* v_new, const void* src_workspace,
+                           size_t src_workspace_bytes, int32_t src_capacity, void* out, void* workspace,
+                           size_t workspace_bytes, hipStream_t st);
 st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
                           const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
                           void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
-                          void* workspace, size_t workspace_bytes, hipStream_t st);
+                          bool keep_all_logits, void* workspace, size_t workspace_bytes, hipStream_t st);
 
 }  // namespace st3
 
@@ -111,6 +116,30 @@ static st3_status check_layer_step(const st3_attn_shape* shape, const st3_kv_lay
     return ST3_OK;
 }
 
+// A lazy layer of the whole-step call (Eq. 6, Alg. 2) against its source entry.
+static st3_status check_lazy_step(const st3_attn_shape* shape, const st3_layer_step& L, const st3_layer_step& S,
+                                  int32_t mode) {
+    st3_status s = validate_kv_value_only(shape, &L.kv, &L.seg);
+    if (s != ST3_OK) return s;
+    if (S.inherit_from >= 0) return ST3_ERR_INVALID_ARG;                 // the source must attend by itself
+    if (!L.v_new || !L.out || !L.workspace || !aligned16(L.v_new) || !aligned16(L.workspace))
+        return ST3_ERR_INVALID_ARG;
+    if (L.workspace == S.workspace) return ST3_ERR_INVALID_ARG;
+    if (L.seg.max_kv_len >= L.kv.capacity) return ST3_ERR_INVALID_ARG;
+    if (L.seg.sys_len != S.seg.sys_len || L.seg.max_vis_len != S.seg.max_vis_len ||
+        L.seg.max_kv_len != S.seg.max_kv_len || L.keep_after != S.keep_after)
+        return ST3_ERR_INVALID_ARG;                                      // both must hold and evict the same rows
+    if (L.vis_mass && L.mass_stride < L.seg.max_vis_len) return ST3_ERR_INVALID_ARG;
+    if (L.keep_after >= 0) {
+        if (!L.score_col || !L.id_col || L.col_stride < L.seg.max_vis_len) return ST3_ERR_INVALID_ARG;
+        if (L.score_col == S.score_col || L.id_col == S.id_col) return ST3_ERR_INVALID_ARG;  // own copies
+        if (mode != ST3_STABLE && mode != ST3_HOLE_FILL) return ST3_ERR_INVALID_ARG;
+    }
+    const DecodeWs wl = decode_ws(shape->batch, shape->heads, shape->head_dim, L.kv.capacity);
+    if (L.workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
+    return ST3_OK;
+}
+
 }  // namespace st3
 
 extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const st3_kv_layer* kv,
@@ -134,7 +163,7 @@ extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     // (1) attention over the cache plus the new token, whose row is read from k_new/v_new and stored on the way
     s = enqueue_decode(shape, q, kv, seg, seg->max_kv_len + 1, k_new, v_new, out, vis_mass, mass_stride,
-                       vis_mass != nullptr, true, workspace, workspace_bytes, st);
+                       vis_mass != nullptr, true, false, workspace, workspace_bytes, st);
     if (s != ST3_OK) return s;
     // (2) one workgroup per sequence: finish the mass, count the appended row, rank and evict for the next step
     launch_evict_plan(ea, shape->batch, st);
@@ -149,15 +178,26 @@ extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
     if (s != ST3_OK) return s;
     if (n_layers <= 0 || !layers) return ST3_ERR_INVALID_ARG;
     std::vector<EvictArgs> plan((size_t)n_layers);
-    std::vector<char> needs_apply((size_t)n_layers, 0);
+    std::vector<char> needs_apply((size_t)n_layers, 0), has_heirs((size_t)n_layers, 0);
+    for (int i = 0; i < n_layers; ++i)
+        if (layers[i].inherit_from >= 0 && layers[i].inherit_from < i) has_heirs[layers[i].inherit_from] = 1;
     for (int i = 0; i < n_layers; ++i) {
         const st3_layer_step& L = layers[i];
-        s = check_layer_step(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_after, mode, L.q,
-                             L.k_new, L.v_new, L.out, L.vis_mass, L.mass_stride, L.workspace, L.workspace_bytes);
+        const bool lazy = L.inherit_from >= 0;
+        if (lazy) {
+            if (L.inherit_from >= i) return ST3_ERR_INVALID_ARG;
+            s = check_lazy_step(shape, L, layers[L.inherit_from], mode);
+        } else {
+            s = check_layer_step(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_after, mode, L.q,
+                                 L.k_new, L.v_new, L.out, L.vis_mass, L.mass_stride, L.workspace, L.workspace_bytes);
+        }
         if (s != ST3_OK) return s;
         bool na = false;
+        // a lazy layer's mass is its source's: finished from the logits in the source's workspace
+        const st3_layer_step* S = lazy ? &layers[L.inherit_from] : nullptr;
         s = build_evict_args(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_after, mode,
-                             L.workspace, L.workspace_bytes, 1, L.vis_mass, L.mass_stride, plan[i], na);
+                             L.workspace, L.workspace_bytes, 1, L.vis_mass, L.mass_stride, plan[i], na,
+                             S ? S->workspace : nullptr, S ? S->kv.capacity : 0);
         if (s != ST3_OK) return s;
         needs_apply[i] = na ? 1 : 0;
     }
@@ -165,8 +205,15 @@ extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
     const int B = shape->batch;
     for (int i = 0; i < n_layers; ++i) {
         const st3_layer_step& L = layers[i];
-        s = enqueue_decode(shape, L.q, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.k_new, L.v_new, L.out, L.vis_mass,
-                           L.mass_stride, L.vis_mass != nullptr, true, L.workspace, L.workspace_bytes, st);
+        if (L.inherit_from >= 0) {
+            const st3_layer_step& S = layers[L.inherit_from];
+            s = enqueue_inherit(shape, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.v_new, S.workspace, S.workspace_bytes,
+                                S.kv.capacity, L.out, L.workspace, L.workspace_bytes, st);
+        } else {
+            s = enqueue_decode(shape, L.q, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.k_new, L.v_new, L.out, L.vis_mass,
+                               L.mass_stride, L.vis_mass != nullptr, true, has_heirs[i] != 0, L.workspace, L.workspace_bytes,
+                               st);
+        }
         if (s != ST3_OK) return s;
     }
     // every layer's plan (finish the mass, count the new row, rank, evict) in one launch per 16

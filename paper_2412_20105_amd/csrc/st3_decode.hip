@@ -55,11 +55,12 @@ struct DecodeArgs {
     const int32_t* vis_len;
     int32_t B, sys_len, max_vis, max_kv, H, nsplit, nsplit_cap, chunk, capacity;
     int32_t defer;          // 1: the mass of this call is finished later; mark it pending
+    int32_t keep_all_logits;  // 1: keep the logit of every key (a lazy layer will ask for them), else visual only
     float scale_l2;
     float* part_o;          // [B,H,nsplit_cap,D]   (nsplit > 1 only)
     float* part_ml;         // [B,H,nsplit_cap,2]
     float* logits;          // [B,H,capacity]; null when no mass is wanted
-    int32_t* pending;       // [B][4]: {valid, nsplit, chunk, -} of a mass still to be finished (null: none)
+    int32_t* pending;       // [B][4]: {mass still to be finished, nsplit, chunk, logits of this call present}
     const void* k_new;      // [B,H,D] rows of the token being appended (null: none); the cache row
     const void* v_new;      //         kv_len[b] is then taken from here and written to the cache
     void* out;              // [B,H,D]
@@ -86,6 +87,7 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
         a.pending[b * 4 + 0] = (a.logits != nullptr && len > 0 && a.defer) ? 1 : 0;
         a.pending[b * 4 + 1] = a.nsplit;
         a.pending[b * 4 + 2] = a.chunk;
+        a.pending[b * 4 + 3] = (a.logits != nullptr && len > 0 && a.keep_all_logits) ? 1 : 0;
     }
     if (len <= 0) {                                  // empty sequence: out = 0, no mass
         if (split == 0 && tid < D) store_out<T>(a.out, bh * D + tid, 0.f);
@@ -106,9 +108,14 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
 #pragma unroll
     for (int e = 0; e < EPL; ++e) st.acc[e] = 0.f;
 
-    const int nv = min(a.vis_len[b], a.max_vis);
+    // Scaled logits kept for later: those of the visual keys become the mass; a layer with lazy
+    // followers (QK heredity, Eq. 6) keeps the logit of EVERY key for them.  Keeping all of them
+    // always was measured at +5 % on this kernel (4 bytes stored against 512 read per key, but as
+    // partial-line writes), so it is done only where it is needed.  Index = cache row either way.
     float* lg = a.logits ? a.logits + bh * a.capacity : nullptr;
-    const int vis_lo = a.sys_len, vis_hi = a.sys_len + nv;
+    const int vis_lo = a.keep_all_logits ? 0 : a.sys_len;
+    const int vis_hi = a.keep_all_logits ? len : a.sys_len + min(a.vis_len[b], a.max_vis);
+    if (lg) lg += vis_lo;           // the wave loop indexes by (row - vis_lo)
     const bool has_new = a.k_new != nullptr && c1 == len;       // this workgroup owns the appended row
     const int c1_cached = has_new ? c1 - 1 : c1;
     // waves take the tiles of the chunk round-robin, so all four stay busy to the end
@@ -161,13 +168,146 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Lazy layer (QK heredity, Eq. 6 / Alg. 2): o = sum_j p_j V[j] with the probabilities p of the
+// SOURCE layer's attention of the same step, rebuilt from the logits and chunk (max, sum) pairs
+// that the source's attend launch left in its workspace.  Streams V once: half the bytes.
+// ---------------------------------------------------------------------------------------------
+struct InheritArgs {
+    void* v;
+    int64_t stride_b, stride_h, stride_t;
+    const int32_t* kv_len;
+    int32_t B, max_kv, H, nsplit, nsplit_cap, chunk;
+    const float* src_logits;    // [B,H,src_capacity]
+    const float* src_part_ml;   // [B,H,src_nsplit_cap,2]
+    const int32_t* src_pending; // [B][4]
+    int32_t src_capacity, src_nsplit_cap;
+    float* part_o;              // [B,H,nsplit_cap,D]   (nsplit > 1 only)
+    const void* v_new;          // [B,H,D] value row of the token being appended (null: none)
+    void* out;
+};
+
+// One wave over the tiles of U*RPL value rows starting at r0, r0+step, ... below r1; next tile's
+// loads are issued before the current tile is consumed.
+template <typename T, int D, int U>
+__device__ __forceinline__ void wave_inherit(const T* vbase, int64_t stride_t, int r0, int r1, int step, int safe_row,
+                                             const float* lg, float m, float rl, int lane, float* acc) {
+    using M = RowMap<T, D>;
+    constexpr int EPL = M::EPL, LPR = M::LPR, RPL = M::RPL;
+    const int grp = lane / LPR;
+    const int64_t col = (int64_t)(lane % LPR) * EPL;
+    if (r0 >= r1) return;
+    u32x4_t vr[U], vn[U];
+    float sr[U], sn[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int row = r0 + u * RPL + grp;
+        const int rr = row < r1 ? row : safe_row;
+        vr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(vbase + (int64_t)rr * stride_t + col));
+        sr[u] = lg[rr];
+    }
+    for (int t0 = r0; t0 < r1; t0 += step) {
+        const int tn = t0 + step;
+        if (tn < r1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int row = tn + u * RPL + grp;
+                const int rr = row < r1 ? row : safe_row;
+                vn[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(vbase + (int64_t)rr * stride_t + col));
+                sn[u] = lg[rr];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int row = t0 + u * RPL + grp;
+            const float p = row < r1 ? exp2_fast(sr[u] - m) * rl : 0.f;
+            float vf[EPL];
+            ElemTraits<T>::unpack(make_uint4(vr[u].x, vr[u].y, vr[u].z, vr[u].w), vf);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+        }
+        if (tn < r1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) { vr[u] = vn[u]; sr[u] = sn[u]; }
+        }
+    }
+}
+
+// grid (nsplit, H, B)
+template <typename T, int D, int U>
+__global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_inherit_kernel(InheritArgs a) {
+    using M = RowMap<T, D>;
+    constexpr int EPL = M::EPL, LPR = M::LPR, TILE = U * M::RPL;
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int len = min(a.kv_len[b] + (a.v_new != nullptr ? 1 : 0), a.max_kv);
+    const int c0 = split * a.chunk;
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int64_t bh = (int64_t)b * a.H + h;
+    const bool have = a.src_pending[b * 4 + 3] != 0;        // the source attended a non-empty sequence
+    if (len <= 0 || !have) {                                // nothing to inherit: out = 0
+        if (split == 0 && tid < D) store_out<T>(a.out, bh * D + tid, 0.f);
+        if (len > 0 && a.nsplit > 1 && c0 < len && tid < D) a.part_o[(bh * a.nsplit_cap + split) * D + tid] = 0.f;
+        return;
+    }
+    if (c0 >= len) return;
+    const int c1 = min(c0 + a.chunk, len);
+    // the source row's maximum and sum from its chunk pairs, in chunk order (every thread alike)
+    const int s_nsplit = min(a.src_pending[b * 4 + 1], a.src_nsplit_cap);
+    const int s_chunk = max(a.src_pending[b * 4 + 2], 32);
+    const int s_ns = min((len + s_chunk - 1) / s_chunk, s_nsplit);
+    const float* ml = a.src_part_ml + bh * a.src_nsplit_cap * 2;
+    float m = ml[0];
+    for (int s = 1; s < s_ns; ++s) m = fmaxf(m, ml[2 * s]);
+    float l = 0.f;
+    for (int s = 0; s < s_ns; ++s) l = fmaf(ml[2 * s + 1], exp2_fast(ml[2 * s] - m), l);
+    const float rl = 1.0f / l;
+
+    T* vbase = reinterpret_cast<T*>(a.v) + b * a.stride_b + h * a.stride_h;
+    const float* lg = a.src_logits + bh * a.src_capacity;
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    const bool has_new = a.v_new != nullptr && c1 == len;
+    const int c1_cached = has_new ? c1 - 1 : c1;
+    wave_inherit<T, D, U>(vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0, lg, m, rl, lane, acc);
+    if (has_new && wave == 0 && lane < LPR) {
+        const T* vn = reinterpret_cast<const T*>(a.v_new) + bh * D + lane * EPL;
+        const uint4 raw = *reinterpret_cast<const uint4*>(vn);
+        const float p = exp2_fast(lg[len - 1] - m) * rl;
+        float vf[EPL];
+        ElemTraits<T>::unpack(raw, vf);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+        *reinterpret_cast<uint4*>(vbase + (int64_t)(len - 1) * a.stride_t + lane * EPL) = raw;
+    }
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], off);
+    }
+    __shared__ float sm_acc[kDecodeWaves][D];
+    if (lane < LPR) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) sm_acc[wave][lane * EPL + e] = acc[e];
+    }
+    __syncthreads();
+    if (tid < D) {
+        float o = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) o += sm_acc[w][tid];
+        if (a.nsplit == 1) store_out<T>(a.out, bh * D + tid, o);
+        else a.part_o[(bh * a.nsplit_cap + split) * D + tid] = o;
+    }
+}
+
 struct FinishArgs {
     const float* part_o;
     const float* part_ml;
     const float* logits;
     const int32_t* kv_len;
     const int32_t* vis_len;
-    int32_t H, nsplit, nsplit_cap, chunk, capacity, max_vis, max_kv;
+    int32_t H, nsplit, nsplit_cap, chunk, capacity, max_vis, max_kv, sys_len;
+    int32_t plain_sum;      // 1: the partial outputs are already normalised, just add them (lazy layers)
     int32_t appended;       // 1: the attend kernel took one more row than kv_len[b] says (the token being appended)
     void* out;              // null: outputs already written (nsplit == 1)
     float* mass;            // null: no mass
@@ -186,6 +326,12 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(FinishArgs a) {
         const int h = blockIdx.x;
         const int64_t bh = (int64_t)b * a.H + h;
         if (tid >= D || ns == 0) return;                // empty sequence: the attend kernel wrote zeros
+        if (a.plain_sum) {
+            float o = 0.f;
+            for (int s = 0; s < ns; ++s) o += a.part_o[(bh * a.nsplit_cap + s) * D + tid];   // chunk order
+            store_out<T>(a.out, bh * D + tid, o);
+            return;
+        }
         const float* ml = a.part_ml + bh * a.nsplit_cap * 2;
         float m = ml[0];
         for (int s = 1; s < ns; ++s) m = fmaxf(m, ml[2 * s]);
@@ -203,7 +349,8 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(FinishArgs a) {
     const int nv = min(a.vis_len[b], a.max_vis);
     head_norms(a.part_ml, b, a.H, ns, a.nsplit_cap, sm_m, sm_rl);
     const int j0 = ((int)blockIdx.x - out_blocks) * 256;
-    finish_mass(a.logits, b, a.H, a.capacity, sm_m, sm_rl, j0, min(j0 + 256, nv), a.mass + (int64_t)b * a.mass_stride);
+    finish_mass(a.logits + a.sys_len, b, a.H, a.capacity, sm_m, sm_rl, j0, min(j0 + 256, nv),
+                a.mass + (int64_t)b * a.mass_stride);
 }
 
 struct AppendArgs {
@@ -224,6 +371,7 @@ __global__ __launch_bounds__(64) void append_kernel(AppendArgs a) {
     const int row = a.kv_len[b];
     if (row < 0 || row >= a.capacity || lane >= 2 * M::LPR) return;
     const bool is_v = lane >= M::LPR;
+    if (!is_v && a.k == nullptr) return;                // a layer that caches V only
     const int c = (lane % M::LPR) * M::EPL;
     const int64_t bh = (int64_t)b * a.H + h;
     const T* src = reinterpret_cast<const T*>(is_v ? a.v_new : a.k_new) + bh * D + c;
@@ -248,6 +396,11 @@ void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
 }
 
 template <typename T, int D>
+void launch_inherit(const InheritArgs& ia, int B, hipStream_t st) {
+    decode_inherit_kernel<T, D, 2 * ST3_DECODE_U><<<dim3(ia.nsplit, ia.H, B), kDecodeThreads, 0, st>>>(ia);
+}
+
+template <typename T, int D>
 void launch_finish(const FinishArgs& fa, int B, hipStream_t st) {
     const int blocks = (fa.out ? fa.H : 0) + (fa.mass ? (fa.max_vis + 255) / 256 : 0);
     if (blocks > 0) decode_finish_kernel<T, D><<<dim3(blocks, B), 256, 0, st>>>(fa);
@@ -268,15 +421,15 @@ void launch_append(const AppendArgs& aa, int B, int32_t* kv_len, hipStream_t st)
         }                                                                                              \
     } while (0)
 
-st3_status check_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg) {
-    if (!kv || !seg || !kv->k || !kv->v || !seg->kv_len || !seg->vis_len) return ST3_ERR_INVALID_ARG;
+st3_status check_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg, bool value_only = false) {
+    if (!kv || !seg || (!kv->k && !value_only) || !kv->v || !seg->kv_len || !seg->vis_len) return ST3_ERR_INVALID_ARG;
     if (kv->capacity <= 0 || seg->sys_len < 0 || seg->max_vis_len < 0 || seg->max_kv_len < 0)
         return ST3_ERR_INVALID_ARG;
     if (seg->max_kv_len > kv->capacity) return ST3_ERR_INVALID_ARG;
     if (seg->sys_len + seg->max_vis_len > kv->capacity) return ST3_ERR_INVALID_ARG;
     if (kv->stride_t < s->head_dim || kv->stride_h < 0 || kv->stride_b < 0) return ST3_ERR_INVALID_ARG;
     const int eb = elem_bytes(s->dtype);
-    if (!aligned16(kv->k) || !aligned16(kv->v)) return ST3_ERR_INVALID_ARG;
+    if ((kv->k && !aligned16(kv->k)) || !aligned16(kv->v)) return ST3_ERR_INVALID_ARG;
     if ((kv->stride_t * eb) % 16 || (kv->stride_h * eb) % 16 || (kv->stride_b * eb) % 16)
         return ST3_ERR_INVALID_ARG;
     return ST3_OK;
@@ -290,7 +443,7 @@ st3_status check_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_s
 st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
                           const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
                           void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
-                          void* workspace, size_t workspace_bytes, hipStream_t st) {
+                          bool keep_all_logits, void* workspace, size_t workspace_bytes, hipStream_t st) {
     const int B = shape->batch, H = shape->heads, D = shape->head_dim;
     const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
     if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
@@ -309,7 +462,8 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     da.scale_l2 = scale_log2(shape);
     da.part_o = reinterpret_cast<float*>(ws + wl.part_o);
     da.part_ml = reinterpret_cast<float*>(ws + wl.part_ml);
-    da.logits = want_mass ? reinterpret_cast<float*>(ws + wl.logits) : nullptr;
+    da.logits = (want_mass || keep_all_logits) ? reinterpret_cast<float*>(ws + wl.logits) : nullptr;
+    da.keep_all_logits = keep_all_logits ? 1 : 0;
     da.pending = reinterpret_cast<int32_t*>(ws + wl.pending);
     da.k_new = k_new; da.v_new = v_new;
     da.out = out;
@@ -321,7 +475,7 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
         fa.part_o = da.part_o; fa.part_ml = da.part_ml; fa.logits = da.logits;
         fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len;
         fa.H = H; fa.nsplit = da.nsplit; fa.nsplit_cap = wl.nsplit_cap; fa.chunk = da.chunk;
-        fa.capacity = kv->capacity; fa.max_vis = seg->max_vis_len; fa.max_kv = max_kv_len;
+        fa.capacity = kv->capacity; fa.max_vis = seg->max_vis_len; fa.max_kv = max_kv_len; fa.sys_len = seg->sys_len;
         fa.appended = k_new != nullptr ? 1 : 0;
         fa.out = da.nsplit > 1 ? out : nullptr;
         fa.mass = mass_now ? vis_mass : nullptr; fa.mass_stride = mass_stride;
@@ -345,6 +499,50 @@ st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st
     return check_kv(s, kv, seg);
 }
 
+st3_status validate_kv_value_only(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg) {
+    return check_kv(s, kv, seg, true);
+}
+
+// Enqueues a lazy layer's attention (Eq. 6): the probabilities come from the attend launch that last
+// used `src_workspace` (same batch, heads and lengths; cache capacity src_capacity), the values
+// from `kv->v` plus - when v_new is given - the row being appended, which is stored on the way.
+st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
+                           int32_t max_kv_len, const void* v_new, const void* src_workspace,
+                           size_t src_workspace_bytes, int32_t src_capacity, void* out, void* workspace,
+                           size_t workspace_bytes, hipStream_t st) {
+    const int B = shape->batch, H = shape->heads, D = shape->head_dim;
+    const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
+    const DecodeWs sl = decode_ws(B, H, D, src_capacity);
+    if (workspace_bytes < wl.total || src_workspace_bytes < sl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
+    if (max_kv_len > src_capacity) return ST3_ERR_INVALID_ARG;       // the source kept a logit per cached key
+    char* ws = reinterpret_cast<char*>(workspace);
+    const char* sws = reinterpret_cast<const char*>(src_workspace);
+    InheritArgs ia{};
+    ia.v = kv->v; ia.stride_b = kv->stride_b; ia.stride_h = kv->stride_h; ia.stride_t = kv->stride_t;
+    ia.kv_len = seg->kv_len; ia.B = B; ia.max_kv = max_kv_len; ia.H = H;
+    ia.nsplit = decode_nsplit(B, H, max_kv_len);
+    if (ia.nsplit > wl.nsplit_cap) ia.nsplit = wl.nsplit_cap;
+    ia.nsplit_cap = wl.nsplit_cap;
+    ia.chunk = decode_chunk(max_kv_len, ia.nsplit);
+    ia.src_logits = reinterpret_cast<const float*>(sws + sl.logits);
+    ia.src_part_ml = reinterpret_cast<const float*>(sws + sl.part_ml);
+    ia.src_pending = reinterpret_cast<const int32_t*>(sws + sl.pending);
+    ia.src_capacity = src_capacity; ia.src_nsplit_cap = sl.nsplit_cap;
+    ia.part_o = reinterpret_cast<float*>(ws + wl.part_o);
+    ia.v_new = v_new; ia.out = out;
+    ST3_DISPATCH(launch_inherit, shape, ia, B, st);
+    if (ia.nsplit > 1) {
+        FinishArgs fa{};
+        fa.part_o = ia.part_o; fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len;
+        fa.H = H; fa.nsplit = ia.nsplit; fa.nsplit_cap = wl.nsplit_cap; fa.chunk = ia.chunk;
+        fa.capacity = kv->capacity; fa.max_kv = max_kv_len; fa.plain_sum = 1;
+        fa.appended = v_new != nullptr ? 1 : 0;
+        fa.out = out;
+        ST3_DISPATCH(launch_finish, shape, fa, B, st);
+    }
+    return check_launch();
+}
+
 }  // namespace st3
 
 extern "C" st3_status st3_decode_attention(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
@@ -358,17 +556,35 @@ extern "C" st3_status st3_decode_attention(const st3_attn_shape* shape, const vo
     if (!st3::aligned16(q) || !st3::aligned16(workspace)) return ST3_ERR_INVALID_ARG;
     if (vis_mass && mass_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
     return st3::enqueue_decode(shape, q, kv, seg, seg->max_kv_len, nullptr, nullptr, out, vis_mass, mass_stride,
-                               vis_mass != nullptr, false, workspace, workspace_bytes,
+                               vis_mass != nullptr, false, true, workspace, workspace_bytes,
                                reinterpret_cast<hipStream_t>(stream));
+}
+
+extern "C" st3_status st3_decode_attention_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv,
+                                                   const st3_segments* seg, const void* src_workspace,
+                                                   size_t src_workspace_bytes, int32_t src_kv_capacity, void* out,
+                                                   void* workspace, size_t workspace_bytes, void* stream) {
+    st3_status s = st3::check_shape(shape);
+    if (s != ST3_OK) return s;
+    s = st3::validate_kv_value_only(shape, kv, seg);
+    if (s != ST3_OK) return s;
+    if (!out || !workspace || !src_workspace || src_kv_capacity <= 0) return ST3_ERR_INVALID_ARG;
+    if (!st3::aligned16(workspace) || !st3::aligned16(src_workspace)) return ST3_ERR_INVALID_ARG;
+    return st3::enqueue_inherit(shape, kv, seg, seg->max_kv_len, nullptr, src_workspace, src_workspace_bytes,
+                                src_kv_capacity, out, workspace, workspace_bytes,
+                                reinterpret_cast<hipStream_t>(stream));
 }
 
 extern "C" st3_status st3_kv_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                                     const void* k_new, const void* v_new, void* stream) {
     st3_status s = st3::check_shape(shape);
     if (s != ST3_OK) return s;
-    s = st3::validate_kv(shape, kv, seg);
+    // a layer that caches V only (lazy layer of Alg. 2) passes kv->k == NULL and k_new == NULL
+    const bool value_only = kv && !kv->k && !k_new;
+    s = value_only ? st3::validate_kv_value_only(shape, kv, seg) : st3::validate_kv(shape, kv, seg);
     if (s != ST3_OK) return s;
-    if (!k_new || !v_new || !st3::aligned16(k_new) || !st3::aligned16(v_new)) return ST3_ERR_INVALID_ARG;
+    if ((!value_only && (!k_new || !st3::aligned16(k_new))) || !v_new || !st3::aligned16(v_new))
+        return ST3_ERR_INVALID_ARG;
     if (seg->max_kv_len >= kv->capacity) return ST3_ERR_INVALID_ARG;
     return st3::enqueue_append(shape, kv, seg, k_new, v_new, reinterpret_cast<hipStream_t>(stream));
 }

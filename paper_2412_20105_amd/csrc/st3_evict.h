@@ -115,7 +115,7 @@ struct EvictArgs {
     int32_t max_moves;
     // extras used by the fused per-layer decode step
     int32_t appended;           // 1: the attention kernel has just written one more row than kv_len[b] says
-    int32_t capacity;
+    int32_t capacity;           // row stride of `logits` (capacity of the cache whose attention produced them)
     int32_t inline_apply;       // 1: HOLE_FILL moves are applied to K and V by this kernel
     char* k;
     char* v;
@@ -124,7 +124,7 @@ struct EvictArgs {
     // visual mass the attention kernel left to be finished here (all null: none)
     const float* part_ml;
     const float* logits;
-    int32_t* pending;           // [B][4] descriptor written by the attend kernel
+    const int32_t* pending;     // [B][4] descriptor written by the attend kernel (read only: lazy layers share it)
     int32_t nsplit_cap;
     float* mass_dst;
     int64_t mass_stride;
@@ -186,9 +186,8 @@ __device__ __forceinline__ void evict_plan_body(const EvictArgs& a, int b, SelSh
             const int chunk = max(a.pending[b * 4 + 2], 32);
             const int ns = len > 0 ? min((len + chunk - 1) / chunk, nsplit) : 0;
             head_norms(a.part_ml, b, a.H, ns, a.nsplit_cap, sm_hm, sm_hrl);
-            finish_mass(a.logits, b, a.H, a.capacity, sm_hm, sm_hrl, 0, n, a.mass_dst + b * a.mass_stride);
+            finish_mass(a.logits + a.sys_len, b, a.H, a.capacity, sm_hm, sm_hrl, 0, n, a.mass_dst + b * a.mass_stride);
             __syncthreads();                            // the ranking below may read these scores
-            if (tid == 0) a.pending[b * 4] = 0;
         }
     }
     if (k < n && a.sys_len + n <= len) {                // something to evict, lengths consistent
@@ -303,10 +302,14 @@ __device__ __forceinline__ void evict_plan_body(const EvictArgs& a, int b, SelSh
 // ---- host side (defined in st3_select.hip) --------------------------------------------------
 // Fills the plan arguments for one layer; needs_apply tells whether evict_apply_kernel must run
 // after the plan (evictions too large for the plan workgroup to move, or STABLE mode).
+// kv->k may be null (a layer that caches V only).  mass_workspace (null: `workspace`) is the
+// workspace whose attend launch left the logits the mass is finished from - a lazy layer's
+// source - and mass_capacity that cache's capacity.
 st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                             float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count, int32_t mode,
                             void* workspace, size_t workspace_bytes, int appended, float* mass_dst,
-                            int64_t mass_stride, EvictArgs& ea, bool& needs_apply);
+                            int64_t mass_stride, EvictArgs& ea, bool& needs_apply,
+                            const void* mass_workspace = nullptr, int32_t mass_capacity = 0);
 void launch_evict_plan(const EvictArgs& ea, int B, hipStream_t st);
 // Plans of n layers (device work of one decode step) with one launch per kPlanBatch layers.
 void launch_evict_plan_batch(const EvictArgs* plans, int n, int B, hipStream_t st);

@@ -154,6 +154,7 @@ __global__ __launch_bounds__(256) void evict_apply_kernel(ApplyArgs a) {
     const int b = blockIdx.y, tid = threadIdx.x;
     const int M = min(a.move_cnt[b], a.max_moves);
     if (M <= 0) return;
+    if ((int)blockIdx.x < a.H && a.k == nullptr) return;    // a layer that caches V only
     const int h = blockIdx.x % a.H;
     char* strip = (blockIdx.x < a.H ? a.k : a.v) + b * a.stride_b + h * a.stride_h;
     const int32_t* mv = a.moves + (int64_t)b * a.max_moves * 2;
@@ -183,6 +184,7 @@ __global__ __launch_bounds__(256) void evict_apply_kernel(ApplyArgs a) {
 }  // namespace
 
 st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
+st3_status validate_kv_value_only(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
 
 // Rows are moved inside the plan kernel when the mode is HOLE_FILL and at most kInlineEvict rows
 // can be evicted per sequence (one workgroup then moves at most ~100 rows on each strip); larger
@@ -192,7 +194,8 @@ constexpr int kInlineEvict = 48;
 st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                             float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count, int32_t mode,
                             void* workspace, size_t workspace_bytes, int appended, float* mass_dst,
-                            int64_t mass_stride, EvictArgs& ea, bool& needs_apply) {
+                            int64_t mass_stride, EvictArgs& ea, bool& needs_apply, const void* mass_workspace,
+                            int32_t mass_capacity) {
     const int B = shape->batch, H = shape->heads, D = shape->head_dim;
     if (seg->max_vis_len > kSelLdsKeys) return ST3_ERR_UNSUPPORTED;
     const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
@@ -214,10 +217,13 @@ st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv,
     ea.stride_b = kv->stride_b * eb; ea.stride_h = kv->stride_h * eb; ea.stride_t = kv->stride_t * eb;
     ea.H = H; ea.vecs_per_row = D * eb / 16;
     if (mass_dst != nullptr) {
-        ea.part_ml = reinterpret_cast<const float*>(ws + wl.part_ml);
-        ea.logits = reinterpret_cast<const float*>(ws + wl.logits);
-        ea.pending = reinterpret_cast<int32_t*>(ws + wl.pending);
-        ea.nsplit_cap = wl.nsplit_cap;
+        const char* mws = mass_workspace ? reinterpret_cast<const char*>(mass_workspace) : ws;
+        const DecodeWs ml = mass_workspace ? decode_ws(B, H, D, mass_capacity) : wl;
+        ea.part_ml = reinterpret_cast<const float*>(mws + ml.part_ml);
+        ea.logits = reinterpret_cast<const float*>(mws + ml.logits);
+        ea.pending = reinterpret_cast<const int32_t*>(mws + ml.pending);
+        ea.nsplit_cap = ml.nsplit_cap;
+        if (mass_workspace) ea.capacity = mass_capacity;
         ea.mass_dst = mass_dst; ea.mass_stride = mass_stride;
     }
     needs_apply = evicting && !ea.inline_apply;
@@ -461,7 +467,7 @@ extern "C" st3_status st3_select_compact_layer(const st3_attn_shape* shape, cons
                                                void* workspace, size_t workspace_bytes, void* stream) {
     st3_status s = st3::check_shape(shape);
     if (s != ST3_OK) return s;
-    s = st3::validate_kv(shape, kv, seg);
+    s = (kv && !kv->k) ? st3::validate_kv_value_only(shape, kv, seg) : st3::validate_kv(shape, kv, seg);
     if (s != ST3_OK) return s;
     if (!score_col || !id_col || !workspace || keep_count < 0) return ST3_ERR_INVALID_ARG;
     if (col_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;

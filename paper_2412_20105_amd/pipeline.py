@@ -8,7 +8,7 @@ that place a layer's inputs where the kernels expect them.
 """
 from __future__ import annotations
 
-from typing import List, Optional, Sequence
+from typing import Dict, List, Optional, Sequence
 
 import torch
 
@@ -37,8 +37,9 @@ def keep_table_for(workload) -> List[List[int]]:
 
 
 class LayerCache:
-    def __init__(self, B, H, d, cap, cap_v, dtype, device, ws_bytes):
-        self.k = torch.empty((B, H, cap, d), dtype=dtype, device=device)
+    def __init__(self, B, H, d, cap, cap_v, dtype, device, ws_bytes, value_only=False):
+        # a lazy layer (QK heredity) never forms K, so it caches V alone
+        self.k = None if value_only else torch.empty((B, H, cap, d), dtype=dtype, device=device)
         self.v = torch.empty((B, H, cap, d), dtype=dtype, device=device)
         self.score = torch.zeros((B, max(cap_v, 1)), dtype=torch.float32, device=device)
         self.ids = torch.zeros((B, max(cap_v, 1)), dtype=torch.int32, device=device)
@@ -46,7 +47,7 @@ class LayerCache:
         self.vis_len = torch.zeros((B,), dtype=torch.int32, device=device)
         self.kv_len = torch.zeros((B,), dtype=torch.int32, device=device)
         self.kv = st3.kv_layer(self.k, self.v)
-        # a workspace of its own: a deferred mass keeps its logits here until the next step
+        # a workspace of its own: the attention leaves its logits here for the mass and for lazy layers
         self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         # host-side bounds (exact here, since every sequence follows the same table)
         self.h_vis = 0
@@ -58,12 +59,15 @@ class Generation:
 
     keep: table keep[l][t] (t = 0 .. steps).  mode: "static" ranks by the column
     fixed at prefill, "current" by the layer's latest decode mass.
+    lazy: {l: src} - QK heredity (Eq. 6, Alg. 2): layer l applies the attention probabilities of
+    source layer src to its own values, at prefill and at every decode step.  Lazy layers follow
+    their source directly and share its row of the keep table; their Q and K inputs are ignored.
     """
 
     def __init__(self, layers: int, heads: int, head_dim: int, dtype: torch.dtype, batch: int,
                  n_sys: int, n_vis: int, n_txt: int, steps: int, keep: Sequence[Sequence[int]],
                  window: int = 1, mode: str = "static", compact_mode: int = st3.ST3_HOLE_FILL,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", lazy: Optional[Dict[int, int]] = None):
         self.L, self.H, self.d, self.B = layers, heads, head_dim, batch
         self.n_sys, self.n_vis, self.n_txt, self.T = n_sys, n_vis, n_txt, steps
         self.keep = [list(r) for r in keep]
@@ -71,12 +75,21 @@ class Generation:
         self.dtype, self.device = dtype, device
         self.shape = st3.make_shape(batch, heads, head_dim, st3._dtype_code(torch.empty(0, dtype=dtype)))
         self.N0 = n_sys + n_vis + n_txt
+        self.lazy = dict(lazy or {})
+        for l, src in self.lazy.items():
+            if not (0 <= src < l < layers) or src in self.lazy:
+                raise ValueError("a lazy layer needs a non-lazy source layer before it")
+            if any(self.lazy.get(m) != src for m in range(src + 1, l)):
+                raise ValueError("lazy layers must follow their source directly")
+            if self.keep[l] != self.keep[src]:
+                raise ValueError("a lazy layer keeps what its source keeps")
         self.layers: List[LayerCache] = []
         for l in range(layers):
             cap = n_sys + self.keep[l][0] + n_txt + steps
             cap = max(cap, self.N0)                 # the unpruned prompt is staged in the cache first
             ws_bytes = st3.st3_workspace_bytes(self.shape, cap, n_vis, window)
-            self.layers.append(LayerCache(batch, heads, head_dim, cap, n_vis, dtype, device, ws_bytes))
+            self.layers.append(LayerCache(batch, heads, head_dim, cap, n_vis, dtype, device, ws_bytes,
+                                          value_only=l in self.lazy))
             st3.st3_workspace_init(self.shape, cap, self.layers[-1].ws)
         self.q_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
         self.out_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
@@ -103,10 +116,12 @@ class Generation:
 
     def prefill_layer(self, l: int, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor):
         """Q, K, V: device tensors [B,H,N0,d] over the unpruned prompt (Alg. 3, PVTP branch).
+        A lazy layer ignores Q and K (may be None): Eq. 6 attends with its source's.
 
         Returns (out view [B,H,n_l,d], mass view [B,keep_l]).
         """
         lc = self.layers[l]
+        src = self.lazy.get(l)
         B, ns, nv, nx = self.B, self.n_sys, self.n_vis, self.n_txt
         k_l = self.keep[l][0]
         if l == 0:
@@ -127,15 +142,23 @@ class Generation:
         alive = self._alive
         n_l = ns + alive + nx
         # stage the layer's inputs: K and V straight into the cache, Q into scratch
-        lc.k[:, :, :self.N0].copy_(K)
         lc.v[:, :, :self.N0].copy_(V)
-        self.q_stage.copy_(Q)
+        if src is None:
+            lc.k[:, :, :self.N0].copy_(K)
+            self.q_stage.copy_(Q)
+            staged = (lc.k, lc.v, self.q_stage)
+            k_rows = lc.k
+        else:
+            # Self-attn(Q^src, K^src, V^l): the source's compacted queries are still staged (only
+            # lazy layers came in between) and its keys are the first n_l rows of its cache
+            staged = (lc.v,)
+            k_rows = self.layers[src].k
         if alive < nv:
             # Alg. 1/3: X = [S, V[T], I]; ids are ascending original positions of the survivors
-            for t in (lc.k, lc.v, self.q_stage):
+            for t in staged:
                 self._compact_strips(t, lc.ids, alive, nv, nx)
         out = self.out_stage[:, :, :n_l]
-        st3.st3_prefill_attention(self.shape, self.q_stage[:, :, :n_l], lc.k[:, :, :n_l], lc.v[:, :, :n_l],
+        st3.st3_prefill_attention(self.shape, self.q_stage[:, :, :n_l], k_rows[:, :, :n_l], lc.v[:, :, :n_l],
                                   n_l, ns, alive, self.window, out, lc.mass, lc.ws)
         # ranking column: scores of the most recent prune event, else the layer's own mass
         lc.score.copy_(lc.mass if self._inherit is None else self._inherit)
@@ -175,6 +198,9 @@ class Generation:
         attention saw; in "current" mode the mass lives in the score column, which the eviction
         compacts, so only its first keep[l][t+1] entries (the survivors) remain meaningful).
         """
+        if self.lazy:
+            raise RuntimeError("QK heredity needs the whole-step call: a group's evictions wait for its last lazy "
+                               "layer, use decode_step()")
         if not getattr(self, "_decoding", False):
             self.begin_decode()
         lc = self.layers[l]
@@ -205,6 +231,7 @@ class Generation:
                 s.vis_mass, s.mass_stride = md.data_ptr(), md.stride(0)
                 s.out = self.dec_out_all[l].data_ptr()
                 s.workspace, s.workspace_bytes = lc.ws.data_ptr(), lc.ws.numel()
+                s.inherit_from = self.lazy.get(l, -1)
             self._steps = arr
         arr = self._steps
         base = qkv.data_ptr()
@@ -224,4 +251,10 @@ class Generation:
         return [lc.h_kv for lc in self.layers]
 
     def kv_bytes(self) -> int:
-        return st3.st3_kv_bytes(self.B, self.H, self.d, self.shape.dtype, self.kv_lens())
+        lens = self.kv_lens()
+        full = [n for l, n in enumerate(lens) if l not in self.lazy]
+        half = [n for l, n in enumerate(lens) if l in self.lazy]          # V only
+        total = st3.st3_kv_bytes(self.B, self.H, self.d, self.shape.dtype, full)
+        if half:
+            total += st3.st3_kv_bytes(self.B, self.H, self.d, self.shape.dtype, half) // 2
+        return total

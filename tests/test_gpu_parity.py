@@ -286,6 +286,61 @@ def test_select_compact_layer(mode, dtype, D):
 
 
 # ---------------------------------------------------------------------------
+# QK heredity at decode (Eq. 6, Alg. 2): a lazy layer applies its source's probabilities to its own V
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,D,B,H,lens,ns,nv,cap_extra", [
+    ("bf16", 128, 3, 5, [739, 257, 256], 35, 200, 0),      # split strips, ragged batch
+    ("bf16", 128, 2, 2, [33, 0], 1, 7, 9),                 # an empty sequence; caches of different capacity
+    ("f32", 64, 2, 3, [300, 1], 0, 1, 0),
+    ("bf16", 128, 26, 40, [200] * 25 + [77], 35, 100, 3),  # enough strips that none is split
+])
+def test_decode_attention_inherit(dtype, D, B, H, lens, ns, nv, cap_extra):
+    print(f"inherit dtype={dtype} D={D} B={B} H={H} lens={lens[:4]}", flush=True)
+    rng = np.random.default_rng(zlib.crc32(repr(("inh", dtype, D, B, H, lens)).encode()))
+    cap_s = max(lens) + 5
+    cap_l = cap_s + cap_extra
+    sigma = 1.0 if dtype == "f32" else 1.43
+    K = rand_values(rng, (B, H, cap_s, D), dtype, sigma)
+    Vs = rand_values(rng, (B, H, cap_s, D), dtype, sigma)
+    Vl = rand_values(rng, (B, H, cap_l, D), dtype, sigma)       # the lazy layer's own values
+    q = rand_values(rng, (B, H, D), dtype, sigma)
+    vn = rand_values(rng, (B, H, D), dtype, sigma)
+    vis = [max(0, min(nv, L - ns)) for L in lens]
+    shape = st3.make_shape(B, H, D, CODE[dtype])
+    dK, dVs, dVl, dq = to_dev(K, dtype), to_dev(Vs, dtype), to_dev(Vl, dtype), to_dev(q, dtype)
+    out_s = torch.zeros((B, H, D), dtype=TORCH_DTYPE[dtype], device=DEV)
+    out_l = torch.full((B, H, D), 5.0, dtype=TORCH_DTYPE[dtype], device=DEV)
+    ws_s, ws_l = _ws(shape, cap_s, nv), _ws(shape, cap_l, nv)
+    # the lazy layer appends first (V only), the source's cache already holds its rows
+    lens_before = [max(L - 1, 0) for L in lens]
+    kv_len_l, vis_len = _i32(lens_before), _i32(vis)
+    lazy_kv = st3.kv_layer(None, dVl)
+    st3.st3_kv_append(shape, lazy_kv, st3.segments(ns, nv, max(lens_before), vis_len, kv_len_l), None, to_dev(vn, dtype))
+    torch.cuda.synchronize()
+    got_len = kv_len_l.cpu().tolist()
+    Vl_ref = Vl.copy()
+    for b in range(B):
+        assert got_len[b] == lens_before[b] + 1
+        Vl_ref[b, :, lens_before[b]] = vn[b]
+    assert np.array_equal(dVl.float().cpu().numpy(), Vl_ref.astype(np.float32))
+    lens_l = got_len                                         # = lens, except an empty sequence now holds one row
+    kv_len_s = _i32(lens_l)
+    # source layer attends (no mass asked for: the probabilities are kept all the same) ...
+    st3.st3_decode_attention(shape, dq, st3.kv_layer(dK, dVs), st3.segments(ns, nv, max(lens_l), vis_len, kv_len_s),
+                             out_s, None, ws_s)
+    # ... and the lazy layer inherits them
+    st3.st3_decode_attention_inherit(shape, lazy_kv, st3.segments(ns, nv, max(lens_l), vis_len, kv_len_l), ws_s, cap_s,
+                                     out_l, ws_l)
+    torch.cuda.synchronize()
+    got = to_np64(out_l)
+    for b in range(B):
+        n = lens_l[b]
+        o, _, p = orc.decode_attention(q[b:b + 1], K[b:b + 1, :, :n], Vl_ref[b:b + 1, :, :n], ns, min(vis[b], n))
+        assert_attention_close(got[b], o[0], dtype, f"b={b}")
+        np.testing.assert_allclose(o[0], np.einsum("hj,hjd->hd", p[0], Vl_ref[b, :, :n].astype(np.float64)), atol=1e-12)
+
+
+# ---------------------------------------------------------------------------
 # fused layer step: append + attention + mass, then the eviction for the next step (Alg. 3)
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("mode", [st3.ST3_STABLE, st3.ST3_HOLE_FILL])

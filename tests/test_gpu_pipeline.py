@@ -16,14 +16,17 @@ from workloads import decode_qkv, get_workload, prefill_qkv
 pytestmark = pytest.mark.gpu
 
 
-def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None, whole_step=False):
+def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None, whole_step=False,
+                     lazy=None):
     T = w.steps if steps is None else steps
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
     keep_np = np.array(keep)
     assert np.array_equal(keep_np, orc.schedule_for(w)[:, :T + 1])
     gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt,
-                              T, keep, window=window, mode=mode, compact_mode=compact_mode, device=DEV)
-    ref = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, keep_np, window=window, mode=mode)
+                              T, keep, window=window, mode=mode, compact_mode=compact_mode, device=DEV,
+                              lazy=lazy)
+    ref = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, keep_np, window=window, mode=mode,
+                         lazy=lazy)
     pre = [prefill_qkv(w, l, B) for l in range(w.layers)]
     r = ref.prefill(lambda l: pre[l])
     diverged = np.zeros((w.layers, B), bool)      # a near-tie was resolved differently: values no longer comparable
@@ -115,7 +118,8 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
                     assert_mass_close(to_np64(lc.score[b, :lc.h_vis]), s["mass"][l][b][pos],
                                       f"ranking column after t={t} l={l} b={b}")
     # KV bytes actually held == closed form
-    assert gen.kv_bytes() == orc.kv_bytes(B, w.heads, w.head_dim, 2 if w.dtype == "bf16" else 4, ref.cache_lens())
+    assert gen.kv_bytes() == orc.kv_bytes(B, w.heads, w.head_dim, 2 if w.dtype == "bf16" else 4, ref.cache_lens(),
+                                          value_only=lazy or ())
     return near_ties, diverged
 
 
@@ -153,6 +157,46 @@ def test_large_evictions_whole_step_call():
     w = dataclasses.replace(get_workload("llava15_13b"), layers=5, heads=4, steps=3, n_txt=20,
                             step_schedule={"kind": "cos", "tau": 3})
     _run_and_compare(w, 2, whole_step=True)
+
+
+def _lazy_workload(name, **kw):
+    """Six layers, the last three a QK-heredity group: layers 4 and 5 inherit from layer 3 (the
+    paper's "28 -> 29~31" pattern), so rows 3-5 of the keep table are equal."""
+    base = dict(layers=6, heads=4, steps=6, n_vis=120, n_txt=9,
+                layer_schedule={"kind": "table", "keep": [120, 120, 100, 80, 80, 80]},
+                step_schedule={"kind": "cos", "tau": 6})
+    base.update(kw)
+    return dataclasses.replace(get_workload(name), **base)
+
+
+@pytest.mark.parametrize("mode", ["static", "current"])
+@pytest.mark.parametrize("compact_mode", [st3.ST3_HOLE_FILL, st3.ST3_STABLE])
+def test_qk_heredity_group(mode, compact_mode):
+    """Eq. 6 / Alg. 2: lazy layers take the source's probabilities, at prefill and at every step;
+    K-less caches; the group evicts alike.  B*H is small, so the strips are split into chunks."""
+    w = _lazy_workload("llava15_7b")
+    near, div = _run_and_compare(w, 2, mode=mode, compact_mode=compact_mode, whole_step=True, lazy={4: 3, 5: 3})
+    assert div.mean() < 0.5
+
+
+def test_qk_heredity_fp32_many_heads_no_split_large_evictions():
+    """fp32, enough (b,h) strips that no strip is split, evictions above the in-kernel move limit."""
+    w = _lazy_workload("tiny", heads=40, head_dim=64, steps=3, n_vis=300, n_sys=8, n_txt=16,
+                       layer_schedule={"kind": "table", "keep": [300, 300, 300, 260, 260, 260]},
+                       step_schedule={"kind": "cos", "tau": 3})
+    _run_and_compare(w, 28, whole_step=True, lazy={1: 0, 2: 0, 5: 4})
+
+
+def test_qk_heredity_needs_the_whole_step_call():
+    w = _lazy_workload("llava15_7b")
+    keep = pipeline.keep_table_for(w)
+    gen = pipeline.Generation(w.layers, w.heads, w.head_dim, torch.bfloat16, 1, w.n_sys, w.n_vis, w.n_txt, w.steps,
+                              keep, device=DEV, lazy={4: 3})
+    with pytest.raises(RuntimeError):
+        gen.decode_layer(0, 1, None, None, None)
+    with pytest.raises(ValueError):
+        pipeline.Generation(w.layers, w.heads, w.head_dim, torch.bfloat16, 1, w.n_sys, w.n_vis, w.n_txt, w.steps,
+                            keep, device=DEV, lazy={3: 2})          # keeps differ
 
 
 def test_tiny_workload_batched_window():
