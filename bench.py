@@ -43,6 +43,10 @@ def parse():
     ap.add_argument("--step-schedule", default="workload", choices=["workload", "cos", "linear", "exp", "none"],
                     help="attenuation over decode steps (Eq. 8 / Sec. 4.4)")
     ap.add_argument("--tau", type=float, default=0.0, help="tau (cos, linear) or sigma (exp); 0 = decode steps")
+    ap.add_argument("--lazy", default="",
+                    help="QK heredity groups (Eq. 6, Alg. 2) as SRC:FIRST-LAST[,SRC:FIRST-LAST...], e.g. 36:37-39 = "
+                         "layers 37..39 reuse the attention probabilities of layer 36 (the paper's '28 -> 29~31' for "
+                         "the 7B model); lazy layers take their source's row of the retention table")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="short run for counter collection: prefill, one plain 1 GiB device copy of known size, "
                          "then the decode steps; prints the algorithmic bytes of each attend launch")
@@ -52,8 +56,9 @@ def parse():
 class Job:
     """Device-resident inputs of one batch and the call sequence of one whole job."""
 
-    def __init__(self, w, B, T, keep, torch, pipeline, st3, seed=1234):
+    def __init__(self, w, B, T, keep, torch, pipeline, st3, seed=1234, lazy=None):
         self.w, self.B, self.T, self.keep = w, B, T, keep
+        self.lazy = dict(lazy or {})
         self.torch = torch
         dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         dev = "cuda:0"
@@ -68,7 +73,7 @@ class Job:
         self.pre = [tuple(randn(shape_p) for _ in range(3)) for _ in range(w.layers)]
         self.dec = [randn(shape_d) for _ in range(T)]
         self.gen = pipeline.Generation(w.layers, w.heads, w.head_dim, dt, B, w.n_sys, w.n_vis, w.n_txt, T, keep,
-                                       device=dev)
+                                       device=dev, lazy=self.lazy)
 
     def run(self):
         gen, w = self.gen, self.w
@@ -94,6 +99,8 @@ class Job:
         total = 0
         for t in range(1, self.T + 1):
             for l in range(w.layers):
+                if l in self.lazy:          # a lazy layer runs the V-only kernel, not this one
+                    continue
                 lkv = w.n_sys + self.keep[l][t] + w.n_txt + t
                 total += self.B * (2 * w.heads * w.head_dim * e * lkv + 2 * w.heads * w.head_dim * e
                                    + 4 * self.keep[l][t])
@@ -145,11 +152,12 @@ def cpu_baseline(w, keep, T, budget_s):
                       f"cost is linear in B"}
 
 
-def pmc_probe(a, w, B, T, keep, torch, pipeline, st3):
+def pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy=None):
     """For `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: the same decode launches as the
     benchmark (first T steps), preceded by a device-to-device copy of exactly 1 GiB whose counter
     reading calibrates the counter's unit."""
-    job = Job(w, B, T, keep, torch, pipeline, st3)
+    lazy = dict(lazy or {})
+    job = Job(w, B, T, keep, torch, pipeline, st3, lazy=lazy)
     job.run_prefill_only()
     n = 1 << 30
     src = torch.empty((n,), dtype=torch.uint8, device="cuda:0")
@@ -162,15 +170,21 @@ def pmc_probe(a, w, B, T, keep, torch, pipeline, st3):
         job.gen.decode_step(t, job.dec[t - 1])
     torch.cuda.synchronize()
     e = 2 if w.dtype == "bf16" else 4
-    per_launch = []
+    per_launch, per_lazy = [], []
+    hd = w.heads * w.head_dim * e
     for t in range(1, T + 1):
         for l in range(w.layers):
             lkv = w.n_sys + keep[l][t] + w.n_txt + t
-            per_launch.append(B * (2 * w.heads * w.head_dim * e * lkv + 2 * w.heads * w.head_dim * e + 4 * keep[l][t]))
+            if l in lazy:       # V rows once, one logit per (head, key), v_new in, o out
+                per_lazy.append(B * (hd * lkv + 4 * w.heads * lkv + 2 * hd))
+            else:
+                per_launch.append(B * (2 * hd * lkv + 2 * hd + 4 * keep[l][t]))
     print(json.dumps({"probe": "pmc", "workload": w.name, "batch": B, "decode_steps": T,
                       "copy_bytes_read": n, "copy_bytes_written": n,
                       "attend_launches": len(per_launch), "alg_bytes_per_launch_mean": sum(per_launch) / len(per_launch),
-                      "alg_bytes_first_launches": per_launch[:8]}))
+                      "alg_bytes_first_launches": per_launch[:8],
+                      "inherit_launches": len(per_lazy),
+                      "inherit_alg_bytes_per_launch_mean": (sum(per_lazy) / len(per_lazy)) if per_lazy else None}))
 
 
 def main():
@@ -205,14 +219,21 @@ def main():
     w = dataclasses.replace(w, steps=T)
     B = a.batch
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
+    lazy = {}
+    for grp in filter(None, a.lazy.split(",")):
+        src, rng = grp.split(":")
+        first, last = (rng.split("-") + [rng])[:2]
+        for l in range(int(first), int(last) + 1):
+            lazy[l] = int(src)
+            keep[l] = list(keep[int(src)])          # a lazy layer holds what its source holds
     def note(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
     if a.pmc_probe:
-        return pmc_probe(a, w, B, T, keep, torch, pipeline, st3)
+        return pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy)
 
     note(f"generating inputs for {w.name} B={B} T={T}")
-    job = Job(w, B, T, keep, torch, pipeline, st3)
+    job = Job(w, B, T, keep, torch, pipeline, st3, lazy=lazy)
     note("warmup")
     for _ in range(a.warmup):
         job.run()
@@ -232,7 +253,8 @@ def main():
         "config": {"workload": f"{w.name}: L={w.layers} H={w.heads} d={w.head_dim} {w.dtype}, prompt "
                                f"{w.n_sys}+{w.n_vis}+{w.n_txt}, T={T} decode steps, batch {B}, "
                                f"schedule {w.layer_schedule}/{w.step_schedule}",
-                   "batch": B, "decode_steps": T, "step_definition": "prefill (all layers, PVTP) + T decode steps (VTA)"},
+                   "batch": B, "decode_steps": T, "step_definition": "prefill (all layers, PVTP) + T decode steps (VTA)",
+                   "lazy_layers": {str(l): s for l, s in sorted(lazy.items())}},
         "prefill_ms": ms_prefill,
         "decode_ms_per_token_step": (ms_job - ms_prefill) / T,
         "decode_only_tokens_per_s": tokens / ((ms_job - ms_prefill) * 1e-3),
@@ -242,7 +264,7 @@ def main():
     note(f"job {ms_job:.1f} ms, prefill {ms_prefill:.1f} ms")
     if not a.no_profile_pass:
         note("instrumented pass")
-        launches = w.layers * T
+        launches = (w.layers - len(lazy)) * T
         st3.st3_profile_enable(launches + 8)
         job.run()
         torch.cuda.synchronize()
