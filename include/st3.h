@@ -197,6 +197,31 @@ ST3_EXPORT st3_status st3_compact_rows(void* rows, int32_t batch, int32_t inner,
                             void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Out-of-place gather of the rows a prune event keeps, for several tensors in ONE launch
+ * (Alg. 1: V = V[T]; X = [S, V, I] - one index list applied to a layer's Q, K and V rows alike,
+ * or to hidden rows of full width; Alg. 3, PVTP branch).  For every pair p < n_pairs, b < batch,
+ * i < inner, on the strips src_p + b*src_stride_b + i*src_stride_inner and dst_p + ... alike:
+ *   dst row r                 <- src row r                              r in [0, head_rows)
+ *   dst row head_rows + j     <- src row head_rows + keep_idx[b][j]     j in [0, k)
+ *   dst row head_rows + k + j <- src row head_rows + n + j              j in [0, tail_rows)
+ * keep_idx: DEVICE int32, row b at keep_idx + b*idx_stride, entries in [0, n) (a destination row
+ * whose entry lies outside is left untouched); NULL means the identity and requires k == n, which
+ * makes the call a strided copy.  Rows are row_bytes long (multiple of 16); all strides are in
+ * bytes and multiples of 16, all pointers 16-byte aligned; no dst strip may overlap a src strip.
+ * At most ST3_MAX_GATHER pairs per call.
+ * ------------------------------------------------------------------------------------------- */
+#define ST3_MAX_GATHER 4
+typedef struct {
+    const void* src;
+    int64_t     src_stride_b, src_stride_inner, src_stride_row;
+    void*       dst;
+    int64_t     dst_stride_b, dst_stride_inner, dst_stride_row;
+} st3_gather_pair;
+ST3_EXPORT st3_status st3_gather_rows(const st3_gather_pair* pairs, int32_t n_pairs, int32_t batch, int32_t inner,
+                                      int32_t row_bytes, int32_t head_rows, const int32_t* keep_idx,
+                                      int64_t idx_stride, int32_t k, int32_t n, int32_t tail_rows, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Select-and-compact for one layer at one decode step (Eq. 7: C_v <- C_v[: |V^{l,0}| * beta^t];
  * Alg. 3, VTA branch; eviction semantics of Sec. 4.3).  For every sequence b with
  * vis_len[b] > keep_count: ranks the layer's visual keys by score_col (total order of

@@ -28,7 +28,7 @@ EXPORTED = [
     "st3_status_string", "st3_last_hip_error", "st3_version", "st3_workspace_bytes", "st3_workspace_init",
     "st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_decode_attention_inherit",
     "st3_select_topk",
-    "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
+    "st3_compact_rows", "st3_gather_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
     "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
     "st3_debug_set_prefill_path", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
     "st3_cosine_similarity",
@@ -62,6 +62,15 @@ class KvLayer(C.Structure):
 class Segments(C.Structure):
     _fields_ = [("sys_len", C.c_int32), ("max_vis_len", C.c_int32), ("max_kv_len", C.c_int32),
                 ("vis_len", C.c_void_p), ("kv_len", C.c_void_p)]
+
+
+class GatherPair(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("src_stride_b", C.c_int64), ("src_stride_inner", C.c_int64),
+                ("src_stride_row", C.c_int64), ("dst", C.c_void_p), ("dst_stride_b", C.c_int64),
+                ("dst_stride_inner", C.c_int64), ("dst_stride_row", C.c_int64)]
+
+
+ST3_MAX_GATHER = 4
 
 
 class LayerStep(C.Structure):
@@ -105,6 +114,9 @@ def lib() -> C.CDLL:
                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.st3_compact_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int32,
                                        C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        L.st3_gather_rows.argtypes = [P(GatherPair), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                      C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        L.st3_gather_rows.restype = C.c_int
         L.st3_select_compact_layer.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_void_p,
                                                C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         L.st3_decode_layer_step.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_void_p, C.c_int64,
@@ -257,6 +269,22 @@ def st3_compact_rows(rows_ptr: int, batch, inner, stride_b_bytes, stride_inner_b
                                   row_bytes, keep_idx.data_ptr(), keep_idx.stride(0), k, n, tail_rows,
                                   _stream(stream)),
            "st3_compact_rows")
+
+
+def st3_gather_rows(pairs, head_rows, keep_idx, k, n, tail_rows, stream=None):
+    """pairs: list of (src, dst) tensors [B, inner, rows, width] with contiguous rows of equal byte length."""
+    src0 = pairs[0][0]
+    eb = src0.element_size()
+    arr = (GatherPair * len(pairs))()
+    for g, (src, dst) in zip(arr, pairs):
+        assert src.dim() == 4 and dst.dim() == 4 and src.stride(3) == 1 and dst.stride(3) == 1
+        assert src.shape[:2] == dst.shape[:2] and src.shape[3] == dst.shape[3] and src.element_size() == eb
+        g.src, g.dst = src.data_ptr(), dst.data_ptr()
+        g.src_stride_b, g.src_stride_inner, g.src_stride_row = (src.stride(i) * eb for i in range(3))
+        g.dst_stride_b, g.dst_stride_inner, g.dst_stride_row = (dst.stride(i) * eb for i in range(3))
+    ist = 0 if keep_idx is None else keep_idx.stride(0)
+    _check(lib().st3_gather_rows(arr, len(pairs), src0.shape[0], src0.shape[1], src0.shape[3] * eb, head_rows,
+                                 _ptr(keep_idx), ist, k, n, tail_rows, _stream(stream)), "st3_gather_rows")
 
 
 def st3_select_compact_layer(shape, kv: KvLayer, seg: Segments, score_col, id_col, keep_count, mode, workspace,

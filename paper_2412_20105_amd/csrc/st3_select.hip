@@ -136,6 +136,50 @@ __global__ __launch_bounds__(kSelThreads) void evict_plan_kernel(EvictArgs a) {
     evict_plan_body(a, blockIdx.x, sm);
 }
 
+// ---- st3_gather_rows: out-of-place gather of kept rows, several tensors per launch -------------
+struct GatherArgs {
+    st3_gather_pair pair[ST3_MAX_GATHER];
+    const int32_t* idx;
+    int64_t idx_stride;
+    int32_t n_pairs, vecs_per_row, head, k, n, tail;
+};
+
+// grid (ceil(rows*vecs_per_row / (256*UR)), inner, batch*n_pairs); a thread moves UR 16-byte vectors.
+__global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
+    constexpr int UR = 8;
+    const int p = blockIdx.z % a.n_pairs, b = blockIdx.z / a.n_pairs;
+    const st3_gather_pair& pr = a.pair[p];
+    const char* src = reinterpret_cast<const char*>(pr.src) + b * pr.src_stride_b + (int64_t)blockIdx.y * pr.src_stride_inner;
+    char* dst = reinterpret_cast<char*>(pr.dst) + b * pr.dst_stride_b + (int64_t)blockIdx.y * pr.dst_stride_inner;
+    const int32_t* idx = a.idx ? a.idx + (int64_t)b * a.idx_stride : nullptr;
+    const int rows = a.head + a.k + a.tail;
+    const int64_t total = (int64_t)rows * a.vecs_per_row;
+    const int64_t base = (int64_t)blockIdx.x * (256 * UR) + threadIdx.x;
+    u32x4_v tmp[UR];
+    int64_t doff[UR];
+#pragma unroll
+    for (int u = 0; u < UR; ++u) {
+        const int64_t e = base + (int64_t)u * 256;
+        doff[u] = -1;
+        if (e < total) {
+            const int r = (int)(e / a.vecs_per_row), vec = (int)(e % a.vecs_per_row);
+            int sr;
+            if (r < a.head) sr = r;
+            else if (r < a.head + a.k) {
+                const int j = idx ? idx[r - a.head] : r - a.head;
+                sr = (j >= 0 && j < a.n) ? a.head + j : -1;
+            } else sr = r - a.k + a.n;
+            if (sr >= 0) {
+                tmp[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_v*>(src + sr * pr.src_stride_row + (int64_t)vec * 16));
+                doff[u] = r * pr.dst_stride_row + (int64_t)vec * 16;
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UR; ++u)
+        if (doff[u] >= 0) *reinterpret_cast<u32x4_v*>(dst + doff[u]) = tmp[u];
+}
+
 struct ApplyArgs {
     char* k;
     char* v;
@@ -459,6 +503,45 @@ extern "C" st3_status st3_compact_rows(void* rows, int32_t batch, int32_t inner,
     if (vec16) st3::compact_rows_kernel<uint4><<<grid, 256, 0, st>>>(a);
     else st3::compact_rows_kernel<uint32_t><<<grid, 256, 0, st>>>(a);
     return st3::check_launch();
+}
+
+extern "C" st3_status st3_gather_rows(const st3_gather_pair* pairs, int32_t n_pairs, int32_t batch, int32_t inner,
+                                      int32_t row_bytes, int32_t head_rows, const int32_t* keep_idx, int64_t idx_stride,
+                                      int32_t k, int32_t n, int32_t tail_rows, void* stream) {
+    using namespace st3;
+    if (!pairs || n_pairs <= 0 || n_pairs > ST3_MAX_GATHER || batch <= 0 || inner <= 0) return ST3_ERR_INVALID_ARG;
+    if (row_bytes <= 0 || row_bytes % 16 || head_rows < 0 || k < 0 || n < 0 || k > n || tail_rows < 0)
+        return ST3_ERR_INVALID_ARG;
+    if (!keep_idx && k != n) return ST3_ERR_INVALID_ARG;
+    if (keep_idx && idx_stride < k) return ST3_ERR_INVALID_ARG;
+    if ((int64_t)batch * n_pairs > 65535 || inner > 65535) return ST3_ERR_UNSUPPORTED;
+    const int64_t src_rows = (int64_t)head_rows + n + tail_rows, dst_rows = (int64_t)head_rows + k + tail_rows;
+    GatherArgs a{};
+    for (int p = 0; p < n_pairs; ++p) {
+        const st3_gather_pair& g = pairs[p];
+        if (!g.src || !g.dst || !aligned16(g.src) || !aligned16(g.dst)) return ST3_ERR_INVALID_ARG;
+        const int64_t st[6] = {g.src_stride_b, g.src_stride_inner, g.src_stride_row,
+                               g.dst_stride_b, g.dst_stride_inner, g.dst_stride_row};
+        for (int64_t v : st) if (v < 0 || v % 16) return ST3_ERR_INVALID_ARG;
+        if (g.src_stride_row < row_bytes || g.dst_stride_row < row_bytes) return ST3_ERR_INVALID_ARG;
+        // the whole source and destination regions of this pair must be disjoint
+        const char* s0 = reinterpret_cast<const char*>(g.src);
+        const char* d0 = reinterpret_cast<const char*>(g.dst);
+        const int64_t s_ext = (batch - 1) * g.src_stride_b + (inner - 1) * g.src_stride_inner +
+                              (src_rows > 0 ? (src_rows - 1) * g.src_stride_row + row_bytes : 0);
+        const int64_t d_ext = (batch - 1) * g.dst_stride_b + (inner - 1) * g.dst_stride_inner +
+                              (dst_rows > 0 ? (dst_rows - 1) * g.dst_stride_row + row_bytes : 0);
+        if (s0 < d0 + d_ext && d0 < s0 + s_ext) return ST3_ERR_INVALID_ARG;
+        a.pair[p] = g;
+    }
+    if (dst_rows == 0) return ST3_OK;
+    a.idx = keep_idx; a.idx_stride = idx_stride; a.n_pairs = n_pairs; a.vecs_per_row = row_bytes / 16;
+    a.head = head_rows; a.k = k; a.n = n; a.tail = tail_rows;
+    const int64_t total = dst_rows * a.vecs_per_row;
+    const int64_t blocks = (total + 256 * 8 - 1) / (256 * 8);
+    if (blocks > 0x7fffffff) return ST3_ERR_UNSUPPORTED;
+    gather_rows_kernel<<<dim3((unsigned)blocks, inner, batch * n_pairs), 256, 0, reinterpret_cast<hipStream_t>(stream)>>>(a);
+    return check_launch();
 }
 
 extern "C" st3_status st3_select_compact_layer(const st3_attn_shape* shape, const st3_kv_layer* kv,

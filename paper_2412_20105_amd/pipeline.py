@@ -104,13 +104,6 @@ class Generation:
         self._eb = eb
 
     # ------------------------------------------------------------------------------------
-    def _compact_strips(self, t: torch.Tensor, idx: torch.Tensor, k: int, n: int, tail: int):
-        """Stable gather of rows [n_sys, n_sys+n) of a [B,H,rows,d] tensor by idx, then the tail."""
-        eb = self._eb
-        base = t.data_ptr() + self.n_sys * t.stride(2) * eb
-        st3.st3_compact_rows(base, self.B, self.H, t.stride(0) * eb, t.stride(1) * eb, t.stride(2) * eb,
-                             self.d * eb, idx, k, n, tail)
-
     def _compact_column(self, col: torch.Tensor, idx: torch.Tensor, k: int, n: int):
         st3.st3_compact_rows(col.data_ptr(), self.B, 1, col.stride(0) * 4, 0, 4, 4, idx, k, n, 0)
 
@@ -141,22 +134,17 @@ class Generation:
                 self._alive = k_l
         alive = self._alive
         n_l = ns + alive + nx
-        # stage the layer's inputs: K and V straight into the cache, Q into scratch
-        lc.v[:, :, :self.N0].copy_(V)
+        # stage the layer's inputs, K and V straight into the cache and Q into scratch, in ONE gather
+        # launch (Alg. 1/3: X = [S, V[T], I]; ids are the ascending original positions of the survivors)
         if src is None:
-            lc.k[:, :, :self.N0].copy_(K)
-            self.q_stage.copy_(Q)
-            staged = (lc.k, lc.v, self.q_stage)
+            pairs = [(Q, self.q_stage), (K, lc.k), (V, lc.v)]
             k_rows = lc.k
         else:
             # Self-attn(Q^src, K^src, V^l): the source's compacted queries are still staged (only
             # lazy layers came in between) and its keys are the first n_l rows of its cache
-            staged = (lc.v,)
+            pairs = [(V, lc.v)]
             k_rows = self.layers[src].k
-        if alive < nv:
-            # Alg. 1/3: X = [S, V[T], I]; ids are ascending original positions of the survivors
-            for t in staged:
-                self._compact_strips(t, lc.ids, alive, nv, nx)
+        st3.st3_gather_rows(pairs, ns, lc.ids if alive < nv else None, alive, nv, nx)
         out = self.out_stage[:, :, :n_l]
         st3.st3_prefill_attention(self.shape, self.q_stage[:, :, :n_l], k_rows[:, :, :n_l], lc.v[:, :, :n_l],
                                   n_l, ns, alive, self.window, out, lc.mass, lc.ws)

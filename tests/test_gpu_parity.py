@@ -224,6 +224,54 @@ def test_compact_rows_stable(row_bytes, inner, stride_pad):
 # ---------------------------------------------------------------------------
 # select-and-compact of a layer's cache
 # ---------------------------------------------------------------------------
+@pytest.mark.parametrize("B,inner,width,dtype,head,n,k,tail,n_pairs", [
+    (3, 5, 128, torch.bfloat16, 35, 200, 77, 40, 3),        # Q, K, V rows of a layer in one launch
+    (2, 1, 5120, torch.bfloat16, 8, 64, 33, 16, 1),         # hidden rows at full width (10 KB)
+    (2, 3, 64, torch.float32, 0, 50, 50, 0, 2),             # identity list = strided copy, no head, no tail
+    (1, 2, 8, torch.bfloat16, 4, 30, 0, 3, 4),              # nothing kept; 16-byte rows; four tensors
+    (2, 2, 128, torch.bfloat16, 3, 2880, 1500, 256, 2),     # high-resolution segment
+])
+def test_gather_rows(B, inner, width, dtype, head, n, k, tail, n_pairs):
+    """Alg. 1/3: X = [S, V[T], I] rebuilt out of place for several tensors with one index list."""
+    print(f"gather B={B} inner={inner} width={width} n={n} k={k} pairs={n_pairs}", flush=True)
+    g = torch.Generator(device="cpu"); g.manual_seed(n * 7 + k)
+    rows_src, rows_dst = head + n + tail, head + k + tail
+    idx = torch.stack([torch.sort(torch.randperm(n, generator=g)[:k]).values for _ in range(B)]).to(torch.int32)
+    if k == n:
+        idx_dev = None
+    else:
+        idx_dev = torch.full((B, k + 5), -3, dtype=torch.int32)
+        idx_dev[:, :k] = idx
+        idx_dev = idx_dev.to(DEV)[:, :max(k, 1)] if k > 0 else idx_dev.to(DEV)
+    pairs, refs = [], []
+    for p in range(n_pairs):
+        src = torch.randn((B, inner, rows_src + p, width), generator=g).to(dtype)      # own strides per tensor
+        dst = torch.full((B, inner, rows_dst + 2 * p + 1, width), 9.0, dtype=dtype)
+        ref = dst.clone()
+        for b in range(B):
+            take = torch.cat([torch.arange(head), head + idx[b].long(), head + n + torch.arange(tail)])
+            ref[b, :, :rows_dst] = src[b][:, take]
+        d_src, d_dst = src.to(DEV), dst.to(DEV)
+        pairs.append((d_src, d_dst)); refs.append(ref)
+    st3.st3_gather_rows(pairs, head, idx_dev, k, n, tail)
+    torch.cuda.synchronize()
+    for (d_src, d_dst), ref in zip(pairs, refs):
+        assert torch.equal(d_dst.cpu().view(torch.uint8), ref.view(torch.uint8))      # bit exact, rows beyond untouched
+
+
+def test_gather_rows_argument_errors():
+    a = torch.zeros((1, 1, 8, 8), dtype=torch.bfloat16, device=DEV)
+    b = torch.zeros((1, 1, 8, 8), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(st3.St3Error):
+        st3.st3_gather_rows([(a, a)], 0, None, 8, 8, 0)                      # destination overlaps source
+    with pytest.raises(st3.St3Error):
+        st3.st3_gather_rows([(a, b)], 0, None, 4, 8, 0)                      # no list, but k != n
+    with pytest.raises(st3.St3Error):
+        st3.st3_gather_rows([(a, b)] * 5, 0, None, 8, 8, 0)                  # too many tensors
+    with pytest.raises(st3.St3Error):
+        st3.st3_gather_rows([(a[..., :4], b[..., :4])], 0, None, 8, 8, 0)    # 8-byte rows
+
+
 @pytest.mark.parametrize("mode", [st3.ST3_STABLE, st3.ST3_HOLE_FILL])
 @pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
 def test_select_compact_layer(mode, dtype, D):
