@@ -47,6 +47,9 @@ def parse():
                     help="QK heredity groups (Eq. 6, Alg. 2) as SRC:FIRST-LAST[,SRC:FIRST-LAST...], e.g. 36:37-39 = "
                          "layers 37..39 reuse the attention probabilities of layer 36 (the paper's '28 -> 29~31' for "
                          "the 7B model); lazy layers take their source's row of the retention table")
+    ap.add_argument("--prefill-probe", action="store_true",
+                    help="prefill only (all layers with progressive pruning), three passes, for kernel traces and MFMA "
+                         "counters of the prefill attention kernel; prints each layer's length and algorithmic flops")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="short run for counter collection: prefill, one plain 1 GiB device copy of known size, "
                          "then the decode steps; prints the algorithmic bytes of each attend launch")
@@ -187,6 +190,21 @@ def pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy=None):
                       "inherit_alg_bytes_per_launch_mean": (sum(per_lazy) / len(per_lazy)) if per_lazy else None}))
 
 
+def prefill_probe(w, B, keep, torch, pipeline, st3):
+    """Three prefill passes; per layer: tokens attended and algorithmic flops (causal half of QK^T and PV)."""
+    job = Job(w, B, 1, [row[:2] for row in keep], torch, pipeline, st3)
+    for _ in range(3):
+        job.run_prefill_only()
+    torch.cuda.synchronize()
+    ms = timed(torch, job.run_prefill_only, 3) * 1e3
+    layers = []
+    for l in range(w.layers):
+        n_l = w.n_sys + keep[l][0] + w.n_txt
+        layers.append({"layer": l, "n": n_l, "flops": B * 4 * w.heads * w.head_dim * n_l * (n_l + 1) // 2})
+    print(json.dumps({"probe": "prefill", "workload": w.name, "batch": B, "prefill_ms_all_layers": ms,
+                      "flops_all_layers": sum(x["flops"] for x in layers), "layers": layers}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -229,6 +247,8 @@ def main():
     def note(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
+    if a.prefill_probe:
+        return prefill_probe(w, B, keep, torch, pipeline, st3)
     if a.pmc_probe:
         return pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy)
 

@@ -12,6 +12,7 @@ struct PrefillArgs {
     int64_t v_sb, v_sh, v_st;
     int64_t o_sb, o_sh, o_st;
     int32_t n, sys_len, vis_len, window, H;
+    int32_t B, n_qt;                // batch and query tiles per strip (filled in by the MFMA launcher)
     float scale_l2;                 // softmax scale times log2(e)
     float* pre_logits;              // [B,H,W,vis_len] log2-domain logits of the last W rows (null: no mass)
     float* pre_ml;                  // [B,H,W,2] row max and row sum of those rows

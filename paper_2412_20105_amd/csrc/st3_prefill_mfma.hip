@@ -107,8 +107,31 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
     __shared__ __attribute__((aligned(16))) uint16_t Ks[kBN * KPAD];
     __shared__ __attribute__((aligned(16))) uint16_t Vt[D * kVPad];
 
-    const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;
-    const int h = blockIdx.y, b = blockIdx.z;
+    // Workgroup -> (query tile, strip).  Workgroups go round-robin by linear id to the 8 XCDs (checked
+    // with a probe: XCC id == id % 8) and, within an XCD, in turn to its 4 shader engines; each XCD
+    // has an L2 of its own; a causal query tile costs in proportion to its index.  With the query
+    // tile as the fastest index, a tile count of 2 or 4 hands all heavy tiles to the same engines
+    // (measured: 4 tiles per strip ran slower than 5).  So each of the 32 dispatch lanes
+    // (id % 32) owns the strips congruent to it and receives the tiles of one strip back to back,
+    // heaviest first: all lanes see the same cost sequence and a strip's K and V stay in one L2.
+#ifndef ST3_PREFILL_LANES
+#define ST3_PREFILL_LANES 32
+#endif
+    constexpr int kLanes = ST3_PREFILL_LANES;
+    const int n_qt = a.n_qt, strips = a.H * a.B;
+    const int full = strips / kLanes * kLanes;
+    const int lin = blockIdx.x;
+    int strip, qt;
+    if (lin < full * n_qt) {
+        const int dl = lin % kLanes, m = lin / kLanes;
+        strip = (m / n_qt) * kLanes + dl;
+        qt = n_qt - 1 - m % n_qt;
+    } else {                                    // the strips left over when H*B is no multiple of 32
+        const int r = lin - full * n_qt;
+        strip = full + r / n_qt;
+        qt = n_qt - 1 - r % n_qt;
+    }
+    const int h = strip % a.H, b = strip / a.H;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, c = lane & 31;
     const int n = a.n;
@@ -251,9 +274,14 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
 
 st3_status launch_prefill_mfma(const PrefillArgs& a, int B, int D, hipStream_t st) {
     // 8-byte output stores and 16-byte input loads need these alignments (rows are 16-byte aligned already)
-    dim3 grid((a.n + kBM - 1) / kBM, a.H, B);
-    if (D == 128) prefill_mfma_kernel<128><<<grid, 256, 0, st>>>(a);
-    else if (D == 64) prefill_mfma_kernel<64><<<grid, 256, 0, st>>>(a);
+    PrefillArgs pa = a;
+    pa.n_qt = (a.n + kBM - 1) / kBM;
+    pa.B = B;
+    const int64_t wgs = (int64_t)pa.n_qt * a.H * B;
+    if (wgs > 0x7fffffff) return ST3_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)wgs);
+    if (D == 128) prefill_mfma_kernel<128><<<grid, 256, 0, st>>>(pa);
+    else if (D == 64) prefill_mfma_kernel<64><<<grid, 256, 0, st>>>(pa);
     else return ST3_ERR_UNSUPPORTED;
     return ST3_OK;
 }

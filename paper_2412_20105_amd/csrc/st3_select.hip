@@ -141,28 +141,38 @@ struct GatherArgs {
     st3_gather_pair pair[ST3_MAX_GATHER];
     const int32_t* idx;
     int64_t idx_stride;
-    int32_t n_pairs, vecs_per_row, head, k, n, tail;
+    int32_t n_pairs, vecs_per_row, vpr_shift, head, k, n, tail;     // vpr_shift >= 0: vecs_per_row == 1 << vpr_shift
 };
 
 // grid (ceil(rows*vecs_per_row / (256*UR)), inner, batch*n_pairs); a thread moves UR 16-byte vectors.
+#ifndef ST3_GATHER_UR
+#define ST3_GATHER_UR 4         // 8 was measured 2x slower, 1-4 alike
+#endif
+#ifndef ST3_GATHER_NT
+#define ST3_GATHER_NT 1
+#endif
+constexpr int kGatherUR = ST3_GATHER_UR;
 __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
-    constexpr int UR = 8;
+    constexpr int UR = kGatherUR;
     const int p = blockIdx.z % a.n_pairs, b = blockIdx.z / a.n_pairs;
     const st3_gather_pair& pr = a.pair[p];
     const char* src = reinterpret_cast<const char*>(pr.src) + b * pr.src_stride_b + (int64_t)blockIdx.y * pr.src_stride_inner;
     char* dst = reinterpret_cast<char*>(pr.dst) + b * pr.dst_stride_b + (int64_t)blockIdx.y * pr.dst_stride_inner;
     const int32_t* idx = a.idx ? a.idx + (int64_t)b * a.idx_stride : nullptr;
     const int rows = a.head + a.k + a.tail;
-    const int64_t total = (int64_t)rows * a.vecs_per_row;
-    const int64_t base = (int64_t)blockIdx.x * (256 * UR) + threadIdx.x;
+    const uint32_t total = (uint32_t)rows * (uint32_t)a.vecs_per_row;      // < 2^31, checked on the host
+    const uint32_t base = blockIdx.x * (256u * UR) + threadIdx.x;
     u32x4_v tmp[UR];
     int64_t doff[UR];
 #pragma unroll
     for (int u = 0; u < UR; ++u) {
-        const int64_t e = base + (int64_t)u * 256;
+        const uint32_t e = base + (uint32_t)u * 256u;
         doff[u] = -1;
         if (e < total) {
-            const int r = (int)(e / a.vecs_per_row), vec = (int)(e % a.vecs_per_row);
+            // 32-bit index arithmetic, a shift when the row is a power of two vectors long: a 64-bit
+            // division per 16 bytes moved made this kernel ALU bound
+            const int r = a.vpr_shift >= 0 ? (int)(e >> a.vpr_shift) : (int)(e / (uint32_t)a.vecs_per_row);
+            const int vec = (int)(e - (uint32_t)r * (uint32_t)a.vecs_per_row);
             int sr;
             if (r < a.head) sr = r;
             else if (r < a.head + a.k) {
@@ -170,7 +180,11 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
                 sr = (j >= 0 && j < a.n) ? a.head + j : -1;
             } else sr = r - a.k + a.n;
             if (sr >= 0) {
+#if ST3_GATHER_NT
                 tmp[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_v*>(src + sr * pr.src_stride_row + (int64_t)vec * 16));
+#else
+                tmp[u] = *reinterpret_cast<const u32x4_v*>(src + sr * pr.src_stride_row + (int64_t)vec * 16);
+#endif
                 doff[u] = r * pr.dst_stride_row + (int64_t)vec * 16;
             }
         }
@@ -538,8 +552,11 @@ extern "C" st3_status st3_gather_rows(const st3_gather_pair* pairs, int32_t n_pa
     a.idx = keep_idx; a.idx_stride = idx_stride; a.n_pairs = n_pairs; a.vecs_per_row = row_bytes / 16;
     a.head = head_rows; a.k = k; a.n = n; a.tail = tail_rows;
     const int64_t total = dst_rows * a.vecs_per_row;
-    const int64_t blocks = (total + 256 * 8 - 1) / (256 * 8);
-    if (blocks > 0x7fffffff) return ST3_ERR_UNSUPPORTED;
+    if (total >= 0x7fffffff) return ST3_ERR_UNSUPPORTED;           // the kernel indexes a strip with 32 bits
+    a.vpr_shift = -1;
+    for (int sh = 0; sh < 31; ++sh)
+        if ((1 << sh) == a.vecs_per_row) a.vpr_shift = sh;
+    const int64_t blocks = (total + 256 * kGatherUR - 1) / (256 * kGatherUR);
     gather_rows_kernel<<<dim3((unsigned)blocks, inner, batch * n_pairs), 256, 0, reinterpret_cast<hipStream_t>(stream)>>>(a);
     return check_launch();
 }
