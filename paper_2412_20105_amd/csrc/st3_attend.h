@@ -116,37 +116,43 @@ __device__ __forceinline__ void wave_attend(const float* qf, const T* kbase, con
     }
 }
 
-// Same contract as wave_attend, software-pipelined: the loads of tile i+1 are issued before tile i
-// is consumed, so a wave always has 2*U loads in flight while it computes.
+// Issues the loads of the tile of U*RPL rows that starts at t0: rows >= bound read `safe_row` instead.
 template <typename T, int D, int U, bool NT>
-__device__ __forceinline__ void wave_attend_pipelined(const float* qf, const T* kbase, const T* vbase,
-                                                      int64_t stride_t, int r0, int r1, int step, int safe_row,
-                                                      float scale_l2, int lane, WaveState<RowMap<T, D>::EPL>& st,
-                                                      float* logit_out, int vis_lo, int vis_hi) {
+__device__ __forceinline__ void issue_tile(const T* kbase, const T* vbase, int64_t stride_t, int t0, int bound,
+                                           int safe_row, int lane, uint4 (&k)[U], uint4 (&v)[U]) {
+    using M = RowMap<T, D>;
+    const int grp = lane / M::LPR;
+    const int64_t col = (int64_t)(lane % M::LPR) * M::EPL;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int row = t0 + u * M::RPL + grp;
+        k[u] = load16<NT>(kbase + (int64_t)(row < bound ? row : safe_row) * stride_t + col);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int row = t0 + u * M::RPL + grp;
+        v[u] = load16<NT>(vbase + (int64_t)(row < bound ? row : safe_row) * stride_t + col);
+    }
+}
+
+// Same contract as wave_attend, software-pipelined: the loads of tile i+1 are issued before tile i
+// is consumed, so a wave always has 2*U loads in flight while it computes.  The loads of the first
+// tile (rows from r0) have been issued by the caller into kr/vr with issue_tile(); any bound >= r1
+// that keeps the reads inside the strip will do there, which lets a kernel issue them before it
+// knows the sequence length.
+template <typename T, int D, int U, bool NT>
+__device__ __forceinline__ void wave_attend_primed(const float* qf, const T* kbase, const T* vbase, int64_t stride_t,
+                                                   int r0, int r1, int step, int safe_row, float scale_l2, int lane,
+                                                   WaveState<RowMap<T, D>::EPL>& st, float* logit_out, int vis_lo,
+                                                   int vis_hi, uint4 (&kr)[U], uint4 (&vr)[U]) {
     using M = RowMap<T, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, RPL = M::RPL;
     const int grp = lane / LPR;
-    const int64_t col = (int64_t)(lane % LPR) * EPL;
     if (r0 >= r1) return;
-    uint4 kr[U], vr[U], kn[U], vn[U];
-    auto issue = [&](int t0, uint4* k, uint4* v) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int row = t0 + u * RPL + grp;
-            int64_t off = (int64_t)(row < r1 ? row : safe_row) * stride_t + col;
-            k[u] = load16<NT>(kbase + off);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int row = t0 + u * RPL + grp;
-            int64_t off = (int64_t)(row < r1 ? row : safe_row) * stride_t + col;
-            v[u] = load16<NT>(vbase + off);
-        }
-    };
-    issue(r0, kr, vr);
+    uint4 kn[U], vn[U];
     for (int t0 = r0; t0 < r1; t0 += step) {
         const int tn = t0 + step;
-        if (tn < r1) issue(tn, kn, vn);
+        if (tn < r1) issue_tile<T, D, U, NT>(kbase, vbase, stride_t, tn, r1, safe_row, lane, kn, vn);
         float s[U];
         float mt = -INFINITY;
 #pragma unroll
@@ -186,6 +192,44 @@ __device__ __forceinline__ void wave_attend_pipelined(const float* qf, const T* 
             for (int u = 0; u < U; ++u) { kr[u] = kn[u]; vr[u] = vn[u]; }
         }
     }
+}
+
+template <typename T, int D, int U, bool NT>
+__device__ __forceinline__ void wave_attend_pipelined(const float* qf, const T* kbase, const T* vbase,
+                                                      int64_t stride_t, int r0, int r1, int step, int safe_row,
+                                                      float scale_l2, int lane, WaveState<RowMap<T, D>::EPL>& st,
+                                                      float* logit_out, int vis_lo, int vis_hi) {
+    if (r0 >= r1) return;
+    uint4 kr[U], vr[U];
+    issue_tile<T, D, U, NT>(kbase, vbase, stride_t, r0, r1, safe_row, lane, kr, vr);
+    wave_attend_primed<T, D, U, NT>(qf, kbase, vbase, stride_t, r0, r1, step, safe_row, scale_l2, lane, st, logit_out,
+                                    vis_lo, vis_hi, kr, vr);
+}
+
+// One more row for a wave's state, from registers: kraw/vraw hold this lane's 16-byte slices of the
+// row (every row-group holds the same row; only group 0 counts it).
+template <typename T, int D>
+__device__ __forceinline__ void wave_attend_row(const float* qf, uint4 kraw, uint4 vraw, int row, float scale_l2,
+                                                int lane, WaveState<RowMap<T, D>::EPL>& st, float* logit_out,
+                                                int vis_lo, int vis_hi) {
+    using M = RowMap<T, D>;
+    constexpr int EPL = M::EPL, LPR = M::LPR;
+    float kf[EPL], vf[EPL];
+    ElemTraits<T>::unpack(kraw, kf);
+    ElemTraits<T>::unpack(vraw, vf);
+    float part = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) part = fmaf(qf[e], kf[e], part);
+    part = group_sum<LPR>(part) * scale_l2;
+    if (logit_out != nullptr && lane == 0 && row >= vis_lo && row < vis_hi) logit_out[row - vis_lo] = part;
+    const float m_new = fmaxf(st.m, part);
+    const float alpha = exp2_fast(st.m - m_new);
+    st.m = m_new;
+    st.l *= alpha;
+    const float p = lane < LPR ? exp2_fast(part - m_new) : 0.f;
+    st.l += p;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) st.acc[e] = fmaf(p, vf[e], st.acc[e] * alpha);
 }
 
 // Folds the row-groups of a wave together: afterwards every lane holds the wave's total l and

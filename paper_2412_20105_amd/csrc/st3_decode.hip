@@ -74,15 +74,30 @@ __device__ __forceinline__ void store_out(void* out, int64_t idx, float o) {
 
 // grid (nsplit, H, B)
 template <typename T, int D, int U>
-__global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_attend_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS)
+__attribute__((amdgpu_waves_per_eu(ST3_DECODE_MIN_BLOCKS, ST3_DECODE_MIN_BLOCKS)))    // do not spill to reach a third wave
+void decode_attend_kernel(DecodeArgs a) {
     using M = RowMap<T, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, TILE = U * M::RPL;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    // the row being appended sits at index kv_len[b]; never trust a device length past the host bound
-    const int len = min(a.kv_len[b] + (a.k_new != nullptr ? 1 : 0), a.max_kv);
     const int c0 = split * a.chunk;
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int64_t bh = (int64_t)b * a.H + h;
+    const T* qrow = reinterpret_cast<const T*>(a.q) + bh * D;
+    T* kbase = reinterpret_cast<T*>(a.k) + b * a.stride_b + h * a.stride_h;
+    T* vbase = reinterpret_cast<T*>(a.v) + b * a.stride_b + h * a.stride_h;
+#if ST3_DECODE_PIPELINED
+    // The first tile's loads go out before the sequence length has arrived: the host bound keeps
+    // them inside the strip (rows the length later rules out are masked when the tile is consumed).
+    // Takes one dependent memory round trip off the front of every workgroup.
+    uint4 kr[U], vr[U];
+    issue_tile<T, D, U, true>(kbase, vbase, a.stride_t, c0 + wave * TILE,
+                              min(c0 + a.chunk, a.max_kv - (a.k_new != nullptr ? 1 : 0)), c0, lane, kr, vr);
+#endif
+    float qf[EPL];
+    load_q_slice<T, D>(qrow, lane, qf);
+    // the row being appended sits at index kv_len[b]; never trust a device length past the host bound
+    const int len = min(a.kv_len[b] + (a.k_new != nullptr ? 1 : 0), a.max_kv);
     if (split == 0 && h == 0 && tid == 0 && a.pending != nullptr) {
         a.pending[b * 4 + 0] = (a.logits != nullptr && len > 0 && a.defer) ? 1 : 0;
         a.pending[b * 4 + 1] = a.nsplit;
@@ -95,13 +110,6 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
     }
     if (c0 >= len) return;
     const int c1 = min(c0 + a.chunk, len);
-
-    const T* qrow = reinterpret_cast<const T*>(a.q) + bh * D;
-    T* kbase = reinterpret_cast<T*>(a.k) + b * a.stride_b + h * a.stride_h;
-    T* vbase = reinterpret_cast<T*>(a.v) + b * a.stride_b + h * a.stride_h;
-
-    float qf[EPL];
-    load_q_slice<T, D>(qrow, lane, qf);
 
     WaveState<EPL> st;
     st.m = -INFINITY; st.l = 0.f;
@@ -118,26 +126,28 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
     if (lg) lg += vis_lo;           // the wave loop indexes by (row - vis_lo)
     const bool has_new = a.k_new != nullptr && c1 == len;       // this workgroup owns the appended row
     const int c1_cached = has_new ? c1 - 1 : c1;
+    // the appended token's row is fetched now and used after the cached rows: off the critical path
+    u32x4_t kn_raw = {0, 0, 0, 0}, vn_raw = {0, 0, 0, 0};       // native vectors: the uint4 class would live in scratch
+    if (has_new && wave == 0) {
+        const int64_t col = bh * D + (lane % LPR) * EPL;
+        kn_raw = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const T*>(a.k_new) + col);
+        vn_raw = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const T*>(a.v_new) + col);
+    }
     // waves take the tiles of the chunk round-robin, so all four stay busy to the end
 #if ST3_DECODE_PIPELINED
-    wave_attend_pipelined<T, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
-                                   c0, a.scale_l2, lane, st, lg, vis_lo, vis_hi);
+    wave_attend_primed<T, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
+                                      c0, a.scale_l2, lane, st, lg, vis_lo, vis_hi, kr, vr);
 #else
     wave_attend<T, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0,
                          a.scale_l2, lane, st, lg, vis_lo, vis_hi);
 #endif
     if (has_new && wave == 0) {
-        // address the new token's rows as if they were cache row len-1
-        const int64_t shift = (int64_t)(len - 1) * a.stride_t;
-        const T* kn = reinterpret_cast<const T*>(a.k_new) + bh * D;
-        const T* vn = reinterpret_cast<const T*>(a.v_new) + bh * D;
-        wave_attend<T, D, 1, false>(qf, kn - shift, vn - shift, a.stride_t, len - 1, len, M::RPL, len - 1, a.scale_l2, lane,
-                             st, lg, vis_lo, vis_hi);
-        if (lane < 2 * LPR) {
-            const int c = (lane % LPR) * EPL;
-            const T* src = (lane < LPR ? kn : vn) + c;
-            T* dst = (lane < LPR ? kbase : vbase) + shift + c;
-            *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+        wave_attend_row<T, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
+                              make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, a.scale_l2, lane, st, lg, vis_lo,
+                              vis_hi);
+        if (lane < 2 * LPR) {                       // store the row into the cache: lanes [0,LPR) K, [LPR,2*LPR) V
+            T* dst = (lane < LPR ? kbase : vbase) + (int64_t)(len - 1) * a.stride_t + (lane % LPR) * EPL;
+            *reinterpret_cast<u32x4_t*>(dst) = lane < LPR ? kn_raw : vn_raw;
         }
     }
     finish_wave<T, D>(st);
