@@ -135,6 +135,11 @@ void decode_attend_kernel(DecodeArgs a) {
     }
     // waves take the tiles of the chunk round-robin, so all four stay busy to the end
 #if ST3_DECODE_PIPELINED
+    // rows of the early tile that the length rules out came from beyond the sequence: their V may
+    // hold anything (NaN included), and 0 * NaN would poison the accumulator
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (c0 + wave * TILE + u * M::RPL + lane / LPR >= c1_cached) vr[u] = make_uint4(0, 0, 0, 0);
     wave_attend_primed<T, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
                                       c0, a.scale_l2, lane, st, lg, vis_lo, vis_hi, kr, vr);
 #else

@@ -18,7 +18,7 @@ def _ws(shape, capacity, max_vis, window=1):
     n = st3.st3_workspace_bytes(shape, capacity, max_vis, window)
     assert n > 0
     ws = torch.empty((n,), dtype=torch.uint8, device=DEV)
-    ws.fill_(0xAB)                                   # not zero-filled: st3_workspace_init must do what is needed
+    ws.fill_(0xFF)                                   # all NaN bit patterns: nothing stale may be read unmasked
     st3.st3_workspace_init(shape, capacity, ws)
     return ws
 
@@ -49,6 +49,8 @@ def test_decode_attention_matches_oracle(dtype, D, B, H, lens, ns, nv):
     vis = [max(0, min(nv, L - ns)) for L in lens]
     shape = st3.make_shape(B, H, D, CODE[dtype])
     dK, dV, dq = to_dev(K, dtype), to_dev(V, dtype), to_dev(q, dtype)
+    for b in range(B):                                 # rows beyond a sequence hold NaN: they must never count
+        dK[b, :, lens[b]:] = float("nan"); dV[b, :, lens[b]:] = float("nan")
     out = torch.zeros((B, H, D), dtype=TORCH_DTYPE[dtype], device=DEV)
     mass = torch.full((B, nv + 3), -7.0, dtype=torch.float32, device=DEV)
     kv_len, vis_len = _i32(lens), _i32(vis)
@@ -372,6 +374,8 @@ def test_decode_attention_inherit(dtype, D, B, H, lens, ns, nv, cap_extra):
         Vl_ref[b, :, lens_before[b]] = vn[b]
     assert np.array_equal(dVl.float().cpu().numpy(), Vl_ref.astype(np.float32))
     lens_l = got_len                                         # = lens, except an empty sequence now holds one row
+    for b in range(B):                                       # rows beyond a sequence hold NaN: they must never count
+        dVl[b, :, lens_l[b]:] = float("nan"); dK[b, :, lens_l[b]:] = float("nan"); dVs[b, :, lens_l[b]:] = float("nan")
     kv_len_s = _i32(lens_l)
     # source layer attends (no mass asked for: the probabilities are kept all the same) ...
     st3.st3_decode_attention(shape, dq, st3.kv_layer(dK, dVs), st3.segments(ns, nv, max(lens_l), vis_len, kv_len_s),
@@ -412,6 +416,8 @@ def test_decode_layer_step(mode, dtype, D, H, lens, keep_after):
     ids = np.stack([rng.permutation(2000)[:nv] for _ in range(B)]).astype(np.int32)
     shape = st3.make_shape(B, H, D, CODE[dtype])
     dK, dV = to_dev(K, dtype), to_dev(V, dtype)
+    for b in range(B):                                 # rows beyond a sequence hold NaN: they must never count
+        dK[b, :, lens[b]:] = float("nan"); dV[b, :, lens[b]:] = float("nan")
     d_score, d_ids = torch.from_numpy(score.copy()).to(DEV), torch.from_numpy(ids.copy()).to(DEV)
     out = torch.zeros((B, H, D), dtype=TORCH_DTYPE[dtype], device=DEV)
     mass = torch.full((B, nv + 2), -7.0, dtype=torch.float32, device=DEV)
