@@ -26,6 +26,13 @@ What is defined here, and the passage each part follows:
 * `overlap`, `cosine_similarity`          - Eq. 10 and Eq. 4-5 (diagnostics).
 * `Generation`                            - Alg. 3 end to end on given Q/K/V:
   prefill with progressive pruning, then decode steps with annealing.
+* `e4m3_decode`, `e4m3_quantize`, `Generation(kv_format="e4m3")` - NOT from the
+  paper: the KV cache held in OCP FP8 E4M3 with one float32 scale per (b, h)
+  strip for K and one for V, as an implementation variant of the cache of
+  Sec. 4.3.  Codes follow the OCP 8-bit floating point specification (bias 7,
+  no infinities, S.1111.111 = NaN, largest finite 448); the quantiser divides
+  by the scale in float32, saturates at +-448 and rounds to nearest, ties to
+  the even code.  Attention then reads code value x scale.
 * `heredity_attention` and `Generation(lazy=...)` - Eq. 6 / Alg. 2 (QK
   heredity): a lazy layer l computes Self-attn(Q^{l-n}, K^{l-n}, V^l), i.e. the
   source layer's probabilities applied to its own values.
@@ -36,7 +43,9 @@ invariance; mass sums; brute-force top-k on all small cases; nestedness; the
 60 printed (L,S,R,P)->C rows of the paper's stride tables; beta closed forms;
 KV bytes against the paper's Table 2 baseline rows; QK heredity: equal values
 give back the source layer's output, the result is linear in V, one-hot values
-return the probabilities themselves.  Accuracy/CIDEr/A100
+return the probabilities themselves; E4M3: all 256 codes and in-range
+rounding against a library float8_e4m3fn conversion, midpoints, saturation,
+idempotence.  Accuracy/CIDEr/A100
 latency figures of the paper are parity unpinned (they need datasets, trained
 weights and other systems).
 """
@@ -316,6 +325,47 @@ def kv_bytes(B: int, H: int, d: int, elem_bytes: int, lens: Sequence[int],
 
 
 # ---------------------------------------------------------------------------
+# FP8 E4M3 KV-cache variant (implementation choice, not in the paper)
+# ---------------------------------------------------------------------------
+E4M3_MAX = 448.0
+
+
+def e4m3_decode(codes) -> np.ndarray:
+    """Value of OCP FP8 E4M3 codes (uint8): sign bit, 4 exponent bits (bias 7), 3 mantissa bits;
+    exponent 0 is subnormal (m/8 * 2^-6); S.1111.111 is NaN; there are no infinities."""
+    c = np.asarray(codes, np.uint8).astype(np.int64)
+    sign = np.where(c >> 7 == 1, -1.0, 1.0)
+    e = (c >> 3) & 15
+    m = c & 7
+    normal = (1.0 + m / 8.0) * np.exp2((e - 7).astype(F64))
+    sub = (m / 8.0) * 2.0 ** -6
+    v = sign * np.where(e == 0, sub, normal)
+    return np.where((e == 15) & (m == 7), np.nan, v)
+
+
+def e4m3_quantize(x, scale) -> np.ndarray:
+    """Codes of x / scale: the division is done in float32 (x and scale as float32), the quotient
+    saturates at +-448 and is rounded to the nearest E4M3 value, ties to the even code; the sign is
+    kept (also of zero); NaN gives 0x7F."""
+    t = np.asarray(x, np.float32) / np.asarray(scale, np.float32)
+    table = e4m3_decode(np.arange(0x7F, dtype=np.uint8))       # the 127 non-negative finite values, ascending
+    a = np.minimum(np.abs(t).astype(F64), E4M3_MAX)
+    hi = np.clip(np.searchsorted(table, a, side="left"), 0, 0x7E)      # first value >= a
+    lo = np.maximum(hi - 1, 0)
+    d_hi, d_lo = table[hi] - a, a - table[lo]
+    pick_lo = (d_lo < d_hi) | ((d_lo == d_hi) & (lo % 2 == 0))
+    code = np.where(pick_lo, lo, hi).astype(np.uint8)
+    code = np.where(np.signbit(t), code | 0x80, code).astype(np.uint8)
+    return np.where(np.isnan(t), np.uint8(0x7F), code).astype(np.uint8)
+
+
+def e4m3_roundtrip(x, scale) -> np.ndarray:
+    """What a cache in E4M3 returns for x: decode(quantize(x, scale)) * scale (scale as float32)."""
+    sc = np.asarray(scale, np.float32).astype(F64)
+    return e4m3_decode(e4m3_quantize(x, scale)) * sc
+
+
+# ---------------------------------------------------------------------------
 # Alg. 3 end to end
 # ---------------------------------------------------------------------------
 class Generation:
@@ -337,12 +387,21 @@ class Generation:
 
     def __init__(self, L: int, H: int, d: int, n_sys: int, n_vis: int, n_txt: int,
                  keep: np.ndarray, window: int = 1, mode: str = "static",
-                 scale: Optional[float] = None, lazy: Optional[Dict[int, int]] = None):
+                 scale: Optional[float] = None, lazy: Optional[Dict[int, int]] = None,
+                 kv_format: str = "same", k_scale=None, v_scale=None):
         self.L, self.H, self.d = L, H, d
         self.n_sys, self.n_vis, self.n_txt = n_sys, n_vis, n_txt
         self.keep = np.asarray(keep)
         assert self.keep.shape[0] == L
         self.window, self.mode, self.scale = window, mode, scale
+        # kv_format "e4m3": what enters a cache (prefill rows, appended rows) is replaced by its
+        # E4M3 round trip with scales k_scale[b, h], v_scale[b, h]; the prefill attention itself
+        # still sees the unquantised prompt
+        if kv_format not in ("same", "e4m3"):
+            raise ValueError(kv_format)
+        self.kv_format = kv_format
+        self.k_scale = None if k_scale is None else np.asarray(k_scale, np.float32)
+        self.v_scale = None if v_scale is None else np.asarray(v_scale, np.float32)
         self.lazy = dict(lazy or {})
         for l, src in self.lazy.items():
             if not (0 <= src < l < L) or src in self.lazy:
@@ -356,6 +415,12 @@ class Generation:
         self.K: List[List[np.ndarray]] = []
         self.V: List[List[np.ndarray]] = []
         self.t = 0
+
+    def _into_cache(self, rows: np.ndarray, scales, b: int) -> np.ndarray:
+        """rows [H, n, d] as the cache of sequence b will return them."""
+        if self.kv_format == "same":
+            return np.array(rows, F64)
+        return e4m3_roundtrip(rows, scales[b][:, None, None])
 
     # -- prefill ------------------------------------------------------------
     def prefill(self, qkv_of_layer) -> Dict[str, list]:
@@ -399,8 +464,8 @@ class Generation:
                                          V[b:b + 1][:, :, rows], ns, len(ids_l[b]),
                                          self.window, self.scale)
                 out_l.append(o[0]); mass_l.append(m[0])
-                Kc.append(None if l in self.lazy else K[b][:, rows].copy())
-                Vc.append(V[b][:, rows].copy())
+                Kc.append(None if l in self.lazy else self._into_cache(K[b][:, rows], self.k_scale, b))
+                Vc.append(self._into_cache(V[b][:, rows], self.v_scale, b))
                 # ranking column: the scores that last decided membership; a
                 # layer that precedes every prune event ranks by its own mass
                 rho_l.append(m[0].copy() if inherited[b] is None else inherited[b].copy())
@@ -442,8 +507,9 @@ class Generation:
                     self.ids[l][b] = ids = ids[pos]
                     self.rho[l][b] = rho = rho[pos]
                 if src is None:
-                    self.K[l][b] = np.concatenate([self.K[l][b], k[b][:, None, :]], axis=1)
-                self.V[l][b] = np.concatenate([self.V[l][b], v[b][:, None, :]], axis=1)
+                    self.K[l][b] = np.concatenate([self.K[l][b], self._into_cache(k[b][:, None, :], self.k_scale, b)],
+                                                  axis=1)
+                self.V[l][b] = np.concatenate([self.V[l][b], self._into_cache(v[b][:, None, :], self.v_scale, b)], axis=1)
                 # ... and keys (its cache holds the same rows in the same order), this layer's values
                 Kb = self.K[l][b] if src is None else self.K[src][b]
                 o, m, _ = decode_attention(q[b:b + 1], Kb[None], self.V[l][b][None],
