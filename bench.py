@@ -47,6 +47,9 @@ def parse():
                     help="QK heredity groups (Eq. 6, Alg. 2) as SRC:FIRST-LAST[,SRC:FIRST-LAST...], e.g. 36:37-39 = "
                          "layers 37..39 reuse the attention probabilities of layer 36 (the paper's '28 -> 29~31' for "
                          "the 7B model); lazy layers take their source's row of the retention table")
+    ap.add_argument("--kv-format", default="plain", choices=["plain", "e4m3"],
+                    help="e4m3: the KV caches hold FP8 E4M3 codes with one scale per (b, h) strip (6 sigma / 448); an extra "
+                         "configuration beside the bf16 headline, not part of the paper")
     ap.add_argument("--prefill-probe", action="store_true",
                     help="prefill only (all layers with progressive pruning), three passes, for kernel traces and MFMA "
                          "counters of the prefill attention kernel; prints each layer's length and algorithmic flops")
@@ -59,9 +62,10 @@ def parse():
 class Job:
     """Device-resident inputs of one batch and the call sequence of one whole job."""
 
-    def __init__(self, w, B, T, keep, torch, pipeline, st3, seed=1234, lazy=None):
+    def __init__(self, w, B, T, keep, torch, pipeline, st3, seed=1234, lazy=None, kv_format="plain"):
         self.w, self.B, self.T, self.keep = w, B, T, keep
         self.lazy = dict(lazy or {})
+        self.kv_format = kv_format
         self.torch = torch
         dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         dev = "cuda:0"
@@ -76,7 +80,8 @@ class Job:
         self.pre = [tuple(randn(shape_p) for _ in range(3)) for _ in range(w.layers)]
         self.dec = [randn(shape_d) for _ in range(T)]
         self.gen = pipeline.Generation(w.layers, w.heads, w.head_dim, dt, B, w.n_sys, w.n_vis, w.n_txt, T, keep,
-                                       device=dev, lazy=self.lazy)
+                                       device=dev, lazy=self.lazy,
+                                       kv_scale=(6 * w.sigma / 448) if kv_format == "e4m3" else None)
 
     def run(self):
         gen, w = self.gen, self.w
@@ -99,13 +104,14 @@ class Job:
         step) K and V rows read once, plus q in, o out and the mass row."""
         w = self.w
         e = 2 if w.dtype == "bf16" else 4
+        ekv = 1 if self.kv_format == "e4m3" else e
         total = 0
         for t in range(1, self.T + 1):
             for l in range(w.layers):
                 if l in self.lazy:          # a lazy layer runs the V-only kernel, not this one
                     continue
                 lkv = w.n_sys + self.keep[l][t] + w.n_txt + t
-                total += self.B * (2 * w.heads * w.head_dim * e * lkv + 2 * w.heads * w.head_dim * e
+                total += self.B * (2 * w.heads * w.head_dim * ekv * lkv + 2 * w.heads * w.head_dim * e
                                    + 4 * self.keep[l][t])
         return total
 
@@ -253,7 +259,7 @@ def main():
         return pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy)
 
     note(f"generating inputs for {w.name} B={B} T={T}")
-    job = Job(w, B, T, keep, torch, pipeline, st3, lazy=lazy)
+    job = Job(w, B, T, keep, torch, pipeline, st3, lazy=lazy, kv_format=a.kv_format)
     note("warmup")
     for _ in range(a.warmup):
         job.run()
@@ -274,7 +280,7 @@ def main():
                                f"{w.n_sys}+{w.n_vis}+{w.n_txt}, T={T} decode steps, batch {B}, "
                                f"schedule {w.layer_schedule}/{w.step_schedule}",
                    "batch": B, "decode_steps": T, "step_definition": "prefill (all layers, PVTP) + T decode steps (VTA)",
-                   "lazy_layers": {str(l): s for l, s in sorted(lazy.items())}},
+                   "lazy_layers": {str(l): s for l, s in sorted(lazy.items())}, "kv_format": a.kv_format},
         "prefill_ms": ms_prefill,
         "decode_ms_per_token_step": (ms_job - ms_prefill) / T,
         "decode_only_tokens_per_s": tokens / ((ms_job - ms_prefill) * 1e-3),
@@ -295,7 +301,7 @@ def main():
         try:        # HBM bytes per launch from the committed counter runs, when they cover this workload
             with open(os.path.join(ROOT, "paper_2412_20105_amd", "measured_traffic.json")) as f:
                 mt = json.load(f)["decode_attend_kernel"]
-            if mt["workload"] == w.name and mt["batch"] == B:
+            if mt["workload"] == w.name and mt["batch"] == B and a.kv_format == "plain":
                 # measured over the first decode steps: scale the ratio to this job's mean launch
                 traffic = mt["traffic_over_algorithmic"] * alg / max(cnt, 1)
         except (OSError, KeyError, ValueError):
@@ -315,7 +321,7 @@ def main():
         keep_u = [row[:T + 1] for row in pipeline.keep_table_for(wu)]
         del job.gen
         torch.cuda.empty_cache()
-        job_u = Job(wu, B, T, keep_u, torch, pipeline, st3)
+        job_u = Job(wu, B, T, keep_u, torch, pipeline, st3, kv_format=a.kv_format)
         job_u.pre, job_u.dec = job.pre, job.dec
         job_u.run()
         ms_u = timed(torch, job_u.run, 1) * 1e3

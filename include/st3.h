@@ -44,7 +44,7 @@ typedef enum {
     ST3_ERR_HIP = 4
 } st3_status;
 
-typedef enum { ST3_F32 = 0, ST3_BF16 = 1 } st3_dtype;
+typedef enum { ST3_F32 = 0, ST3_BF16 = 1, ST3_E4M3 = 2 /* one byte; cache element of ST3_KV_E4M3, st3_kv_bytes only */ } st3_dtype;
 
 /* How select-and-compact rearranges a layer's cache (see st3_select_compact_layer). */
 typedef enum { ST3_STABLE = 0, ST3_HOLE_FILL = 1 } st3_compact_mode;
@@ -67,12 +67,25 @@ typedef struct {
     int64_t stride_b, stride_h, stride_t;
 } st3_tensor4;
 
-/* One layer's KV cache on the DEVICE: K and V share strides; `capacity` rows exist per (b,h). */
+/* How a cache row is stored.  ST3_KV_PLAIN: d elements of shape->dtype.  ST3_KV_E4M3 (an
+ * implementation variant of the KV cache of Sec. 4.3, not part of the paper): d bytes, each an OCP
+ * FP8 E4M3 code (bias 7, no infinities, S.1111.111 = NaN, largest finite 448); the value of an
+ * element of strip (b,h) is its code value times k_scale[b*H+h] (v_scale for V).  Rows enter such
+ * a cache through st3_quantize_rows, st3_kv_append and the fused step calls, which divide by the
+ * scale in float32, saturate at +-448 and round to nearest, ties to the even code.  Requires
+ * shape->dtype == ST3_BF16. */
+typedef enum { ST3_KV_PLAIN = 0, ST3_KV_E4M3 = 1 } st3_kv_format;
+
+/* One layer's KV cache on the DEVICE: K and V share strides (in cache elements); `capacity` rows
+ * exist per (b,h).  k_scale / v_scale: DEVICE float32 [B*H], positive, read only for ST3_KV_E4M3. */
 typedef struct {
     void*   k;
     void*   v;
     int64_t stride_b, stride_h, stride_t;
     int32_t capacity;
+    int32_t format;         /* st3_kv_format */
+    const float* k_scale;
+    const float* v_scale;
 } st3_kv_layer;
 
 /* Where the visual keys sit in a layer's cache.  For sequence b the cache holds kv_len[b] rows;
@@ -120,6 +133,15 @@ ST3_EXPORT st3_status st3_prefill_attention(const st3_attn_shape* shape, const s
                                  const st3_tensor4* v, int32_t n, int32_t sys_len, int32_t vis_len,
                                  int32_t score_window, const st3_tensor4* out, float* vis_mass,
                                  int64_t mass_stride, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Writes rows [0, n) of a [B,H,n,d] tensor of shape->dtype into rows [0, n) of a cache's K
+ * (which = 0) or V (which = 1) in the cache's own format: a copy for ST3_KV_PLAIN, the E4M3
+ * quantiser described at st3_kv_format otherwise.  Used after prefill, whose attention runs on
+ * the unquantised prompt.  n <= capacity.
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_quantize_rows(const st3_attn_shape* shape, const st3_tensor4* src, const st3_kv_layer* kv,
+                                        int32_t which, int32_t n, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * KV append (KV-cache use of Sec. 4.3): writes k_new/v_new (DEVICE, contiguous [B,H,d]) at row

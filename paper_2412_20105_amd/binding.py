@@ -20,13 +20,14 @@ ST3_ERR_INVALID_ARG = 1
 ST3_ERR_UNSUPPORTED = 2
 ST3_ERR_WORKSPACE_TOO_SMALL = 3
 ST3_ERR_HIP = 4
-ST3_F32, ST3_BF16 = 0, 1
+ST3_F32, ST3_BF16, ST3_E4M3 = 0, 1, 2
+ST3_KV_PLAIN, ST3_KV_E4M3 = 0, 1
 ST3_STABLE, ST3_HOLE_FILL = 0, 1
 ST3_ANNEAL_COS, ST3_ANNEAL_LINEAR, ST3_ANNEAL_EXP, ST3_ANNEAL_DROP, ST3_ANNEAL_NONE = 0, 1, 2, 3, 4
 
 EXPORTED = [
     "st3_status_string", "st3_last_hip_error", "st3_version", "st3_workspace_bytes", "st3_workspace_init",
-    "st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_decode_attention_inherit",
+    "st3_prefill_attention", "st3_quantize_rows", "st3_kv_append", "st3_decode_attention", "st3_decode_attention_inherit",
     "st3_select_topk",
     "st3_compact_rows", "st3_gather_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
     "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
@@ -56,7 +57,8 @@ class Tensor4(C.Structure):
 
 class KvLayer(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("stride_b", C.c_int64),
-                ("stride_h", C.c_int64), ("stride_t", C.c_int64), ("capacity", C.c_int32)]
+                ("stride_h", C.c_int64), ("stride_t", C.c_int64), ("capacity", C.c_int32), ("format", C.c_int32),
+                ("k_scale", C.c_void_p), ("v_scale", C.c_void_p)]
 
 
 class Segments(C.Structure):
@@ -104,6 +106,8 @@ def lib() -> C.CDLL:
         L.st3_prefill_attention.argtypes = [P(AttnShape), P(Tensor4), P(Tensor4), P(Tensor4), C.c_int32, C.c_int32,
                                             C.c_int32, C.c_int32, P(Tensor4), C.c_void_p, C.c_int64, C.c_void_p,
                                             C.c_size_t, C.c_void_p]
+        L.st3_quantize_rows.argtypes = [P(AttnShape), P(Tensor4), P(KvLayer), C.c_int32, C.c_int32, C.c_void_p]
+        L.st3_quantize_rows.restype = C.c_int
         L.st3_kv_append.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_void_p, C.c_void_p]
         L.st3_decode_attention.argtypes = [P(AttnShape), C.c_void_p, P(KvLayer), P(Segments), C.c_void_p, C.c_void_p,
                                            C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -129,7 +133,7 @@ def lib() -> C.CDLL:
         L.st3_schedule_anneal.argtypes = [C.c_int32, C.c_double, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
         L.st3_kv_bytes.restype = C.c_int64
         L.st3_kv_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32]
-        for name in ("st3_prefill_attention", "st3_kv_append", "st3_decode_attention", "st3_decode_attention_inherit",
+        for name in ("st3_prefill_attention", "st3_quantize_rows", "st3_kv_append", "st3_decode_attention", "st3_decode_attention_inherit",
     "st3_select_topk",
                      "st3_compact_rows", "st3_select_compact_layer", "st3_decode_layer_step",
                      "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal"):
@@ -174,12 +178,20 @@ def tensor4(t: torch.Tensor) -> Tensor4:
     return s
 
 
-def kv_layer(k: Optional[torch.Tensor], v: torch.Tensor) -> KvLayer:
-    """k is None for a layer that caches values only (lazy layer of QK heredity)."""
+def kv_layer(k: Optional[torch.Tensor], v: torch.Tensor, k_scale: Optional[torch.Tensor] = None,
+             v_scale: Optional[torch.Tensor] = None) -> KvLayer:
+    """k is None for a layer that caches values only (lazy layer of QK heredity).  uint8 tensors are
+    E4M3 caches and come with float32 scales [B, H] (k_scale may be None when k is)."""
     assert v.dim() == 4 and v.stride(3) == 1 and v.is_cuda
-    assert k is None or (k.stride() == v.stride() and k.shape == v.shape and k.is_cuda)
-    s = KvLayer(None if k is None else k.data_ptr(), v.data_ptr(), v.stride(0), v.stride(1), v.stride(2), v.shape[2])
-    s._refs = (k, v)
+    assert k is None or (k.stride() == v.stride() and k.shape == v.shape and k.is_cuda and k.dtype == v.dtype)
+    fmt = ST3_KV_E4M3 if v.dtype == torch.uint8 else ST3_KV_PLAIN
+    if fmt == ST3_KV_E4M3:
+        for sc in (k_scale, v_scale):
+            assert sc is None or (sc.dtype == torch.float32 and sc.is_contiguous() and sc.is_cuda)
+        assert v_scale is not None and (k is None or k_scale is not None)
+    s = KvLayer(None if k is None else k.data_ptr(), v.data_ptr(), v.stride(0), v.stride(1), v.stride(2), v.shape[2], fmt,
+                _ptr(k_scale) if fmt else None, _ptr(v_scale) if fmt else None)
+    s._refs = (k, v, k_scale, v_scale)
     return s
 
 
@@ -231,6 +243,11 @@ def st3_prefill_attention(shape, q, k, v, n, sys_len, vis_len, score_window, out
                                        score_window, C.byref(to), _ptr(vis_mass), ms, _ptr(workspace),
                                        0 if workspace is None else workspace.numel() * workspace.element_size(),
                                        _stream(stream)), "st3_prefill_attention")
+
+
+def st3_quantize_rows(shape, src, kv: KvLayer, which: int, n: int, stream=None):
+    _check(lib().st3_quantize_rows(C.byref(shape), C.byref(tensor4(src)), C.byref(kv), which, n, _stream(stream)),
+           "st3_quantize_rows")
 
 
 def st3_kv_append(shape, kv: KvLayer, seg: Segments, k_new, v_new, stream=None):

@@ -41,6 +41,22 @@ __device__ __forceinline__ void load_q_slice(const T* qrow, int lane, float* qf)
     ElemTraits<T>::unpack(raw, qf);
 }
 
+// This lane's slice of a [d] row of elements T when the lane map is that of cache elements KT
+// (RowMap<KT, D>::EPL elements per lane, which is more than one 16-byte vector of T when KT is
+// narrower than T), as floats.
+template <typename T, typename KT, int D>
+__device__ __forceinline__ void load_row_slice(const T* row, int lane, float* f) {
+    using M = RowMap<KT, D>;
+    constexpr int PV = ElemTraits<T>::kPerVec, NV = M::EPL / PV;
+    static_assert(M::EPL % PV == 0, "a lane's slice is a whole number of 16-byte vectors");
+    const T* p = row + (lane % M::LPR) * M::EPL;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(p + i * PV);
+        ElemTraits<T>::unpack(raw, f + i * PV);
+    }
+}
+
 // Online-softmax state of one wave.  `l` holds, per lane, the sum of probabilities over the rows
 // of that lane's row-group only; `acc` likewise.  finish_wave() folds the row-groups together.
 template <int EPL>

@@ -25,7 +25,11 @@ inline st3_status check_launch() {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-inline int elem_bytes(int dtype) { return dtype == ST3_BF16 ? 2 : 4; }
+inline int elem_bytes(int dtype) { return dtype == ST3_BF16 ? 2 : dtype == ST3_E4M3 ? 1 : 4; }
+// bytes of one cache element of a layer
+inline int kv_elem_bytes(const st3_attn_shape* s, const st3_kv_layer* kv) {
+    return kv->format == ST3_KV_E4M3 ? 1 : elem_bytes(s->dtype);
+}
 
 // Validates what every attention entry point needs from `shape`.
 inline st3_status check_shape(const st3_attn_shape* s) {
@@ -155,7 +159,50 @@ template <> struct ElemTraits<bf16_t> {
     }
 };
 
-// Sum over aligned groups of G consecutive lanes (G in {8,16,32}); every lane of a group ends
+// One byte per element: OCP FP8 E4M3 code.  The hardware conversion used by unpack() was checked
+// against the format's definition for all 256 codes (bias 7, subnormals, S.1111.111 = NaN, 448
+// largest) and takes the bytes of a word from low to high.
+struct e4m3_t { uint8_t bits; };
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+template <> struct ElemTraits<e4m3_t> {
+    static constexpr int kBytes = 1;
+    static constexpr int kPerVec = 16;
+    __device__ static __forceinline__ void unpack(const uint4& r, float* f) {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f32x2_t lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
+            const f32x2_t hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
+            f[4 * i] = lo.x; f[4 * i + 1] = lo.y; f[4 * i + 2] = hi.x; f[4 * i + 3] = hi.y;
+        }
+    }
+};
+
+// float32 -> E4M3 code: saturate at +-448, round to nearest, ties to the even code, sign kept
+// (also of zero), NaN -> 0x7F.  Written out in integer arithmetic so that the result does not
+// depend on a conversion instruction's mode bits.
+__device__ __forceinline__ uint32_t f32_to_e4m3(float t) {
+    const uint32_t u = __float_as_uint(t);
+    const uint32_t sign = (u >> 24) & 0x80u;
+    const uint32_t a = u & 0x7fffffffu;
+    if (a > 0x7f800000u) return 0x7fu;                      // NaN
+    if (a >= 0x43e00000u) return sign | 0x7eu;              // |t| >= 448 (infinity included)
+    if (a < 0x3c800000u) {                                  // |t| < 2^-6: multiples of 2^-9, code = the multiple
+        const float m = rintf(__uint_as_float(a) * 512.0f); // exact product, round half to even; 8 carries into 2^-6
+        return sign | (uint32_t)m;
+    }
+    const uint32_t e = (a >> 23) - 127u + 7u;               // 1 .. 15
+    const uint32_t mant = a & 0x7fffffu;
+    uint32_t code = (e << 3) | (mant >> 20);
+    const uint32_t rem = mant & 0xfffffu;
+    code += (rem > 0x80000u || (rem == 0x80000u && (code & 1u))) ? 1u : 0u;     // carry runs into the exponent
+    return sign | code;
+}
+
+// x / scale as the quantiser defines it: one correctly rounded float32 division.
+__device__ __forceinline__ uint32_t quantize_e4m3(float x, float scale) { return f32_to_e4m3(__fdiv_rn(x, scale)); }
+
+// Sum over aligned groups of G consecutive lanes (G in {4,8,16,32}); every lane of a group ends
 // with the group's total.  Steps below 16 lanes use DPP row operations; they rely on all lanes
 // of the already-reduced sub-group holding the same value, so a mirror acts as the XOR step.
 template <int G>
@@ -163,8 +210,8 @@ __device__ __forceinline__ float group_sum(float v) {
     // xor 1, xor 2 inside a quad
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
-    // row_half_mirror: lane i <-> 7-i within 8 lanes
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
+    if (G >= 8)   // row_half_mirror: lane i <-> 7-i within 8 lanes
+        v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
     if (G >= 16)  // row_mirror: lane i <-> 15-i within 16 lanes
         v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
     if (G >= 32) v += __shfl_xor(v, 16);

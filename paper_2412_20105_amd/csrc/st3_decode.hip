@@ -57,6 +57,8 @@ struct DecodeArgs {
     int32_t defer;          // 1: the mass of this call is finished later; mark it pending
     int32_t keep_all_logits;  // 1: keep the logit of every key (a lazy layer will ask for them), else visual only
     float scale_l2;
+    const float* k_scale;   // [B*H] value of one K code unit (E4M3 caches; null: 1)
+    const float* v_scale;   // [B*H] likewise for V
     float* part_o;          // [B,H,nsplit_cap,D]   (nsplit > 1 only)
     float* part_ml;         // [B,H,nsplit_cap,2]
     float* logits;          // [B,H,capacity]; null when no mass is wanted
@@ -72,30 +74,57 @@ __device__ __forceinline__ void store_out(void* out, int64_t idx, float o) {
     else reinterpret_cast<uint16_t*>(out)[idx] = (uint16_t)f32_to_bf16_bits(o);
 }
 
-// grid (nsplit, H, B)
-template <typename T, int D, int U>
+// This lane's 16-byte slice of a new token's row, in the format of the cache it is going into
+// (lane map of RowMap<KT, D>): a plain copy when the cache holds elements of T, the E4M3 quantiser
+// otherwise.  What the attention then reads is exactly what later steps will find in the cache.
+template <typename T, typename KT, int D>
+struct NewRow {
+    static __device__ __forceinline__ u32x4_t load(const T* row, int lane, float) {
+        using M = RowMap<KT, D>;
+        return *reinterpret_cast<const u32x4_t*>(row + (lane % M::LPR) * M::EPL);
+    }
+};
+template <typename T, int D>
+struct NewRow<T, e4m3_t, D> {
+    static __device__ __forceinline__ u32x4_t load(const T* row, int lane, float scale) {
+        float f[16];
+        load_row_slice<T, e4m3_t, D>(row, lane, f);
+        u32x4_t r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            r[i] = quantize_e4m3(f[4 * i], scale) | (quantize_e4m3(f[4 * i + 1], scale) << 8) |
+                   (quantize_e4m3(f[4 * i + 2], scale) << 16) | (quantize_e4m3(f[4 * i + 3], scale) << 24);
+        return r;
+    }
+};
+
+// grid (nsplit, H, B).  T: element type of q, k_new, v_new and out; KT: element type of the cache.
+template <typename T, typename KT, int D, int U>
 __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS)
 __attribute__((amdgpu_waves_per_eu(ST3_DECODE_MIN_BLOCKS, ST3_DECODE_MIN_BLOCKS)))    // do not spill to reach a third wave
 void decode_attend_kernel(DecodeArgs a) {
-    using M = RowMap<T, D>;
+    using M = RowMap<KT, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, TILE = U * M::RPL;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int c0 = split * a.chunk;
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int64_t bh = (int64_t)b * a.H + h;
     const T* qrow = reinterpret_cast<const T*>(a.q) + bh * D;
-    T* kbase = reinterpret_cast<T*>(a.k) + b * a.stride_b + h * a.stride_h;
-    T* vbase = reinterpret_cast<T*>(a.v) + b * a.stride_b + h * a.stride_h;
+    KT* kbase = reinterpret_cast<KT*>(a.k) + b * a.stride_b + h * a.stride_h;
+    KT* vbase = reinterpret_cast<KT*>(a.v) + b * a.stride_b + h * a.stride_h;
 #if ST3_DECODE_PIPELINED
     // The first tile's loads go out before the sequence length has arrived: the host bound keeps
     // them inside the strip (rows the length later rules out are masked when the tile is consumed).
     // Takes one dependent memory round trip off the front of every workgroup.
     uint4 kr[U], vr[U];
-    issue_tile<T, D, U, true>(kbase, vbase, a.stride_t, c0 + wave * TILE,
+    issue_tile<KT, D, U, true>(kbase, vbase, a.stride_t, c0 + wave * TILE,
                               min(c0 + a.chunk, a.max_kv - (a.k_new != nullptr ? 1 : 0)), c0, lane, kr, vr);
 #endif
     float qf[EPL];
-    load_q_slice<T, D>(qrow, lane, qf);
+    load_row_slice<T, KT, D>(qrow, lane, qf);
+    // a code unit of K is worth k_scale: folded into the logit scale; V's goes onto the output
+    const float k_unit = a.k_scale ? a.k_scale[bh] : 1.0f, v_unit = a.v_scale ? a.v_scale[bh] : 1.0f;
+    const float scale_l2 = a.scale_l2 * k_unit;
     // the row being appended sits at index kv_len[b]; never trust a device length past the host bound
     const int len = min(a.kv_len[b] + (a.k_new != nullptr ? 1 : 0), a.max_kv);
     if (split == 0 && h == 0 && tid == 0 && a.pending != nullptr) {
@@ -129,9 +158,8 @@ void decode_attend_kernel(DecodeArgs a) {
     // the appended token's row is fetched now and used after the cached rows: off the critical path
     u32x4_t kn_raw = {0, 0, 0, 0}, vn_raw = {0, 0, 0, 0};       // native vectors: the uint4 class would live in scratch
     if (has_new && wave == 0) {
-        const int64_t col = bh * D + (lane % LPR) * EPL;
-        kn_raw = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const T*>(a.k_new) + col);
-        vn_raw = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const T*>(a.v_new) + col);
+        kn_raw = NewRow<T, KT, D>::load(reinterpret_cast<const T*>(a.k_new) + bh * D, lane, k_unit);
+        vn_raw = NewRow<T, KT, D>::load(reinterpret_cast<const T*>(a.v_new) + bh * D, lane, v_unit);
     }
     // waves take the tiles of the chunk round-robin, so all four stay busy to the end
 #if ST3_DECODE_PIPELINED
@@ -140,22 +168,22 @@ void decode_attend_kernel(DecodeArgs a) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (c0 + wave * TILE + u * M::RPL + lane / LPR >= c1_cached) vr[u] = make_uint4(0, 0, 0, 0);
-    wave_attend_primed<T, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
-                                      c0, a.scale_l2, lane, st, lg, vis_lo, vis_hi, kr, vr);
+    wave_attend_primed<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
+                                       c0, scale_l2, lane, st, lg, vis_lo, vis_hi, kr, vr);
 #else
-    wave_attend<T, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0,
-                         a.scale_l2, lane, st, lg, vis_lo, vis_hi);
+    wave_attend<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0,
+                          scale_l2, lane, st, lg, vis_lo, vis_hi);
 #endif
     if (has_new && wave == 0) {
-        wave_attend_row<T, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
-                              make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, a.scale_l2, lane, st, lg, vis_lo,
+        wave_attend_row<KT, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
+                               make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, scale_l2, lane, st, lg, vis_lo,
                               vis_hi);
         if (lane < 2 * LPR) {                       // store the row into the cache: lanes [0,LPR) K, [LPR,2*LPR) V
-            T* dst = (lane < LPR ? kbase : vbase) + (int64_t)(len - 1) * a.stride_t + (lane % LPR) * EPL;
+            KT* dst = (lane < LPR ? kbase : vbase) + (int64_t)(len - 1) * a.stride_t + (lane % LPR) * EPL;
             *reinterpret_cast<u32x4_t*>(dst) = lane < LPR ? kn_raw : vn_raw;
         }
     }
-    finish_wave<T, D>(st);
+    finish_wave<KT, D>(st);
 
     __shared__ float sm_acc[kDecodeWaves][D];
     __shared__ float sm_m[kDecodeWaves], sm_l[kDecodeWaves];
@@ -177,8 +205,8 @@ void decode_attend_kernel(DecodeArgs a) {
             l = fmaf(sm_l[w], f, l);
         }
         const int64_t slot = bh * a.nsplit_cap + split;
-        if (a.nsplit == 1) store_out<T>(a.out, bh * D + tid, o / l);
-        else a.part_o[slot * D + tid] = o;
+        if (a.nsplit == 1) store_out<T>(a.out, bh * D + tid, o / l * v_unit);
+        else a.part_o[slot * D + tid] = o * v_unit;
         if (tid == 0) { a.part_ml[slot * 2] = m; a.part_ml[slot * 2 + 1] = l; }
     }
 }
@@ -199,6 +227,7 @@ struct InheritArgs {
     int32_t src_capacity, src_nsplit_cap;
     float* part_o;              // [B,H,nsplit_cap,D]   (nsplit > 1 only)
     const void* v_new;          // [B,H,D] value row of the token being appended (null: none)
+    const float* v_scale;       // [B*H] value of one V code unit (E4M3 caches; null: 1)
     void* out;
 };
 
@@ -249,9 +278,9 @@ __device__ __forceinline__ void wave_inherit(const T* vbase, int64_t stride_t, i
 }
 
 // grid (nsplit, H, B)
-template <typename T, int D, int U>
+template <typename T, typename KT, int D, int U>
 __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_inherit_kernel(InheritArgs a) {
-    using M = RowMap<T, D>;
+    using M = RowMap<KT, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, TILE = U * M::RPL;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int len = min(a.kv_len[b] + (a.v_new != nullptr ? 1 : 0), a.max_kv);
@@ -277,23 +306,23 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
     for (int s = 0; s < s_ns; ++s) l = fmaf(ml[2 * s + 1], exp2_fast(ml[2 * s] - m), l);
     const float rl = 1.0f / l;
 
-    T* vbase = reinterpret_cast<T*>(a.v) + b * a.stride_b + h * a.stride_h;
+    KT* vbase = reinterpret_cast<KT*>(a.v) + b * a.stride_b + h * a.stride_h;
     const float* lg = a.src_logits + bh * a.src_capacity;
+    const float v_unit = a.v_scale ? a.v_scale[bh] : 1.0f;
     float acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
     const bool has_new = a.v_new != nullptr && c1 == len;
     const int c1_cached = has_new ? c1 - 1 : c1;
-    wave_inherit<T, D, U>(vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0, lg, m, rl, lane, acc);
+    wave_inherit<KT, D, U>(vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0, lg, m, rl, lane, acc);
     if (has_new && wave == 0 && lane < LPR) {
-        const T* vn = reinterpret_cast<const T*>(a.v_new) + bh * D + lane * EPL;
-        const uint4 raw = *reinterpret_cast<const uint4*>(vn);
+        const u32x4_t raw = NewRow<T, KT, D>::load(reinterpret_cast<const T*>(a.v_new) + bh * D, lane, v_unit);
         const float p = exp2_fast(lg[len - 1] - m) * rl;
         float vf[EPL];
-        ElemTraits<T>::unpack(raw, vf);
+        ElemTraits<KT>::unpack(make_uint4(raw.x, raw.y, raw.z, raw.w), vf);
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
-        *reinterpret_cast<uint4*>(vbase + (int64_t)(len - 1) * a.stride_t + lane * EPL) = raw;
+        *reinterpret_cast<u32x4_t*>(vbase + (int64_t)(len - 1) * a.stride_t + lane * EPL) = raw;
     }
 #pragma unroll
     for (int off = LPR; off < kWave; off <<= 1) {
@@ -310,8 +339,8 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
         float o = 0.f;
 #pragma unroll
         for (int w = 0; w < kDecodeWaves; ++w) o += sm_acc[w][tid];
-        if (a.nsplit == 1) store_out<T>(a.out, bh * D + tid, o);
-        else a.part_o[(bh * a.nsplit_cap + split) * D + tid] = o;
+        if (a.nsplit == 1) store_out<T>(a.out, bh * D + tid, o * v_unit);
+        else a.part_o[(bh * a.nsplit_cap + split) * D + tid] = o * v_unit;
     }
 }
 
@@ -375,23 +404,51 @@ struct AppendArgs {
     const void* k_new;
     const void* v_new;
     const int32_t* kv_len;
+    const float* k_scale;
+    const float* v_scale;
     int32_t H, capacity;
 };
 
-// grid (H, B), 64 threads: lanes [0, LPR) copy the K row, lanes [LPR, 2*LPR) the V row.
-template <typename T, int D>
+// grid (H, B), 64 threads: lanes [0, LPR) write the K row, lanes [LPR, 2*LPR) the V row.
+template <typename T, typename KT, int D>
 __global__ __launch_bounds__(64) void append_kernel(AppendArgs a) {
-    using M = RowMap<T, D>;
+    using M = RowMap<KT, D>;
     const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
     const int row = a.kv_len[b];
     if (row < 0 || row >= a.capacity || lane >= 2 * M::LPR) return;
     const bool is_v = lane >= M::LPR;
     if (!is_v && a.k == nullptr) return;                // a layer that caches V only
-    const int c = (lane % M::LPR) * M::EPL;
     const int64_t bh = (int64_t)b * a.H + h;
-    const T* src = reinterpret_cast<const T*>(is_v ? a.v_new : a.k_new) + bh * D + c;
-    T* dst = reinterpret_cast<T*>(is_v ? a.v : a.k) + b * a.stride_b + h * a.stride_h + row * a.stride_t + c;
-    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+    const float* sc = is_v ? a.v_scale : a.k_scale;
+    const T* src = reinterpret_cast<const T*>(is_v ? a.v_new : a.k_new) + bh * D;
+    const u32x4_t raw = NewRow<T, KT, D>::load(src, lane % M::LPR, sc ? sc[bh] : 1.0f);
+    KT* dst = reinterpret_cast<KT*>(is_v ? a.v : a.k) + b * a.stride_b + h * a.stride_h + row * a.stride_t +
+              (lane % M::LPR) * M::EPL;
+    *reinterpret_cast<u32x4_t*>(dst) = raw;
+}
+
+// Rows [0, n) of a [B,H,n,D] tensor of T into rows [0, n) of one half of a cache, in its format.
+struct QuantArgs {
+    const void* src;
+    int64_t s_sb, s_sh, s_st;       // elements of T
+    void* dst;
+    int64_t d_sb, d_sh, d_st;       // cache elements
+    const float* scale;             // [B*H] or null
+    int32_t H, n;
+};
+
+// grid (ceil(n / rows per block), H, B), 256 threads: LPR lanes per row.
+template <typename T, typename KT, int D>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(QuantArgs a) {
+    using M = RowMap<KT, D>;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int row = blockIdx.x * (256 / M::LPR) + threadIdx.x / M::LPR;
+    if (row >= a.n) return;
+    const int64_t bh = (int64_t)b * a.H + h;
+    const T* src = reinterpret_cast<const T*>(a.src) + b * a.s_sb + h * a.s_sh + row * a.s_st;
+    const u32x4_t raw = NewRow<T, KT, D>::load(src, threadIdx.x % M::LPR, a.scale ? a.scale[bh] : 1.0f);
+    KT* dst = reinterpret_cast<KT*>(a.dst) + b * a.d_sb + h * a.d_sh + row * a.d_st + (threadIdx.x % M::LPR) * M::EPL;
+    *reinterpret_cast<u32x4_t*>(dst) = raw;
 }
 
 __global__ void bump_len_kernel(int32_t* kv_len, int32_t B, int32_t capacity) {
@@ -399,20 +456,20 @@ __global__ void bump_len_kernel(int32_t* kv_len, int32_t B, int32_t capacity) {
     if (b < B && kv_len[b] >= 0 && kv_len[b] < capacity) kv_len[b] += 1;
 }
 
-template <typename T, int D>
+template <typename T, typename KT, int D>
 void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
     const dim3 grid(da.nsplit, da.H, B);
     hipEvent_t e0, e1;
     if (profile_take(&e0, &e1))     // timed launch: the events receive the kernel's own start and end
-        hipExtLaunchKernelGGL((decode_attend_kernel<T, D, ST3_DECODE_U>), grid, dim3(kDecodeThreads), 0, st, e0, e1, 0,
+        hipExtLaunchKernelGGL((decode_attend_kernel<T, KT, D, ST3_DECODE_U>), grid, dim3(kDecodeThreads), 0, st, e0, e1, 0,
                               da);
     else
-        decode_attend_kernel<T, D, ST3_DECODE_U><<<grid, kDecodeThreads, 0, st>>>(da);
+        decode_attend_kernel<T, KT, D, ST3_DECODE_U><<<grid, kDecodeThreads, 0, st>>>(da);
 }
 
-template <typename T, int D>
+template <typename T, typename KT, int D>
 void launch_inherit(const InheritArgs& ia, int B, hipStream_t st) {
-    decode_inherit_kernel<T, D, 2 * ST3_DECODE_U><<<dim3(ia.nsplit, ia.H, B), kDecodeThreads, 0, st>>>(ia);
+    decode_inherit_kernel<T, KT, D, 2 * ST3_DECODE_U><<<dim3(ia.nsplit, ia.H, B), kDecodeThreads, 0, st>>>(ia);
 }
 
 template <typename T, int D>
@@ -421,11 +478,34 @@ void launch_finish(const FinishArgs& fa, int B, hipStream_t st) {
     if (blocks > 0) decode_finish_kernel<T, D><<<dim3(blocks, B), 256, 0, st>>>(fa);
 }
 
-template <typename T, int D>
+template <typename T, typename KT, int D>
 void launch_append(const AppendArgs& aa, int B, int32_t* kv_len, hipStream_t st) {
-    append_kernel<T, D><<<dim3(aa.H, B), 64, 0, st>>>(aa);
+    append_kernel<T, KT, D><<<dim3(aa.H, B), 64, 0, st>>>(aa);
     bump_len_kernel<<<(B + 255) / 256, 256, 0, st>>>(kv_len, B, aa.capacity);
 }
+
+template <typename T, typename KT, int D>
+void launch_quantize(const QuantArgs& qa, int B, hipStream_t st) {
+    using M = RowMap<KT, D>;
+    const int rpb = 256 / M::LPR;
+    quantize_rows_kernel<T, KT, D><<<dim3((qa.n + rpb - 1) / rpb, qa.H, B), 256, 0, st>>>(qa);
+}
+
+// Launchers that depend on the cache element type: KT = T for plain caches, e4m3_t (bf16 I/O only,
+// checked on the host) for E4M3 caches.
+#define ST3_DISPATCH_KV(fn, shape, kv, ...)                                                                    \
+    do {                                                                                                       \
+        if ((kv)->format == ST3_KV_E4M3) {                                                                     \
+            if ((shape)->head_dim == 128) fn<bf16_t, e4m3_t, 128>(__VA_ARGS__);                                \
+            else fn<bf16_t, e4m3_t, 64>(__VA_ARGS__);                                                          \
+        } else if ((shape)->dtype == ST3_BF16) {                                                               \
+            if ((shape)->head_dim == 128) fn<bf16_t, bf16_t, 128>(__VA_ARGS__);                                \
+            else fn<bf16_t, bf16_t, 64>(__VA_ARGS__);                                                          \
+        } else {                                                                                               \
+            if ((shape)->head_dim == 128) fn<float, float, 128>(__VA_ARGS__);                                  \
+            else fn<float, float, 64>(__VA_ARGS__);                                                            \
+        }                                                                                                      \
+    } while (0)
 
 #define ST3_DISPATCH(fn, shape, ...)                                                                   \
     do {                                                                                               \
@@ -443,7 +523,12 @@ st3_status check_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_s
     if (seg->max_kv_len > kv->capacity) return ST3_ERR_INVALID_ARG;
     if (seg->sys_len + seg->max_vis_len > kv->capacity) return ST3_ERR_INVALID_ARG;
     if (kv->stride_t < s->head_dim || kv->stride_h < 0 || kv->stride_b < 0) return ST3_ERR_INVALID_ARG;
-    const int eb = elem_bytes(s->dtype);
+    if (kv->format != ST3_KV_PLAIN && kv->format != ST3_KV_E4M3) return ST3_ERR_INVALID_ARG;
+    if (kv->format == ST3_KV_E4M3) {
+        if (s->dtype != ST3_BF16) return ST3_ERR_UNSUPPORTED;
+        if ((kv->k && !kv->k_scale) || !kv->v_scale) return ST3_ERR_INVALID_ARG;
+    }
+    const int eb = kv_elem_bytes(s, kv);
     if ((kv->k && !aligned16(kv->k)) || !aligned16(kv->v)) return ST3_ERR_INVALID_ARG;
     if ((kv->stride_t * eb) % 16 || (kv->stride_h * eb) % 16 || (kv->stride_b * eb) % 16)
         return ST3_ERR_INVALID_ARG;
@@ -475,6 +560,7 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     da.chunk = decode_chunk(max_kv_len, da.nsplit);
     da.capacity = kv->capacity;
     da.scale_l2 = scale_log2(shape);
+    if (kv->format == ST3_KV_E4M3) { da.k_scale = kv->k_scale; da.v_scale = kv->v_scale; }
     da.part_o = reinterpret_cast<float*>(ws + wl.part_o);
     da.part_ml = reinterpret_cast<float*>(ws + wl.part_ml);
     da.logits = (want_mass || keep_all_logits) ? reinterpret_cast<float*>(ws + wl.logits) : nullptr;
@@ -483,7 +569,7 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     da.k_new = k_new; da.v_new = v_new;
     da.out = out;
     da.defer = (want_mass && defer_mass) ? 1 : 0;
-    ST3_DISPATCH(launch_attend, shape, da, B, st);
+    ST3_DISPATCH_KV(launch_attend, shape, kv, da, B, st);
     const bool mass_now = want_mass && !defer_mass;
     if (da.nsplit > 1 || mass_now) {
         FinishArgs fa{};
@@ -506,7 +592,8 @@ st3_status enqueue_append(const st3_attn_shape* shape, const st3_kv_layer* kv, c
     aa.k = kv->k; aa.v = kv->v;
     aa.stride_b = kv->stride_b; aa.stride_h = kv->stride_h; aa.stride_t = kv->stride_t;
     aa.k_new = k_new; aa.v_new = v_new; aa.kv_len = seg->kv_len; aa.H = H; aa.capacity = kv->capacity;
-    ST3_DISPATCH(launch_append, shape, aa, B, seg->kv_len, st);
+    if (kv->format == ST3_KV_E4M3) { aa.k_scale = kv->k_scale; aa.v_scale = kv->v_scale; }
+    ST3_DISPATCH_KV(launch_append, shape, kv, aa, B, seg->kv_len, st);
     return check_launch();
 }
 
@@ -545,7 +632,8 @@ st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, 
     ia.src_capacity = src_capacity; ia.src_nsplit_cap = sl.nsplit_cap;
     ia.part_o = reinterpret_cast<float*>(ws + wl.part_o);
     ia.v_new = v_new; ia.out = out;
-    ST3_DISPATCH(launch_inherit, shape, ia, B, st);
+    if (kv->format == ST3_KV_E4M3) ia.v_scale = kv->v_scale;
+    ST3_DISPATCH_KV(launch_inherit, shape, kv, ia, B, st);
     if (ia.nsplit > 1) {
         FinishArgs fa{};
         fa.part_o = ia.part_o; fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len;
@@ -588,6 +676,31 @@ extern "C" st3_status st3_decode_attention_inherit(const st3_attn_shape* shape, 
     return st3::enqueue_inherit(shape, kv, seg, seg->max_kv_len, nullptr, src_workspace, src_workspace_bytes,
                                 src_kv_capacity, out, workspace, workspace_bytes,
                                 reinterpret_cast<hipStream_t>(stream));
+}
+
+extern "C" st3_status st3_quantize_rows(const st3_attn_shape* shape, const st3_tensor4* src, const st3_kv_layer* kv,
+                                        int32_t which, int32_t n, void* stream) {
+    using namespace st3;
+    st3_status s = check_shape(shape);
+    if (s != ST3_OK) return s;
+    if (!src || !src->data || !kv || (which != 0 && which != 1) || n < 0) return ST3_ERR_INVALID_ARG;
+    if (kv->format != ST3_KV_PLAIN && kv->format != ST3_KV_E4M3) return ST3_ERR_INVALID_ARG;
+    if (kv->format == ST3_KV_E4M3 && shape->dtype != ST3_BF16) return ST3_ERR_UNSUPPORTED;
+    void* dst = which == 0 ? kv->k : kv->v;
+    const float* scale = kv->format == ST3_KV_E4M3 ? (which == 0 ? kv->k_scale : kv->v_scale) : nullptr;
+    if (!dst || (kv->format == ST3_KV_E4M3 && !scale) || n > kv->capacity) return ST3_ERR_INVALID_ARG;
+    const int eb = elem_bytes(shape->dtype), ceb = kv_elem_bytes(shape, kv);
+    if (!aligned16(src->data) || !aligned16(dst)) return ST3_ERR_INVALID_ARG;
+    if ((src->stride_t * eb) % 16 || (src->stride_h * eb) % 16 || (src->stride_b * eb) % 16) return ST3_ERR_INVALID_ARG;
+    if ((kv->stride_t * ceb) % 16 || (kv->stride_h * ceb) % 16 || (kv->stride_b * ceb) % 16) return ST3_ERR_INVALID_ARG;
+    if (src->stride_t < shape->head_dim || kv->stride_t < shape->head_dim) return ST3_ERR_INVALID_ARG;
+    if (n == 0) return ST3_OK;
+    QuantArgs qa{};
+    qa.src = src->data; qa.s_sb = src->stride_b; qa.s_sh = src->stride_h; qa.s_st = src->stride_t;
+    qa.dst = dst; qa.d_sb = kv->stride_b; qa.d_sh = kv->stride_h; qa.d_st = kv->stride_t;
+    qa.scale = scale; qa.H = shape->heads; qa.n = n;
+    ST3_DISPATCH_KV(launch_quantize, shape, kv, qa, shape->batch, reinterpret_cast<hipStream_t>(stream));
+    return check_launch();
 }
 
 extern "C" st3_status st3_kv_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,

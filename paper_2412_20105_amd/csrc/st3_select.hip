@@ -259,7 +259,7 @@ st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv,
     const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
     if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
     char* ws = reinterpret_cast<char*>(workspace);
-    const int eb = elem_bytes(shape->dtype);
+    const int eb = kv_elem_bytes(shape, kv);
     const bool evicting = keep_count >= 0 && keep_count < seg->max_vis_len;
     ea = EvictArgs{};
     ea.score_col = score_col; ea.id_col = id_col; ea.col_stride = col_stride;

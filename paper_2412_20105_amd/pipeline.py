@@ -37,16 +37,22 @@ def keep_table_for(workload) -> List[List[int]]:
 
 
 class LayerCache:
-    def __init__(self, B, H, d, cap, cap_v, dtype, device, ws_bytes, value_only=False):
-        # a lazy layer (QK heredity) never forms K, so it caches V alone
-        self.k = None if value_only else torch.empty((B, H, cap, d), dtype=dtype, device=device)
-        self.v = torch.empty((B, H, cap, d), dtype=dtype, device=device)
+    def __init__(self, B, H, d, cap, cap_v, dtype, device, ws_bytes, value_only=False, kv_scale=None):
+        # a lazy layer (QK heredity) never forms K, so it caches V alone.
+        # kv_scale: None = rows of `dtype`; a float = E4M3 codes worth that much per unit, every strip
+        cdt = dtype if kv_scale is None else torch.uint8
+        self.k = None if value_only else torch.empty((B, H, cap, d), dtype=cdt, device=device)
+        self.v = torch.empty((B, H, cap, d), dtype=cdt, device=device)
+        self.k_scale = self.v_scale = None
+        if kv_scale is not None:
+            self.k_scale = None if value_only else torch.full((B, H), kv_scale, dtype=torch.float32, device=device)
+            self.v_scale = torch.full((B, H), kv_scale, dtype=torch.float32, device=device)
         self.score = torch.zeros((B, max(cap_v, 1)), dtype=torch.float32, device=device)
         self.ids = torch.zeros((B, max(cap_v, 1)), dtype=torch.int32, device=device)
         self.mass = torch.zeros((B, max(cap_v, 1)), dtype=torch.float32, device=device)
         self.vis_len = torch.zeros((B,), dtype=torch.int32, device=device)
         self.kv_len = torch.zeros((B,), dtype=torch.int32, device=device)
-        self.kv = st3.kv_layer(self.k, self.v)
+        self.kv = st3.kv_layer(self.k, self.v, self.k_scale, self.v_scale)
         # a workspace of its own: the attention leaves its logits here for the mass and for lazy layers
         self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
         # host-side bounds (exact here, since every sequence follows the same table)
@@ -62,12 +68,14 @@ class Generation:
     lazy: {l: src} - QK heredity (Eq. 6, Alg. 2): layer l applies the attention probabilities of
     source layer src to its own values, at prefill and at every decode step.  Lazy layers follow
     their source directly and share its row of the keep table; their Q and K inputs are ignored.
+    kv_scale: None keeps the caches in `dtype`; a float makes them FP8 E4M3 (bf16 only) with that
+    scale for every (b, h) strip of K and of V - the caller's calibration, e.g. 6 sigma / 448.
     """
 
     def __init__(self, layers: int, heads: int, head_dim: int, dtype: torch.dtype, batch: int,
                  n_sys: int, n_vis: int, n_txt: int, steps: int, keep: Sequence[Sequence[int]],
                  window: int = 1, mode: str = "static", compact_mode: int = st3.ST3_HOLE_FILL,
-                 device: str = "cuda:0", lazy: Optional[Dict[int, int]] = None):
+                 device: str = "cuda:0", lazy: Optional[Dict[int, int]] = None, kv_scale: Optional[float] = None):
         self.L, self.H, self.d, self.B = layers, heads, head_dim, batch
         self.n_sys, self.n_vis, self.n_txt, self.T = n_sys, n_vis, n_txt, steps
         self.keep = [list(r) for r in keep]
@@ -89,9 +97,16 @@ class Generation:
             cap = max(cap, self.N0)                 # the unpruned prompt is staged in the cache first
             ws_bytes = st3.st3_workspace_bytes(self.shape, cap, n_vis, window)
             self.layers.append(LayerCache(batch, heads, head_dim, cap, n_vis, dtype, device, ws_bytes,
-                                          value_only=l in self.lazy))
+                                          value_only=l in self.lazy, kv_scale=kv_scale))
             st3.st3_workspace_init(self.shape, cap, self.layers[-1].ws)
+        self.kv_scale = kv_scale
         self.q_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
+        # an E4M3 cache cannot serve as the prefill's K/V input: the prompt is attended unquantised
+        # from staging buffers and its rows enter the cache through the quantiser afterwards
+        self.k_stage = self.v_stage = None
+        if kv_scale is not None:
+            self.k_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
+            self.v_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
         self.out_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
         self.dec_out = torch.empty((batch, heads, head_dim), dtype=dtype, device=device)
         self.dec_out_all = torch.empty((layers, batch, heads, head_dim), dtype=dtype, device=device)
@@ -136,18 +151,25 @@ class Generation:
         n_l = ns + alive + nx
         # stage the layer's inputs, K and V straight into the cache and Q into scratch, in ONE gather
         # launch (Alg. 1/3: X = [S, V[T], I]; ids are the ascending original positions of the survivors)
+        fp8 = self.kv_scale is not None
+        k_dst, v_dst = (self.k_stage, self.v_stage) if fp8 else (lc.k, lc.v)
         if src is None:
-            pairs = [(Q, self.q_stage), (K, lc.k), (V, lc.v)]
-            k_rows = lc.k
+            pairs = [(Q, self.q_stage), (K, k_dst), (V, v_dst)]
+            k_rows = k_dst
         else:
             # Self-attn(Q^src, K^src, V^l): the source's compacted queries are still staged (only
-            # lazy layers came in between) and its keys are the first n_l rows of its cache
-            pairs = [(V, lc.v)]
-            k_rows = self.layers[src].k
+            # lazy layers came in between) and its keys are the first n_l rows of its cache (of the
+            # key staging buffer when the caches are E4M3)
+            pairs = [(V, v_dst)]
+            k_rows = self.k_stage if fp8 else self.layers[src].k
         st3.st3_gather_rows(pairs, ns, lc.ids if alive < nv else None, alive, nv, nx)
         out = self.out_stage[:, :, :n_l]
-        st3.st3_prefill_attention(self.shape, self.q_stage[:, :, :n_l], k_rows[:, :, :n_l], lc.v[:, :, :n_l],
+        st3.st3_prefill_attention(self.shape, self.q_stage[:, :, :n_l], k_rows[:, :, :n_l], v_dst[:, :, :n_l],
                                   n_l, ns, alive, self.window, out, lc.mass, lc.ws)
+        if fp8:
+            if src is None:
+                st3.st3_quantize_rows(self.shape, self.k_stage, lc.kv, 0, n_l)
+            st3.st3_quantize_rows(self.shape, self.v_stage, lc.kv, 1, n_l)
         # ranking column: scores of the most recent prune event, else the layer's own mass
         lc.score.copy_(lc.mass if self._inherit is None else self._inherit)
         lc.vis_len.fill_(alive)
@@ -242,7 +264,8 @@ class Generation:
         lens = self.kv_lens()
         full = [n for l, n in enumerate(lens) if l not in self.lazy]
         half = [n for l, n in enumerate(lens) if l in self.lazy]          # V only
-        total = st3.st3_kv_bytes(self.B, self.H, self.d, self.shape.dtype, full)
+        edt = self.shape.dtype if self.kv_scale is None else st3.ST3_E4M3
+        total = st3.st3_kv_bytes(self.B, self.H, self.d, edt, full)
         if half:
-            total += st3.st3_kv_bytes(self.B, self.H, self.d, self.shape.dtype, half) // 2
+            total += st3.st3_kv_bytes(self.B, self.H, self.d, edt, half) // 2
         return total

@@ -393,6 +393,98 @@ def test_decode_attention_inherit(dtype, D, B, H, lens, ns, nv, cap_extra):
 
 
 # ---------------------------------------------------------------------------
+# FP8 E4M3 KV cache (implementation variant of the cache, not from the paper)
+# ---------------------------------------------------------------------------
+def _e4m3_adversarial(rng, shape, scale):
+    """bf16-exact inputs that land on E4M3 values, on the midpoints between them (ties), just beside
+    the midpoints, in the subnormal range, beyond +-448, plus ordinary random values."""
+    table = orc.e4m3_decode(np.arange(0x7F, dtype=np.uint8))
+    mids = (table[:-1] + table[1:]) / 2                       # 4 significant bits: exact in bf16
+    pool = np.concatenate([table, mids, mids * (1 + 2.0 ** -7), mids * (1 - 2.0 ** -7), [0.0, 500.0, 1e6, 2.0 ** -10,
+                           2.0 ** -11, 3 * 2.0 ** -11]])
+    x = rng.choice(pool, shape) * rng.choice([-1.0, 1.0], shape) * scale
+    r = rng.random(shape) < 0.5
+    x = np.where(r, rng.standard_normal(shape) * 100 * scale, x)
+    return to_np64(torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16)).astype(np.float32)   # round to bf16 once
+
+
+@pytest.mark.parametrize("D", [128, 64])
+def test_quantize_rows_and_append_give_the_oracles_codes(D):
+    rng = np.random.default_rng(50 + D)
+    B, H, n, cap = 2, 3, 70, 75
+    ks = np.array([[1.0, 0.25, 0.0191], [3.0, 0.013, 1.0]], np.float32)
+    vs = np.array([[0.5, 1.0, 0.02], [0.0107, 2.0, 0.3]], np.float32)
+    K = _e4m3_adversarial(rng, (B, H, n, D), ks[:, :, None, None].astype(np.float64))
+    V = _e4m3_adversarial(rng, (B, H, n, D), vs[:, :, None, None].astype(np.float64))
+    shape = st3.make_shape(B, H, D, st3.ST3_BF16)
+    dKc = torch.full((B, H, cap, D), 0x55, dtype=torch.uint8, device=DEV); dVc = dKc.clone()
+    kv = st3.kv_layer(dKc, dVc, torch.from_numpy(ks).to(DEV), torch.from_numpy(vs).to(DEV))
+    st3.st3_quantize_rows(shape, to_dev(K, "bf16"), kv, 0, n)
+    st3.st3_quantize_rows(shape, to_dev(V, "bf16"), kv, 1, n)
+    # one more row through the append call
+    kn = _e4m3_adversarial(rng, (B, H, D), ks[:, :, None].astype(np.float64))
+    vn = _e4m3_adversarial(rng, (B, H, D), vs[:, :, None].astype(np.float64))
+    kv_len = _i32([n, n - 3])
+    st3.st3_kv_append(shape, kv, st3.segments(0, 0, n, _i32([0, 0]), kv_len), to_dev(kn, "bf16"), to_dev(vn, "bf16"))
+    torch.cuda.synchronize()
+    want_K = orc.e4m3_quantize(K, ks[:, :, None, None]); want_V = orc.e4m3_quantize(V, vs[:, :, None, None])
+    got_K, got_V = dKc.cpu().numpy(), dVc.cpu().numpy()
+    for b, row in enumerate([n, n - 3]):               # the appended row lands at the old kv_len[b]
+        wk = np.concatenate([want_K[b], np.full((H, cap - n, D), 0x55, np.uint8)], axis=1)
+        wv = np.concatenate([want_V[b], np.full((H, cap - n, D), 0x55, np.uint8)], axis=1)
+        wk[:, row] = orc.e4m3_quantize(kn[b], ks[b][:, None])
+        wv[:, row] = orc.e4m3_quantize(vn[b], vs[b][:, None])
+        assert np.array_equal(got_K[b], wk), b
+        assert np.array_equal(got_V[b], wv), b
+    assert kv_len.cpu().tolist() == [n + 1, n - 2]
+
+
+@pytest.mark.parametrize("D,B,H,lens,ns,nv", [
+    (128, 3, 5, [739, 257, 256], 35, 200),
+    (64, 2, 3, [1000, 31], 3, 20),
+    (128, 26, 40, [200] * 25 + [77], 35, 100),
+])
+def test_decode_attention_and_heredity_over_an_e4m3_cache(D, B, H, lens, ns, nv):
+    print(f"e4m3 decode D={D} B={B} H={H} lens={lens[:4]}", flush=True)
+    rng = np.random.default_rng(zlib.crc32(repr(("e4m3", D, B, H, lens)).encode()))
+    cap = max(lens) + 5
+    def codes(shape):
+        c = rng.integers(0, 256, shape, dtype=np.uint8)
+        return np.where(c & 0x7F == 0x7F, np.uint8(0x30), c).astype(np.uint8)      # no NaN codes in valid rows
+    Kc, Vc, Vl = codes((B, H, cap, D)), codes((B, H, cap, D)), codes((B, H, cap, D))
+    # scales that put the logits in a sane range: code values are up to 448
+    ks = (0.002 + rng.random((B, H)) * 0.004).astype(np.float32)
+    vs = (0.005 + rng.random((B, H)) * 0.01).astype(np.float32)
+    q = rand_values(rng, (B, H, D), "bf16", 1.43)
+    vis = [max(0, min(nv, L - ns)) for L in lens]
+    shape = st3.make_shape(B, H, D, st3.ST3_BF16)
+    dK, dV, dVl = (torch.from_numpy(x.copy()).to(DEV) for x in (Kc, Vc, Vl))
+    for b in range(B):                                 # NaN codes beyond every sequence
+        dK[b, :, lens[b]:] = 0x7F; dV[b, :, lens[b]:] = 0xFF; dVl[b, :, lens[b]:] = 0x7F
+    d_ks, d_vs = torch.from_numpy(ks).to(DEV), torch.from_numpy(vs).to(DEV)
+    out = torch.zeros((B, H, D), dtype=torch.bfloat16, device=DEV)
+    out_l = torch.zeros((B, H, D), dtype=torch.bfloat16, device=DEV)
+    mass = torch.full((B, nv + 3), -7.0, dtype=torch.float32, device=DEV)
+    kv_len, vis_len = _i32(lens), _i32(vis)
+    seg = st3.segments(ns, nv, max(lens), vis_len, kv_len)
+    ws_s, ws_l = _ws(shape, cap, nv), _ws(shape, cap, nv)
+    st3.st3_decode_attention(shape, to_dev(q, "bf16"), st3.kv_layer(dK, dV, d_ks, d_vs), seg, out, mass, ws_s)
+    st3.st3_decode_attention_inherit(shape, st3.kv_layer(None, dVl, None, d_vs), seg, ws_s, cap, out_l, ws_l)
+    torch.cuda.synchronize()
+    got_o, got_l, got_m = to_np64(out), to_np64(out_l), to_np64(mass)
+    for b in range(B):
+        n = lens[b]
+        Kd = orc.e4m3_decode(Kc[b:b + 1, :, :n]) * ks[b].astype(np.float64)[None, :, None, None]
+        Vd = orc.e4m3_decode(Vc[b:b + 1, :, :n]) * vs[b].astype(np.float64)[None, :, None, None]
+        Vld = orc.e4m3_decode(Vl[b:b + 1, :, :n]) * vs[b].astype(np.float64)[None, :, None, None]
+        o, m, _ = orc.decode_attention(q[b:b + 1], Kd, Vd, ns, vis[b])
+        ol, _, _ = orc.decode_attention(q[b:b + 1], Kd, Vld, ns, vis[b])
+        assert_attention_close(got_o[b], o[0], "bf16", f"b={b}")
+        assert_attention_close(got_l[b], ol[0], "bf16", f"lazy b={b}")
+        assert_mass_close(got_m[b, :vis[b]], m[0], f"b={b}")
+
+
+# ---------------------------------------------------------------------------
 # fused layer step: append + attention + mass, then the eviction for the next step (Alg. 3)
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("mode", [st3.ST3_STABLE, st3.ST3_HOLE_FILL])

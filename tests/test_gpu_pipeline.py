@@ -17,16 +17,18 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None, whole_step=False,
-                     lazy=None):
+                     lazy=None, kv_scale=None):
     T = w.steps if steps is None else steps
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
     keep_np = np.array(keep)
     assert np.array_equal(keep_np, orc.schedule_for(w)[:, :T + 1])
     gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt,
                               T, keep, window=window, mode=mode, compact_mode=compact_mode, device=DEV,
-                              lazy=lazy)
+                              lazy=lazy, kv_scale=kv_scale)
+    fp8 = {} if kv_scale is None else dict(kv_format="e4m3", k_scale=np.full((B, w.heads), kv_scale, np.float32),
+                                           v_scale=np.full((B, w.heads), kv_scale, np.float32))
     ref = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, keep_np, window=window, mode=mode,
-                         lazy=lazy)
+                         lazy=lazy, **fp8)
     pre = [prefill_qkv(w, l, B) for l in range(w.layers)]
     r = ref.prefill(lambda l: pre[l])
     diverged = np.zeros((w.layers, B), bool)      # a near-tie was resolved differently: values no longer comparable
@@ -118,8 +120,8 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
                     assert_mass_close(to_np64(lc.score[b, :lc.h_vis]), s["mass"][l][b][pos],
                                       f"ranking column after t={t} l={l} b={b}")
     # KV bytes actually held == closed form
-    assert gen.kv_bytes() == orc.kv_bytes(B, w.heads, w.head_dim, 2 if w.dtype == "bf16" else 4, ref.cache_lens(),
-                                          value_only=lazy or ())
+    ebytes = 1 if kv_scale is not None else 2 if w.dtype == "bf16" else 4
+    assert gen.kv_bytes() == orc.kv_bytes(B, w.heads, w.head_dim, ebytes, ref.cache_lens(), value_only=lazy or ())
     return near_ties, diverged
 
 
@@ -197,6 +199,21 @@ def test_qk_heredity_needs_the_whole_step_call():
     with pytest.raises(ValueError):
         pipeline.Generation(w.layers, w.heads, w.head_dim, torch.bfloat16, 1, w.n_sys, w.n_vis, w.n_txt, w.steps,
                             keep, device=DEV, lazy={3: 2})          # keeps differ
+
+
+@pytest.mark.parametrize("whole_step", [False, True])
+def test_e4m3_kv_cache_13b_shape_cut_down(whole_step):
+    """The caches in FP8 E4M3 (scale 6 sigma / 448 for every strip): prefill attends the unquantised
+    prompt, its rows and every appended row go through the quantiser, decode reads code x scale."""
+    w = dataclasses.replace(get_workload("llava15_13b"), layers=5, heads=8, steps=8,
+                            step_schedule={"kind": "cos", "tau": 8})
+    near, div = _run_and_compare(w, 2, whole_step=whole_step, kv_scale=6 * w.sigma / 448)
+    assert div.mean() < 0.5
+
+
+def test_e4m3_kv_cache_with_heredity_group_and_current_mode():
+    w = _lazy_workload("llava15_7b")
+    _run_and_compare(w, 2, mode="current", whole_step=True, lazy={4: 3, 5: 3}, kv_scale=6 * w.sigma / 448)
 
 
 def test_tiny_workload_batched_window():
