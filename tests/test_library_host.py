@@ -115,3 +115,42 @@ def test_argument_errors_are_reported_before_any_launch():
     # schedule helpers
     assert lib.st3_schedule_pvtp(32, 576, 3, 0, 5000, 100, fake) == st3.ST3_ERR_INVALID_ARG
     assert lib.st3_schedule_anneal(0, C.c_double(0.0), 4, fake, 2, fake) == st3.ST3_ERR_INVALID_ARG
+
+
+def test_ctypes_structures_have_the_layout_the_c_header_declares(tmp_path):
+    """Compiles a few lines of plain C against include/st3.h (also proving the header is valid C) and
+    compares sizeof / offsetof of every structure with the ctypes mirror in the binding."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    structs = {"st3_attn_shape": st3.AttnShape, "st3_tensor4": st3.Tensor4, "st3_kv_layer": st3.KvLayer,
+               "st3_segments": st3.Segments, "st3_gather_pair": st3.GatherPair, "st3_layer_step": st3.LayerStep}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "st3.h"', 'int main(void) {']
+    for cname, ct in structs.items():
+        lines.append(f'  printf("{cname} %zu\\n", sizeof({cname}));')
+        for fname, _ in ct._fields_:
+            lines.append(f'  printf("{cname}.{fname} %zu\\n", offsetof({cname}, {fname}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    got = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for cname, ct in structs.items():
+        assert int(got[cname]) == C.sizeof(ct), cname
+        for fname, _ in ct._fields_:
+            assert int(got[f"{cname}.{fname}"]) == getattr(ct, fname).offset, f"{cname}.{fname}"
+    # enumerators the binding repeats as plain integers
+    enums = {"ST3_KV_E4M3": st3.ST3_KV_E4M3, "ST3_E4M3": st3.ST3_E4M3, "ST3_HOLE_FILL": st3.ST3_HOLE_FILL,
+             "ST3_BF16": st3.ST3_BF16, "ST3_ERR_WORKSPACE_TOO_SMALL": st3.ST3_ERR_WORKSPACE_TOO_SMALL,
+             "ST3_ANNEAL_NONE": st3.ST3_ANNEAL_NONE, "ST3_MAX_GATHER": st3.ST3_MAX_GATHER}
+    src2 = tmp_path / "enums.c"
+    src2.write_text('#include <stdio.h>\n#include "st3.h"\nint main(void) {\n' +
+                    "".join(f'  printf("{k} %d\\n", (int){k});\n' for k in enums) + "  return 0;\n}\n")
+    exe2 = tmp_path / "enums"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src2), "-o", str(exe2)], check=True)
+    got2 = dict(l.split() for l in subprocess.run([str(exe2)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for k, v in enums.items():
+        assert int(got2[k]) == v, k
