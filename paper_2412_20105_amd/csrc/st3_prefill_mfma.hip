@@ -171,7 +171,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
         stage_tile<D>(tr, Ks, Vt, tid);
         __syncthreads();
         if (k0 + kBN < k_end) fetch_tile<D>(tr, Kp, Vp, a.k_st, a.v_st, k0 + kBN, n, tid);   // in flight while this tile is consumed
-        if (k0 > q0 + 31) continue;                     // tile entirely above this wave's diagonal
+        if (k0 > q0 + 31 || q0 >= n) continue;          // tile entirely above this wave's diagonal, or a wave whose
+                                                        // 32 queries all lie beyond the prompt (ragged last tile)
 
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
