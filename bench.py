@@ -50,6 +50,9 @@ def parse():
     ap.add_argument("--kv-format", default="plain", choices=["plain", "e4m3"],
                     help="e4m3: the KV caches hold FP8 E4M3 codes with one scale per (b, h) strip (6 sigma / 448); an extra "
                          "configuration beside the bf16 headline, not part of the paper")
+    ap.add_argument("--length-probe", type=int, default=0, metavar="BLOCK",
+                    help="decode latency and KV bytes against the generated length (the paper's latency figure, right "
+                         "panel): times every BLOCK decode steps of one job, pruned and unpruned; prints one JSON object")
     ap.add_argument("--prefill-probe", action="store_true",
                     help="prefill only (all layers with progressive pruning), three passes, for kernel traces and MFMA "
                          "counters of the prefill attention kernel; prints each layer's length and algorithmic flops")
@@ -196,6 +199,43 @@ def pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy=None):
                       "inherit_alg_bytes_per_launch_mean": (sum(per_lazy) / len(per_lazy)) if per_lazy else None}))
 
 
+def length_probe(w, B, T, keep, block, lazy, kv_format, torch, pipeline, st3):
+    """Per block of decode steps: mean ms per step and KV bytes held at the end of the block, for the
+    pruned schedule and for the same kernels without pruning."""
+    import dataclasses
+    wu = dataclasses.replace(w, layer_schedule={"kind": "full"}, step_schedule={"kind": "none"})
+    keep_u = [row[:T + 1] for row in pipeline.keep_table_for(wu)]
+    out = {"probe": "length", "workload": w.name, "batch": B, "decode_steps": T, "block": block, "rows": []}
+    series = {}
+    shared = None
+    for name, kp, lz in (("pruned", keep, lazy), ("unpruned", keep_u, {})):
+        job = Job(w if name == "pruned" else wu, B, T, kp, torch, pipeline, st3, lazy=lz, kv_format=kv_format)
+        if shared is not None:
+            job.pre, job.dec = shared
+        shared = (job.pre, job.dec)
+        job.run()                                   # warm-up
+        job.run_prefill_only()
+        torch.cuda.synchronize()
+        rows = []
+        for t0 in range(1, T + 1, block):
+            t1 = min(t0 + block, T + 1)
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            for t in range(t0, t1):
+                job.gen.decode_step(t, job.dec[t - 1])
+            torch.cuda.synchronize()
+            rows.append({"generated": t1 - 1, "ms_per_step": (time.perf_counter() - c0) * 1e3 / (t1 - t0),
+                         "kv_bytes": job.gen.kv_bytes()})
+        series[name] = rows
+        del job
+        torch.cuda.empty_cache()
+    for a_, b_ in zip(series["pruned"], series["unpruned"]):
+        out["rows"].append({"generated": a_["generated"], "pruned_ms_per_step": a_["ms_per_step"],
+                            "unpruned_ms_per_step": b_["ms_per_step"], "pruned_kv_bytes": a_["kv_bytes"],
+                            "unpruned_kv_bytes": b_["kv_bytes"]})
+    print(json.dumps(out))
+
+
 def prefill_probe(w, B, keep, torch, pipeline, st3):
     """Three prefill passes; per layer: tokens attended and algorithmic flops (causal half of QK^T and PV)."""
     job = Job(w, B, 1, [row[:2] for row in keep], torch, pipeline, st3)
@@ -255,6 +295,8 @@ def main():
 
     if a.prefill_probe:
         return prefill_probe(w, B, keep, torch, pipeline, st3)
+    if a.length_probe > 0:
+        return length_probe(w, B, T, keep, a.length_probe, lazy, a.kv_format, torch, pipeline, st3)
     if a.pmc_probe:
         return pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy)
 
