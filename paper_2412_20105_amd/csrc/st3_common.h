@@ -49,8 +49,9 @@ inline float scale_log2(const st3_attn_shape* s) {
 
 // ---------------------------------------------------------------------------------------------
 // Workspace carving.  The decode-path region is laid out from the cache CAPACITY alone, so that
-// a layer which keeps its own workspace sees the same offsets at every step (the deferred visual
-// mass relies on the saved logits surviving from one call to the next).  The prefill region
+// every call on a layer's workspace sees the same offsets whatever the step's lengths are: the
+// eviction plan finishes the mass from what the attend launch left there, and a lazy layer reads
+// its source layer's logits and normalisers from the source's workspace.  The prefill region
 // starts behind it and depends on the call's own sizes.
 // ---------------------------------------------------------------------------------------------
 constexpr int kMaxWindow = 16;

@@ -1,6 +1,6 @@
 // Head reduction of the visual mass (Sec. 3.2: last-row attention on the visual keys, here
-// averaged over heads), shared by the decode finish kernel and by the select-and-compact kernel
-// that finishes a deferred mass at the start of the next step.
+// averaged over heads), shared by the decode finish kernel and by the eviction-plan kernel, which
+// finishes the mass of the attention launch that preceded it.
 #pragma once
 
 #include "st3_attend.h"

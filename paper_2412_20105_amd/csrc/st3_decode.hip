@@ -54,7 +54,7 @@ struct DecodeArgs {
     const int32_t* kv_len;
     const int32_t* vis_len;
     int32_t B, sys_len, max_vis, max_kv, H, nsplit, nsplit_cap, chunk, capacity;
-    int32_t defer;          // 1: the mass of this call is finished later; mark it pending
+    int32_t defer;          // 1: the mass of this call is finished by the eviction plan that follows; mark it pending
     int32_t keep_all_logits;  // 1: keep the logit of every key (a lazy layer will ask for them), else visual only
     float scale_l2;
     const float* k_scale;   // [B*H] value of one K code unit (E4M3 caches; null: 1)

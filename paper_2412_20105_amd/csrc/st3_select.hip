@@ -324,10 +324,10 @@ void launch_evict_apply(const EvictArgs& ea, int B, hipStream_t st) {
 }
 
 
-// Eviction plan (+ optional append bookkeeping, deferred-mass finish and in-kernel row moves),
+// Eviction plan (+ optional append bookkeeping, finishing of the mass and in-kernel row moves),
 // then the separate move kernel when the plan kernel does not move the rows itself.
 //   appended:   the attention kernel has just written one row beyond kv_len[b]; it is counted here
-//   mass_dst:   where a mass left pending by the previous attention call is finished (null: skip)
+//   mass_dst:   where the mass of the attention launch before this call is finished (null: skip)
 st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                                   float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count,
                                   int32_t mode, void* workspace, size_t workspace_bytes, hipStream_t st,
