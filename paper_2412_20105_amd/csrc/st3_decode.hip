@@ -112,6 +112,7 @@ void decode_attend_kernel(DecodeArgs a) {
     const T* qrow = reinterpret_cast<const T*>(a.q) + bh * D;
     KT* kbase = reinterpret_cast<KT*>(a.k) + b * a.stride_b + h * a.stride_h;
     KT* vbase = reinterpret_cast<KT*>(a.v) + b * a.stride_b + h * a.stride_h;
+    if (a.max_kv > 0 && c0 >= a.max_kv) return;     // (the host launches no such chunk; the early loads below rely on it)
 #if ST3_DECODE_PIPELINED
     // The first tile's loads go out before the sequence length has arrived: the host bound keeps
     // them inside the strip (rows the length later rules out are masked when the tile is consumed).
@@ -563,6 +564,8 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     if (da.nsplit > wl.nsplit_cap) da.nsplit = wl.nsplit_cap;
     da.nsplit_cap = wl.nsplit_cap;
     da.chunk = decode_chunk(max_kv_len, da.nsplit);
+    da.nsplit = (max_kv_len + da.chunk - 1) / da.chunk;         // rounding the chunk up to 32 rows can leave chunks empty
+    if (da.nsplit < 1) da.nsplit = 1;
     da.capacity = kv->capacity;
     da.scale_l2 = scale_log2(shape);
     if (kv->format == ST3_KV_E4M3) { da.k_scale = kv->k_scale; da.v_scale = kv->v_scale; }
@@ -631,6 +634,8 @@ st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, 
     if (ia.nsplit > wl.nsplit_cap) ia.nsplit = wl.nsplit_cap;
     ia.nsplit_cap = wl.nsplit_cap;
     ia.chunk = decode_chunk(max_kv_len, ia.nsplit);
+    ia.nsplit = (max_kv_len + ia.chunk - 1) / ia.chunk;
+    if (ia.nsplit < 1) ia.nsplit = 1;
     ia.src_logits = reinterpret_cast<const float*>(sws + sl.logits);
     ia.src_part_ml = reinterpret_cast<const float*>(sws + sl.part_ml);
     ia.src_pending = reinterpret_cast<const int32_t*>(sws + sl.pending);

@@ -37,6 +37,8 @@ def _i32(x):
     ("bf16", 64, 2, 2, [1000, 31], 3, 20),
     ("bf16", 128, 2, 2, [33, 0], 1, 7),                # an empty sequence
     ("bf16", 128, 1, 40, [1251], 35, 576),             # 13B head count, cache at full length
+    ("bf16", 128, 1, 22, [1000], 35, 200),             # 12 chunks wanted, 11 needed once the chunk is rounded to 32 rows
+    ("f32", 64, 3, 7, [2000, 1999, 5], 0, 0),          # no visual segment at all
 ])
 def test_decode_attention_matches_oracle(dtype, D, B, H, lens, ns, nv):
     print(f"decode dtype={dtype} D={D} B={B} H={H} lens={lens}", flush=True)
