@@ -47,6 +47,9 @@ def parse():
                     help="QK heredity groups (Eq. 6, Alg. 2) as SRC:FIRST-LAST[,SRC:FIRST-LAST...], e.g. 36:37-39 = "
                          "layers 37..39 reuse the attention probabilities of layer 36 (the paper's '28 -> 29~31' for "
                          "the 7B model); lazy layers take their source's row of the retention table")
+    ap.add_argument("--contiguous-tail", action="store_true",
+                    help="keep every cache contiguous (an eviction closes the tail up: two row moves per evicted row) "
+                         "instead of leaving the instruction + generated rows at a fixed offset (one move)")
     ap.add_argument("--kv-format", default="plain", choices=["plain", "e4m3"],
                     help="e4m3: the KV caches hold FP8 E4M3 codes with one scale per (b, h) strip (6 sigma / 448); an extra "
                          "configuration beside the bf16 headline, not part of the paper")
@@ -65,7 +68,7 @@ def parse():
 class Job:
     """Device-resident inputs of one batch and the call sequence of one whole job."""
 
-    def __init__(self, w, B, T, keep, torch, pipeline, st3, seed=1234, lazy=None, kv_format="plain"):
+    def __init__(self, w, B, T, keep, torch, pipeline, st3, seed=1234, lazy=None, kv_format="plain", fixed_tail=True):
         self.w, self.B, self.T, self.keep = w, B, T, keep
         self.lazy = dict(lazy or {})
         self.kv_format = kv_format
@@ -84,7 +87,8 @@ class Job:
         self.dec = [randn(shape_d) for _ in range(T)]
         self.gen = pipeline.Generation(w.layers, w.heads, w.head_dim, dt, B, w.n_sys, w.n_vis, w.n_txt, T, keep,
                                        device=dev, lazy=self.lazy,
-                                       kv_scale=(6 * w.sigma / 448) if kv_format == "e4m3" else None)
+                                       kv_scale=(6 * w.sigma / 448) if kv_format == "e4m3" else None,
+                                       fixed_tail=fixed_tail)
 
     def run(self):
         gen, w = self.gen, self.w
@@ -301,7 +305,7 @@ def main():
         return pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy)
 
     note(f"generating inputs for {w.name} B={B} T={T}")
-    job = Job(w, B, T, keep, torch, pipeline, st3, lazy=lazy, kv_format=a.kv_format)
+    job = Job(w, B, T, keep, torch, pipeline, st3, lazy=lazy, kv_format=a.kv_format, fixed_tail=not a.contiguous_tail)
     note("warmup")
     for _ in range(a.warmup):
         job.run()
@@ -322,7 +326,8 @@ def main():
                                f"{w.n_sys}+{w.n_vis}+{w.n_txt}, T={T} decode steps, batch {B}, "
                                f"schedule {w.layer_schedule}/{w.step_schedule}",
                    "batch": B, "decode_steps": T, "step_definition": "prefill (all layers, PVTP) + T decode steps (VTA)",
-                   "lazy_layers": {str(l): s for l, s in sorted(lazy.items())}, "kv_format": a.kv_format},
+                   "lazy_layers": {str(l): s for l, s in sorted(lazy.items())}, "kv_format": a.kv_format,
+                   "tail": "contiguous" if a.contiguous_tail else "fixed offset"},
         "prefill_ms": ms_prefill,
         "decode_ms_per_token_step": (ms_job - ms_prefill) / T,
         "decode_only_tokens_per_s": tokens / ((ms_job - ms_prefill) * 1e-3),
@@ -363,7 +368,7 @@ def main():
         keep_u = [row[:T + 1] for row in pipeline.keep_table_for(wu)]
         del job.gen
         torch.cuda.empty_cache()
-        job_u = Job(wu, B, T, keep_u, torch, pipeline, st3, kv_format=a.kv_format)
+        job_u = Job(wu, B, T, keep_u, torch, pipeline, st3, kv_format=a.kv_format, fixed_tail=not a.contiguous_tail)
         job_u.pre, job_u.dec = job.pre, job.dec
         job_u.run()
         ms_u = timed(torch, job_u.run, 1) * 1e3

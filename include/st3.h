@@ -88,17 +88,36 @@ typedef struct {
     const float* v_scale;
 } st3_kv_layer;
 
-/* Where the visual keys sit in a layer's cache.  For sequence b the cache holds kv_len[b] rows;
- * rows [sys_len, sys_len + vis_len[b]) are visual keys; everything else (system prompt, instruction,
- * generated tokens) is never pruned.  kv_len and vis_len live on the DEVICE because the kernels
- * update them; max_kv_len / max_vis_len are HOST-side upper bounds used to size launches and to
- * index the workspace (kv_len[b] <= max_kv_len <= capacity, vis_len[b] <= max_vis_len). */
+/* Where the visual keys sit in a layer's cache.  For sequence b the cache holds rows up to
+ * kv_len[b]; rows [sys_len, sys_len + vis_len[b]) are visual keys; everything else (system prompt,
+ * instruction, generated tokens) is never pruned.  kv_len and vis_len live on the DEVICE because the
+ * kernels update them; max_kv_len / max_vis_len are HOST-side upper bounds used to size launches and
+ * to index the workspace (kv_len[b] <= max_kv_len <= capacity, vis_len[b] <= max_vis_len).
+ * tail_start (DEVICE [B], may be NULL) chooses between two layouts of the rows behind the visual
+ * segment (instruction + generated tokens, "the tail"):
+ *   NULL      the tail follows the visual rows directly; an eviction closes the cache up again
+ *             (up to two row moves per evicted row) and lowers kv_len[b];
+ *   non-NULL  the tail starts at row tail_start[b] >= sys_len + vis_len[b] and stays there; rows
+ *             [sys_len + vis_len[b], tail_start[b]) hold nothing and no call reads them.  An
+ *             eviction only refills holes inside the visual segment (at most one row move per
+ *             evicted row) and leaves kv_len[b], the END of the tail, alone.  Requires
+ *             kv_len[b] >= tail_start[b].  Keys attended: kv_len[b] - (tail_start[b] - sys_len - vis_len[b]).
+ * A prefill leaves [system | kept visual | instruction] contiguous, so tail_start[b] =
+ * sys_len + vis_len[b] at that moment is where the fixed-tail layout begins.
+ * vis_len_hint / tail_start_hint (HOST values; tail_start_hint <= 0: none) are the caller's guess at
+ * the value most sequences have in vis_len[b] / tail_start[b] right now.  The decode attention
+ * addresses its first loads with them while the device values are still on their way; a sequence
+ * whose values differ has those loads repeated, so a wrong guess costs time and never changes a
+ * result.  Ignored when tail_start is NULL. */
 typedef struct {
     int32_t  sys_len;
     int32_t  max_vis_len;
     int32_t  max_kv_len;
     int32_t* vis_len;       /* DEVICE [B] */
     int32_t* kv_len;        /* DEVICE [B] */
+    const int32_t* tail_start;  /* DEVICE [B] or NULL */
+    int32_t  vis_len_hint;
+    int32_t  tail_start_hint;
 } st3_segments;
 
 ST3_EXPORT const char* st3_status_string(st3_status s);

@@ -63,7 +63,8 @@ class KvLayer(C.Structure):
 
 class Segments(C.Structure):
     _fields_ = [("sys_len", C.c_int32), ("max_vis_len", C.c_int32), ("max_kv_len", C.c_int32),
-                ("vis_len", C.c_void_p), ("kv_len", C.c_void_p)]
+                ("vis_len", C.c_void_p), ("kv_len", C.c_void_p), ("tail_start", C.c_void_p),
+                ("vis_len_hint", C.c_int32), ("tail_start_hint", C.c_int32)]
 
 
 class GatherPair(C.Structure):
@@ -195,10 +196,13 @@ def kv_layer(k: Optional[torch.Tensor], v: torch.Tensor, k_scale: Optional[torch
     return s
 
 
-def segments(sys_len: int, max_vis_len: int, max_kv_len: int, vis_len: torch.Tensor, kv_len: torch.Tensor) -> Segments:
+def segments(sys_len: int, max_vis_len: int, max_kv_len: int, vis_len: torch.Tensor, kv_len: torch.Tensor,
+             tail_start: Optional[torch.Tensor] = None, vis_len_hint: int = 0, tail_start_hint: int = 0) -> Segments:
     assert vis_len.dtype == torch.int32 and kv_len.dtype == torch.int32 and vis_len.is_cuda and kv_len.is_cuda
-    s = Segments(sys_len, max_vis_len, max_kv_len, vis_len.data_ptr(), kv_len.data_ptr())
-    s._refs = (vis_len, kv_len)
+    assert tail_start is None or (tail_start.dtype == torch.int32 and tail_start.is_cuda)
+    s = Segments(sys_len, max_vis_len, max_kv_len, vis_len.data_ptr(), kv_len.data_ptr(), _ptr(tail_start),
+                 vis_len_hint, tail_start_hint)
+    s._refs = (vis_len, kv_len, tail_start)
     return s
 
 

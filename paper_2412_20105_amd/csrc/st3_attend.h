@@ -132,23 +132,79 @@ __device__ __forceinline__ void wave_attend(const float* qf, const T* kbase, con
     }
 }
 
+// Where the rows a wave walks over sit in the strip.  A cache may keep its never-pruned tail
+// (instruction and generated rows) at a fixed row offset while the visual segment in front of it
+// shrinks: the rows the attention sees are then numbered without the gap, and row r of that
+// numbering is stored at r (r < split_row) or at r + gap.  {INT_MAX, 0}: no gap.
+struct RowShift {
+    int split_row;
+    int gap;
+    __device__ __forceinline__ int physical(int r) const { return r + (r >= split_row ? gap : 0); }
+};
+
+// The two layouts of the rows behind the visual segment, resolved for one sequence: `len_phys`
+// rows exist physically; tail_start == null: they are contiguous; else the tail begins at
+// tail_start[b] and the rows between the visual segment and it are dead.
+struct SeqLayout {
+    int nv;         // visual rows
+    int base;       // sys_len + nv: first row behind the visual segment in the gap-free numbering
+    int gap;        // dead rows between the segment and the tail
+    int vlen;       // rows the attention sees
+    __device__ __forceinline__ RowShift shift() const { return RowShift{base, gap}; }
+};
+__device__ __forceinline__ SeqLayout seq_layout(int sys_len, int vis_len_b, int max_vis, int len_phys,
+                                                const int32_t* tail_start, int b) {
+    SeqLayout L;
+    L.nv = max(0, min(vis_len_b, max_vis));
+    L.base = min(sys_len + L.nv, max(len_phys, 0));
+    const int ts = tail_start ? tail_start[b] : L.base;
+    L.gap = ts > L.base ? ts - L.base : 0;
+    L.vlen = L.base + max(0, len_phys - (L.base + L.gap));
+    return L;
+}
+
 // Issues the loads of the tile of U*RPL rows that starts at t0: rows >= bound read `safe_row` instead.
 template <typename T, int D, int U, bool NT>
 __device__ __forceinline__ void issue_tile(const T* kbase, const T* vbase, int64_t stride_t, int t0, int bound,
-                                           int safe_row, int lane, uint4 (&k)[U], uint4 (&v)[U]) {
+                                           int safe_row, int lane, uint4 (&k)[U], uint4 (&v)[U],
+                                           const RowShift sh = RowShift{0x7fffffff, 0}) {
     using M = RowMap<T, D>;
     const int grp = lane / M::LPR;
     const int64_t col = (int64_t)(lane % M::LPR) * M::EPL;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int row = t0 + u * M::RPL + grp;
-        k[u] = load16<NT>(kbase + (int64_t)(row < bound ? row : safe_row) * stride_t + col);
+        k[u] = load16<NT>(kbase + (int64_t)sh.physical(row < bound ? row : safe_row) * stride_t + col);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int row = t0 + u * M::RPL + grp;
-        v[u] = load16<NT>(vbase + (int64_t)(row < bound ? row : safe_row) * stride_t + col);
+        v[u] = load16<NT>(vbase + (int64_t)sh.physical(row < bound ? row : safe_row) * stride_t + col);
     }
+}
+
+// The same for a tile whose placement is a guess (`sh` may be wrong for this sequence): rows of the
+// tile at or beyond row_bound, and rows that `sh` would place at or beyond phys_bound, read
+// `safe_row` (< row_bound, taken as stored where it is numbered) instead, so every address stays
+// below phys_bound whatever the guess.
+template <typename T, int D, int U, bool NT>
+__device__ __forceinline__ void issue_tile_within(const T* kbase, const T* vbase, int64_t stride_t, int t0, int row_bound,
+                                                  int phys_bound, int safe_row, int lane, uint4 (&k)[U], uint4 (&v)[U],
+                                                  const RowShift sh) {
+    using M = RowMap<T, D>;
+    const int grp = lane / M::LPR;
+    const int64_t col = (int64_t)(lane % M::LPR) * M::EPL;
+    int64_t off[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int row = t0 + u * M::RPL + grp;
+        const int p = sh.physical(row);
+        off[u] = (int64_t)((row < row_bound && p < phys_bound) ? p : safe_row) * stride_t + col;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) k[u] = load16<NT>(kbase + off[u]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = load16<NT>(vbase + off[u]);
 }
 
 // Same contract as wave_attend, software-pipelined: the loads of tile i+1 are issued before tile i
@@ -160,7 +216,8 @@ template <typename T, int D, int U, bool NT>
 __device__ __forceinline__ void wave_attend_primed(const float* qf, const T* kbase, const T* vbase, int64_t stride_t,
                                                    int r0, int r1, int step, int safe_row, float scale_l2, int lane,
                                                    WaveState<RowMap<T, D>::EPL>& st, float* logit_out, int vis_lo,
-                                                   int vis_hi, uint4 (&kr)[U], uint4 (&vr)[U]) {
+                                                   int vis_hi, uint4 (&kr)[U], uint4 (&vr)[U],
+                                                   const RowShift sh = RowShift{0x7fffffff, 0}) {
     using M = RowMap<T, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, RPL = M::RPL;
     const int grp = lane / LPR;
@@ -168,7 +225,7 @@ __device__ __forceinline__ void wave_attend_primed(const float* qf, const T* kba
     uint4 kn[U], vn[U];
     for (int t0 = r0; t0 < r1; t0 += step) {
         const int tn = t0 + step;
-        if (tn < r1) issue_tile<T, D, U, NT>(kbase, vbase, stride_t, tn, r1, safe_row, lane, kn, vn);
+        if (tn < r1) issue_tile<T, D, U, NT>(kbase, vbase, stride_t, tn, r1, safe_row, lane, kn, vn, sh);
         float s[U];
         float mt = -INFINITY;
 #pragma unroll

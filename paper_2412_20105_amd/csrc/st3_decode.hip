@@ -53,7 +53,9 @@ struct DecodeArgs {
     int64_t stride_b, stride_h, stride_t;
     const int32_t* kv_len;
     const int32_t* vis_len;
+    const int32_t* tail_start;  // [B] or null (the tail follows the visual rows directly)
     int32_t B, sys_len, max_vis, max_kv, H, nsplit, nsplit_cap, chunk, capacity;
+    int32_t hint_base, hint_gap;    // the host's guess at the layout of a fixed-tail cache (INT_MAX, 0: none)
     int32_t defer;          // 1: the mass of this call is finished by the eviction plan that follows; mark it pending
     int32_t keep_all_logits;  // 1: keep the logit of every key (a lazy layer will ask for them), else visual only
     float scale_l2;
@@ -116,10 +118,12 @@ void decode_attend_kernel(DecodeArgs a) {
 #if ST3_DECODE_PIPELINED
     // The first tile's loads go out before the sequence length has arrived: the host bound keeps
     // them inside the strip (rows the length later rules out are masked when the tile is consumed).
-    // Takes one dependent memory round trip off the front of every workgroup.
+    // Takes one dependent memory round trip off the front of every workgroup.  Where the cache keeps
+    // a gap behind its visual segment the rows are placed by the host's guess at it.
     uint4 kr[U], vr[U];
-    issue_tile<KT, D, U, true>(kbase, vbase, a.stride_t, c0 + wave * TILE,
-                              min(c0 + a.chunk, a.max_kv - (a.k_new != nullptr ? 1 : 0)), c0, lane, kr, vr);
+    const RowShift guess{a.hint_base, a.hint_gap};
+    issue_tile_within<KT, D, U, true>(kbase, vbase, a.stride_t, c0 + wave * TILE, c0 + a.chunk,
+                                     a.max_kv - (a.k_new != nullptr ? 1 : 0), c0, lane, kr, vr, guess);
 #endif
     float qf[EPL];
     load_row_slice<T, KT, D>(qrow, lane, qf);
@@ -127,7 +131,12 @@ void decode_attend_kernel(DecodeArgs a) {
     const float k_unit = a.k_scale ? a.k_scale[bh] : 1.0f, v_unit = a.v_scale ? a.v_scale[bh] : 1.0f;
     const float scale_l2 = a.scale_l2 * k_unit;
     // the row being appended sits at index kv_len[b]; never trust a device length past the host bound
-    const int len = min(a.kv_len[b] + (a.k_new != nullptr ? 1 : 0), a.max_kv);
+    const int len_phys = min(a.kv_len[b] + (a.k_new != nullptr ? 1 : 0), a.max_kv);
+    // `len` and every row index below are in the gap-free numbering (a cache with a fixed tail keeps
+    // dead rows between the visual segment and the tail); `sh` maps a row to where it is stored
+    const SeqLayout lay = seq_layout(a.sys_len, a.vis_len[b], a.max_vis, len_phys, a.tail_start, b);
+    const int len = lay.vlen;
+    const RowShift sh = lay.shift();
     if (split == 0 && h == 0 && tid == 0 && a.pending != nullptr) {
         a.pending[b * 4 + 0] = (a.logits != nullptr && len > 0 && a.defer) ? 1 : 0;
         a.pending[b * 4 + 1] = a.nsplit;
@@ -152,9 +161,10 @@ void decode_attend_kernel(DecodeArgs a) {
     // partial-line writes), so it is done only where it is needed.  Index = cache row either way.
     float* lg = a.logits ? a.logits + bh * a.capacity : nullptr;
     const int vis_lo = a.keep_all_logits ? 0 : a.sys_len;
-    const int vis_hi = a.keep_all_logits ? len : a.sys_len + min(a.vis_len[b], a.max_vis);
+    const int vis_hi = a.keep_all_logits ? len : a.sys_len + lay.nv;
     if (lg) lg += vis_lo;           // the wave loop indexes by (row - vis_lo)
-    const bool has_new = a.k_new != nullptr && c1 == len;       // this workgroup owns the appended row
+    // this workgroup owns the appended row (stored at the physical end, which a fixed tail must have reached)
+    const bool has_new = a.k_new != nullptr && c1 == len && len_phys - 1 >= lay.base + lay.gap;
     const int c1_cached = has_new ? c1 - 1 : c1;
     // the appended token's row is fetched now and used after the cached rows: off the critical path
     u32x4_t kn_raw = {0, 0, 0, 0}, vn_raw = {0, 0, 0, 0};       // native vectors: the uint4 class would live in scratch
@@ -164,23 +174,32 @@ void decode_attend_kernel(DecodeArgs a) {
     }
     // waves take the tiles of the chunk round-robin, so all four stay busy to the end
 #if ST3_DECODE_PIPELINED
+    // the early tile placed its rows by the host's guess: fetch it again if that put a row this
+    // sequence attends to in the wrong place (a sequence that differs from the guess, in a tile that
+    // reaches behind its visual segment or the guessed one)
+    {
+        const int tile_end = min(c0 + wave * TILE + TILE, c1_cached);
+        const bool same = lay.gap == guess.gap && (lay.gap == 0 || lay.base == guess.split_row);
+        const bool in_front = tile_end <= lay.base && (guess.gap == 0 || tile_end <= guess.split_row);
+        if (!same && !in_front)
+            issue_tile<KT, D, U, true>(kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, c0, lane, kr, vr, sh);
+    }
     // rows of the early tile that the length rules out came from beyond the sequence: their V may
     // hold anything (NaN included), and 0 * NaN would poison the accumulator
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (c0 + wave * TILE + u * M::RPL + lane / LPR >= c1_cached) vr[u] = make_uint4(0, 0, 0, 0);
     wave_attend_primed<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
-                                       c0, scale_l2, lane, st, lg, vis_lo, vis_hi, kr, vr);
+                                       c0, scale_l2, lane, st, lg, vis_lo, vis_hi, kr, vr, sh);
 #else
-    wave_attend<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0,
-                          scale_l2, lane, st, lg, vis_lo, vis_hi);
+#error "the decode kernel is built on the pipelined wave loop"
 #endif
     if (has_new && wave == 0) {
         wave_attend_row<KT, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
                                make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, scale_l2, lane, st, lg, vis_lo,
                               vis_hi);
         if (lane < 2 * LPR) {                       // store the row into the cache: lanes [0,LPR) K, [LPR,2*LPR) V
-            KT* dst = (lane < LPR ? kbase : vbase) + (int64_t)(len - 1) * a.stride_t + (lane % LPR) * EPL;
+            KT* dst = (lane < LPR ? kbase : vbase) + (int64_t)(len_phys - 1) * a.stride_t + (lane % LPR) * EPL;
             *reinterpret_cast<u32x4_t*>(dst) = lane < LPR ? kn_raw : vn_raw;
         }
     }
@@ -221,7 +240,9 @@ struct InheritArgs {
     void* v;
     int64_t stride_b, stride_h, stride_t;
     const int32_t* kv_len;
-    int32_t B, max_kv, H, nsplit, nsplit_cap, chunk;
+    const int32_t* vis_len;
+    const int32_t* tail_start;  // [B] or null
+    int32_t B, max_kv, H, nsplit, nsplit_cap, chunk, sys_len, max_vis;
     const float* src_logits;    // [B,H,src_capacity]
     const float* src_part_ml;   // [B,H,src_nsplit_cap,2]
     const int32_t* src_pending; // [B][4]
@@ -236,7 +257,8 @@ struct InheritArgs {
 // loads are issued before the current tile is consumed.
 template <typename T, int D, int U>
 __device__ __forceinline__ void wave_inherit(const T* vbase, int64_t stride_t, int r0, int r1, int step, int safe_row,
-                                             const float* lg, float m, float rl, int lane, float* acc) {
+                                             const float* lg, float m, float rl, int lane, float* acc,
+                                             const RowShift sh) {
     using M = RowMap<T, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, RPL = M::RPL;
     const int grp = lane / LPR;
@@ -248,7 +270,7 @@ __device__ __forceinline__ void wave_inherit(const T* vbase, int64_t stride_t, i
     for (int u = 0; u < U; ++u) {
         const int row = r0 + u * RPL + grp;
         const int rr = row < r1 ? row : safe_row;
-        vr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(vbase + (int64_t)rr * stride_t + col));
+        vr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(vbase + (int64_t)sh.physical(rr) * stride_t + col));
         sr[u] = lg[rr];
     }
     for (int t0 = r0; t0 < r1; t0 += step) {
@@ -258,7 +280,7 @@ __device__ __forceinline__ void wave_inherit(const T* vbase, int64_t stride_t, i
             for (int u = 0; u < U; ++u) {
                 const int row = tn + u * RPL + grp;
                 const int rr = row < r1 ? row : safe_row;
-                vn[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(vbase + (int64_t)rr * stride_t + col));
+                vn[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(vbase + (int64_t)sh.physical(rr) * stride_t + col));
                 sn[u] = lg[rr];
             }
         }
@@ -284,7 +306,11 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
     using M = RowMap<KT, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, TILE = U * M::RPL;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int len = min(a.kv_len[b] + (a.v_new != nullptr ? 1 : 0), a.max_kv);
+    const int len_phys = min(a.kv_len[b] + (a.v_new != nullptr ? 1 : 0), a.max_kv);
+    // rows are numbered without the gap a fixed-tail cache keeps behind its visual segment, as in the
+    // source layer's attend launch (same lengths, same layout): its logits are indexed the same way
+    const SeqLayout lay = seq_layout(a.sys_len, a.vis_len[b], a.max_vis, len_phys, a.tail_start, b);
+    const int len = lay.vlen;
     const int c0 = split * a.chunk;
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int64_t bh = (int64_t)b * a.H + h;
@@ -313,9 +339,10 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
     float acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-    const bool has_new = a.v_new != nullptr && c1 == len;
+    const bool has_new = a.v_new != nullptr && c1 == len && len_phys - 1 >= lay.base + lay.gap;
     const int c1_cached = has_new ? c1 - 1 : c1;
-    wave_inherit<KT, D, U>(vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0, lg, m, rl, lane, acc);
+    wave_inherit<KT, D, U>(vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE, c0, lg, m, rl, lane, acc,
+                           lay.shift());
     if (has_new && wave == 0 && lane < LPR) {
         const u32x4_t raw = NewRow<T, KT, D>::load(reinterpret_cast<const T*>(a.v_new) + bh * D, lane, v_unit);
         const float p = exp2_fast(lg[len - 1] - m) * rl;
@@ -323,7 +350,7 @@ __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_
         ElemTraits<KT>::unpack(make_uint4(raw.x, raw.y, raw.z, raw.w), vf);
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
-        *reinterpret_cast<u32x4_t*>(vbase + (int64_t)(len - 1) * a.stride_t + lane * EPL) = raw;
+        *reinterpret_cast<u32x4_t*>(vbase + (int64_t)(len_phys - 1) * a.stride_t + lane * EPL) = raw;
     }
 #pragma unroll
     for (int off = LPR; off < kWave; off <<= 1) {
@@ -351,6 +378,7 @@ struct FinishArgs {
     const float* logits;
     const int32_t* kv_len;
     const int32_t* vis_len;
+    const int32_t* tail_start;  // [B] or null
     int32_t H, nsplit, nsplit_cap, chunk, capacity, max_vis, max_kv, sys_len;
     int32_t plain_sum;      // 1: the partial outputs are already normalised, just add them (lazy layers)
     int32_t appended;       // 1: the attend kernel took one more row than kv_len[b] says (the token being appended)
@@ -364,7 +392,9 @@ struct FinishArgs {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_finish_kernel(FinishArgs a) {
     const int b = blockIdx.y, tid = threadIdx.x;
-    const int len = min(a.kv_len[b] + a.appended, a.max_kv);
+    const SeqLayout lay = seq_layout(a.sys_len, a.vis_len[b], a.max_vis, min(a.kv_len[b] + a.appended, a.max_kv),
+                                     a.tail_start, b);
+    const int len = lay.vlen;                           // rows the attend launch saw
     const int ns = len > 0 ? min((len + a.chunk - 1) / a.chunk, a.nsplit) : 0;
     const int out_blocks = a.out ? a.H : 0;
     if ((int)blockIdx.x < out_blocks) {
@@ -391,7 +421,7 @@ __global__ __launch_bounds__(256) void decode_finish_kernel(FinishArgs a) {
     }
     if (a.mass == nullptr) return;
     __shared__ float sm_m[1024], sm_rl[1024];
-    const int nv = min(a.vis_len[b], a.max_vis);
+    const int nv = lay.nv;
     head_norms(a.part_ml, b, a.H, ns, a.nsplit_cap, sm_m, sm_rl);
     const int j0 = ((int)blockIdx.x - out_blocks) * 256;
     finish_mass(a.logits + a.sys_len, b, a.H, a.capacity, sm_m, sm_rl, j0, min(j0 + 256, nv),
@@ -558,8 +588,15 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     DecodeArgs da{};
     da.q = q; da.k = kv->k; da.v = kv->v;
     da.stride_b = kv->stride_b; da.stride_h = kv->stride_h; da.stride_t = kv->stride_t;
-    da.kv_len = seg->kv_len; da.vis_len = seg->vis_len;
+    da.kv_len = seg->kv_len; da.vis_len = seg->vis_len; da.tail_start = seg->tail_start;
     da.B = B; da.sys_len = seg->sys_len; da.max_vis = seg->max_vis_len; da.max_kv = max_kv_len; da.H = H;
+    da.hint_base = 0x7fffffff; da.hint_gap = 0;
+    if (seg->tail_start != nullptr && seg->tail_start_hint > 0) {
+        const int nv = std::max(0, std::min(seg->vis_len_hint, seg->max_vis_len));
+        const int base = seg->sys_len + nv;
+        const int ts = std::min(seg->tail_start_hint, kv->capacity);    // (keeps row + gap far from overflow)
+        if (ts > base) { da.hint_base = base; da.hint_gap = ts - base; }
+    }
     da.nsplit = decode_nsplit(B, H, max_kv_len);
     if (da.nsplit > wl.nsplit_cap) da.nsplit = wl.nsplit_cap;
     da.nsplit_cap = wl.nsplit_cap;
@@ -582,7 +619,7 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     if (da.nsplit > 1 || mass_now) {
         FinishArgs fa{};
         fa.part_o = da.part_o; fa.part_ml = da.part_ml; fa.logits = da.logits;
-        fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len;
+        fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len; fa.tail_start = seg->tail_start;
         fa.H = H; fa.nsplit = da.nsplit; fa.nsplit_cap = wl.nsplit_cap; fa.chunk = da.chunk;
         fa.capacity = kv->capacity; fa.max_vis = seg->max_vis_len; fa.max_kv = max_kv_len; fa.sys_len = seg->sys_len;
         fa.appended = k_new != nullptr ? 1 : 0;
@@ -629,7 +666,9 @@ st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, 
     const char* sws = reinterpret_cast<const char*>(src_workspace);
     InheritArgs ia{};
     ia.v = kv->v; ia.stride_b = kv->stride_b; ia.stride_h = kv->stride_h; ia.stride_t = kv->stride_t;
-    ia.kv_len = seg->kv_len; ia.B = B; ia.max_kv = max_kv_len; ia.H = H;
+    ia.kv_len = seg->kv_len; ia.vis_len = seg->vis_len; ia.tail_start = seg->tail_start;
+    ia.sys_len = seg->sys_len; ia.max_vis = seg->max_vis_len;
+    ia.B = B; ia.max_kv = max_kv_len; ia.H = H;
     ia.nsplit = decode_nsplit(B, H, max_kv_len);
     if (ia.nsplit > wl.nsplit_cap) ia.nsplit = wl.nsplit_cap;
     ia.nsplit_cap = wl.nsplit_cap;
@@ -646,7 +685,8 @@ st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, 
     ST3_DISPATCH_KV(launch_inherit, shape, kv, ia, B, st);
     if (ia.nsplit > 1) {
         FinishArgs fa{};
-        fa.part_o = ia.part_o; fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len;
+        fa.part_o = ia.part_o; fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len; fa.tail_start = seg->tail_start;
+        fa.sys_len = seg->sys_len; fa.max_vis = seg->max_vis_len;
         fa.H = H; fa.nsplit = ia.nsplit; fa.nsplit_cap = wl.nsplit_cap; fa.chunk = ia.chunk;
         fa.capacity = kv->capacity; fa.max_kv = max_kv_len; fa.plain_sum = 1;
         fa.appended = v_new != nullptr ? 1 : 0;

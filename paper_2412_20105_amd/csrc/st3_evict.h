@@ -109,6 +109,7 @@ struct EvictArgs {
     int64_t col_stride;
     int32_t* vis_len;
     int32_t* kv_len;
+    const int32_t* tail_start;  // [B] or null: the tail keeps its place (no tail moves, kv_len not lowered)
     int32_t sys_len, max_vis, max_kv, keep_count, mode;
     int32_t* move_cnt;          // [B]
     int32_t* moves;             // [B][max_moves][2] = (dst row, src row)
@@ -184,7 +185,8 @@ __device__ __forceinline__ void evict_plan_body(const EvictArgs& a, int b, SelSh
         if (valid) {
             const int nsplit = min(a.pending[b * 4 + 1], a.nsplit_cap);
             const int chunk = max(a.pending[b * 4 + 2], 32);
-            const int ns = len > 0 ? min((len + chunk - 1) / chunk, nsplit) : 0;
+            const int seen = seq_layout(a.sys_len, n, a.max_vis, len, a.tail_start, b).vlen;    // rows the attend launch saw
+            const int ns = seen > 0 ? min((seen + chunk - 1) / chunk, nsplit) : 0;
             head_norms(a.part_ml, b, a.H, ns, a.nsplit_cap, sm_hm, sm_hrl);
             finish_mass(a.logits + a.sys_len, b, a.H, a.capacity, sm_hm, sm_hrl, 0, n, a.mass_dst + b * a.mass_stride);
             __syncthreads();                            // the ranking below may read these scores
@@ -211,7 +213,8 @@ __device__ __forceinline__ void evict_plan_body(const EvictArgs& a, int b, SelSh
         }
         __syncthreads();
         const int g = n - k;                            // rows evicted
-        const int r = len - (a.sys_len + n);            // rows behind the visual segment
+        // rows behind the visual segment that have to close up; none when the tail keeps its place
+        const int r = a.tail_start ? 0 : len - (a.sys_len + n);
         int m = 0;                                      // moves inside the visual segment
         if (a.mode == ST3_HOLE_FILL) {
             int base_h = 0, base_f = 0;
@@ -290,7 +293,7 @@ __device__ __forceinline__ void evict_plan_body(const EvictArgs& a, int b, SelSh
             }
             moves_left = m + r;
         }
-        new_len = len - g;
+        new_len = a.tail_start ? len : len - g;
         if (tid == 0) a.vis_len[b] = k;
     }
     if (tid == 0) {

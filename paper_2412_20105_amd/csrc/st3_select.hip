@@ -263,7 +263,7 @@ st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv,
     const bool evicting = keep_count >= 0 && keep_count < seg->max_vis_len;
     ea = EvictArgs{};
     ea.score_col = score_col; ea.id_col = id_col; ea.col_stride = col_stride;
-    ea.vis_len = seg->vis_len; ea.kv_len = seg->kv_len;
+    ea.vis_len = seg->vis_len; ea.kv_len = seg->kv_len; ea.tail_start = seg->tail_start;
     ea.sys_len = seg->sys_len; ea.max_vis = seg->max_vis_len; ea.max_kv = seg->max_kv_len;
     ea.keep_count = evicting ? keep_count : -1; ea.mode = mode;
     ea.move_cnt = reinterpret_cast<int32_t*>(ws + wl.moves_cnt);

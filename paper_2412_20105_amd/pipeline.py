@@ -52,6 +52,8 @@ class LayerCache:
         self.mass = torch.zeros((B, max(cap_v, 1)), dtype=torch.float32, device=device)
         self.vis_len = torch.zeros((B,), dtype=torch.int32, device=device)
         self.kv_len = torch.zeros((B,), dtype=torch.int32, device=device)
+        self.tail_start = None      # set at prefill when the tail keeps its place (Generation(fixed_tail=True))
+        self.h_tail = 0             # host copy of it
         self.kv = st3.kv_layer(self.k, self.v, self.k_scale, self.v_scale)
         # a workspace of its own: the attention leaves its logits here for the mass and for lazy layers
         self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=device)
@@ -68,6 +70,9 @@ class Generation:
     lazy: {l: src} - QK heredity (Eq. 6, Alg. 2): layer l applies the attention probabilities of
     source layer src to its own values, at prefill and at every decode step.  Lazy layers follow
     their source directly and share its row of the keep table; their Q and K inputs are ignored.
+    fixed_tail: the rows behind a layer's visual segment (instruction + generated tokens) stay where
+    the prefill put them while the segment shrinks: an eviction then moves at most one row per evicted
+    row instead of two (no closing up of the tail); False keeps every cache contiguous.
     kv_scale: None keeps the caches in `dtype`; a float makes them FP8 E4M3 (bf16 only) with that
     scale for every (b, h) strip of K and of V - the caller's calibration, e.g. 6 sigma / 448.
     """
@@ -75,7 +80,8 @@ class Generation:
     def __init__(self, layers: int, heads: int, head_dim: int, dtype: torch.dtype, batch: int,
                  n_sys: int, n_vis: int, n_txt: int, steps: int, keep: Sequence[Sequence[int]],
                  window: int = 1, mode: str = "static", compact_mode: int = st3.ST3_HOLE_FILL,
-                 device: str = "cuda:0", lazy: Optional[Dict[int, int]] = None, kv_scale: Optional[float] = None):
+                 device: str = "cuda:0", lazy: Optional[Dict[int, int]] = None, kv_scale: Optional[float] = None,
+                 fixed_tail: bool = True):
         self.L, self.H, self.d, self.B = layers, heads, head_dim, batch
         self.n_sys, self.n_vis, self.n_txt, self.T = n_sys, n_vis, n_txt, steps
         self.keep = [list(r) for r in keep]
@@ -100,6 +106,7 @@ class Generation:
                                           value_only=l in self.lazy, kv_scale=kv_scale))
             st3.st3_workspace_init(self.shape, cap, self.layers[-1].ws)
         self.kv_scale = kv_scale
+        self.fixed_tail = fixed_tail
         self.q_stage = torch.empty((batch, heads, self.N0, head_dim), dtype=dtype, device=device)
         # an E4M3 cache cannot serve as the prefill's K/V input: the prompt is attended unquantised
         # from staging buffers and its rows enter the cache through the quantiser afterwards
@@ -175,6 +182,11 @@ class Generation:
         lc.vis_len.fill_(alive)
         lc.kv_len.fill_(n_l)
         lc.h_vis, lc.h_kv = alive, n_l
+        if self.fixed_tail:         # [system | kept visual | instruction] is contiguous now: the tail starts here for good
+            if lc.tail_start is None:
+                lc.tail_start = torch.empty((self.B,), dtype=torch.int32, device=self.device)
+            lc.h_tail = ns + alive
+            lc.tail_start.fill_(lc.h_tail)
         self._decoding = False
         return out, lc.mass[:, :alive]
 
@@ -185,10 +197,11 @@ class Generation:
         for l, lc in enumerate(self.layers):
             target = min(self.keep[l][1], lc.h_vis) if self.T >= 1 else lc.h_vis
             if target < lc.h_vis:
-                seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len)
+                seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len, lc.tail_start)
                 st3.st3_select_compact_layer(self.shape, lc.kv, seg, lc.score, lc.ids, target, self.compact_mode,
                                              lc.ws)
-                lc.h_kv -= lc.h_vis - target
+                if not self.fixed_tail:
+                    lc.h_kv -= lc.h_vis - target
                 lc.h_vis = target
         self._decoding = True
 
@@ -216,11 +229,11 @@ class Generation:
         lc = self.layers[l]
         n_attn = lc.h_vis
         target = self._keep_after(l, t)
-        seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len)
+        seg = st3.segments(self.n_sys, lc.h_vis, lc.h_kv, lc.vis_len, lc.kv_len, lc.tail_start, lc.h_vis, lc.h_tail)
         mass_dst = self._mass_dst(lc)
         st3.st3_decode_layer_step(self.shape, lc.kv, seg, lc.score, lc.ids, target if target < lc.h_vis else -1,
                                   self.compact_mode, q, k_new, v_new, self.dec_out, mass_dst, lc.ws)
-        lc.h_kv = lc.h_kv + 1 - (lc.h_vis - target)
+        lc.h_kv = lc.h_kv + 1 - (0 if self.fixed_tail else lc.h_vis - target)
         lc.h_vis = target
         return self.dec_out, mass_dst[:, :n_attn]
 
@@ -235,7 +248,7 @@ class Generation:
             for l, lc in enumerate(self.layers):
                 s = arr[l]
                 s.kv = lc.kv
-                s.seg = st3.segments(self.n_sys, 0, 0, lc.vis_len, lc.kv_len)
+                s.seg = st3.segments(self.n_sys, 0, 0, lc.vis_len, lc.kv_len, lc.tail_start)
                 s.score_col, s.id_col, s.col_stride = lc.score.data_ptr(), lc.ids.data_ptr(), lc.score.stride(0)
                 md = self._mass_dst(lc)
                 s.vis_mass, s.mass_stride = md.data_ptr(), md.stride(0)
@@ -251,14 +264,18 @@ class Generation:
             target = self._keep_after(l, t)
             s.keep_after = target if target < lc.h_vis else -1
             s.seg.max_vis_len, s.seg.max_kv_len = lc.h_vis, lc.h_kv
+            s.seg.vis_len_hint, s.seg.tail_start_hint = lc.h_vis, lc.h_tail     # every sequence holds these (equal images)
             s.q, s.k_new, s.v_new = base + (3 * l) * one, base + (3 * l + 1) * one, base + (3 * l + 2) * one
-            lc.h_kv = lc.h_kv + 1 - (lc.h_vis - target)
+            lc.h_kv = lc.h_kv + 1 - (0 if self.fixed_tail else lc.h_vis - target)
             lc.h_vis = target
         st3.st3_decode_step(self.shape, arr, self.L, self.compact_mode)
         return self.dec_out_all
 
     def kv_lens(self) -> List[int]:
-        return [lc.h_kv for lc in self.layers]
+        """Keys each layer holds (dead rows between a visual segment and a fixed tail do not count)."""
+        if not self.fixed_tail:
+            return [lc.h_kv for lc in self.layers]
+        return [lc.h_kv - (lc.h_tail - self.n_sys - lc.h_vis) for lc in self.layers]
 
     def kv_bytes(self) -> int:
         lens = self.kv_lens()

@@ -98,7 +98,8 @@ def test_full_shape_one_sequence_replayed_by_oracle(name, batch, sample_b, oracl
         step_mass.append([to_np64(gen.layers[l].mass[sample_b]) for l in range(LO)])   # in the order attended
     for l in range(w.layers):
         k_end = keep_full[l][T + 1] if T < w.steps else keep_full[l][T]
-        assert gen.layers[l].kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, k_end, w.n_txt, T)] * batch
+        assert gen.kv_lens()[l] == orc.kv_len(w.n_sys, k_end, w.n_txt, T)
+        assert gen.layers[l].kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, keep_full[l][0], w.n_txt, T)] * batch   # the tail keeps its place
         assert gen.layers[l].vis_len.cpu().tolist() == [k_end] * batch
 
     # ---- the oracle replays the sampled sequence from the original inputs -----------------------

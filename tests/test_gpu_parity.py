@@ -555,6 +555,79 @@ def test_decode_layer_step(mode, dtype, D, H, lens, keep_after):
         assert np.array_equal(got_tail_K, Kb[:, srcs]) and np.array_equal(got_tail_V, Vb[:, srcs])
 
 
+@pytest.mark.parametrize("mode,hint", [(st3.ST3_STABLE, "none"), (st3.ST3_HOLE_FILL, "none"), (st3.ST3_STABLE, "first"),
+                                       (st3.ST3_HOLE_FILL, "last"), (st3.ST3_STABLE, "far")])
+@pytest.mark.parametrize("dtype,D,H,tails,keep_after,B_extra", [
+    ("bf16", 128, 4, [60, 1, 129, 0], 20, 0),      # a sequence without any tail row yet: the new row is its first
+    ("bf16", 128, 40, [128, 300, 7, 64], 90, 24),  # enough strips that none is split; rows past the segment in the first tiles
+    ("f32", 64, 3, [40, 41, 42, 43], 0, 0),        # the whole visual segment goes, the tail stays where it is
+    ("bf16", 128, 2, [33, 200, 90, 5], 7, 0),      # more than the in-kernel row-move limit is evicted
+])
+def test_decode_layer_step_with_a_fixed_tail(mode, hint, dtype, D, H, tails, keep_after, B_extra):
+    """The rows behind the visual segment start at tail_start[b] and never move; between the segment
+    and them the cache holds NaN.  Attention must see system + visual + tail + the new token; the
+    eviction may only touch the visual segment.  The host's guess at the layout (right for one
+    sequence and wrong for the others, or wrong for all) must not show in any result."""
+    print(f"fixed tail mode={mode} hint={hint} dtype={dtype} H={H} tails={tails} keep_after={keep_after}", flush=True)
+    tails = tails + [50] * B_extra
+    rng = np.random.default_rng(zlib.crc32(repr(("ft", dtype, D, H, tails, keep_after)).encode()))
+    B, ns = len(tails), 6
+    vis = [100 + (37 * b) % 120 for b in range(B)]
+    nv = max(vis)
+    ts = [ns + v + (13 * b) % 70 for b, v in enumerate(vis)]          # some sequences have no gap yet (b = 0)
+    lens = [t + r for t, r in zip(ts, tails)]                         # physical end of each tail
+    cap = max(lens) + 3
+    sigma = 1.0 if dtype == "f32" else 1.43
+    K = rand_values(rng, (B, H, cap, D), dtype, sigma); V = rand_values(rng, (B, H, cap, D), dtype, sigma)
+    q, kn, vn = (rand_values(rng, (B, H, D), dtype, sigma) for _ in range(3))
+    score = rng.standard_normal((B, nv)).astype(np.float32)
+    ids = np.stack([rng.permutation(2000)[:nv] for _ in range(B)]).astype(np.int32)
+    shape = st3.make_shape(B, H, D, CODE[dtype])
+    dK, dV = to_dev(K, dtype), to_dev(V, dtype)
+    for b in range(B):                                 # dead rows and everything past the end: NaN
+        for t in (dK, dV):
+            t[b, :, ns + vis[b]:ts[b]] = float("nan"); t[b, :, lens[b]:] = float("nan")
+    K0, V0 = dK.float().cpu().numpy(), dV.float().cpu().numpy()
+    d_score, d_ids = torch.from_numpy(score.copy()).to(DEV), torch.from_numpy(ids.copy()).to(DEV)
+    out = torch.zeros((B, H, D), dtype=TORCH_DTYPE[dtype], device=DEV)
+    mass = torch.full((B, nv + 2), -7.0, dtype=torch.float32, device=DEV)
+    vis_len, kv_len, tail_start = _i32(vis), _i32(lens), _i32(ts)
+    guess = {"none": (0, 0), "first": (vis[0], ts[0]), "last": (vis[-1], ts[-1]), "far": (3, 2 ** 31 - 1)}[hint]
+    seg = st3.segments(ns, nv, max(lens), vis_len, kv_len, tail_start, *guess)
+    st3.st3_decode_layer_step(shape, st3.kv_layer(dK, dV), seg, d_score, d_ids, keep_after, mode, to_dev(q, dtype),
+                              to_dev(kn, dtype), to_dev(vn, dtype), out, mass, _ws(shape, cap, nv))
+    torch.cuda.synchronize()
+    got_o, got_m = to_np64(out), to_np64(mass)
+    gK, gV = dK.float().cpu().numpy(), dV.float().cpu().numpy()
+    g_ids, g_score = d_ids.cpu().numpy(), d_score.cpu().numpy()
+    assert tail_start.cpu().tolist() == ts
+    for b in range(B):
+        nb, L = vis[b], lens[b]
+        live = np.concatenate([np.arange(ns + nb), np.arange(ts[b], L)])
+        Kb = np.concatenate([K[b][:, live], kn[b][:, None]], axis=1)
+        Vb = np.concatenate([V[b][:, live], vn[b][:, None]], axis=1)
+        o, m, _ = orc.decode_attention(q[b:b + 1], Kb[None], Vb[None], ns, nb)
+        assert_attention_close(got_o[b], o[0], dtype, f"b={b}")
+        assert_mass_close(got_m[b, :nb], m[0], f"b={b}")
+        kb = nb if keep_after < 0 else min(keep_after, nb)
+        assert vis_len[b].item() == kb and kv_len[b].item() == L + 1, b        # the end of the tail only grows
+        pos = orc.select_topk(score[b, :nb].astype(np.float64), ids[b, :nb], kb)
+        got_ids = g_ids[b, :kb]
+        if mode == st3.ST3_STABLE or kb == nb:
+            assert np.array_equal(got_ids, ids[b, pos])
+        else:
+            assert sorted(got_ids.tolist()) == sorted(ids[b, pos].tolist())
+        where = {int(t): p for p, t in enumerate(ids[b, :nb])}
+        order = np.array([where[int(t)] for t in got_ids], dtype=np.int64)
+        assert np.array_equal(g_score[b, :kb], score[b, order])
+        assert np.array_equal(gK[b][:, :ns], K[b][:, :ns])
+        assert np.array_equal(gK[b][:, ns:ns + kb], K[b][:, ns + order]) and np.array_equal(gV[b][:, ns:ns + kb], V[b][:, ns + order])
+        # the tail: bit for bit where it was, the new row right behind it, nothing else touched from there on
+        assert np.array_equal(gK[b][:, ts[b]:L], K[b][:, ts[b]:L]) and np.array_equal(gV[b][:, ts[b]:L], V[b][:, ts[b]:L])
+        assert np.array_equal(gK[b][:, L], kn[b]) and np.array_equal(gV[b][:, L], vn[b])
+        assert np.array_equal(gK[b][:, L + 1:], K0[b][:, L + 1:], equal_nan=True)
+
+
 # ---------------------------------------------------------------------------
 # prefill attention + mass
 # ---------------------------------------------------------------------------

@@ -17,14 +17,19 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None, whole_step=False,
-                     lazy=None, kv_scale=None):
+                     lazy=None, kv_scale=None, fixed_tail=True):
     T = w.steps if steps is None else steps
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
     keep_np = np.array(keep)
     assert np.array_equal(keep_np, orc.schedule_for(w)[:, :T + 1])
     gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt,
                               T, keep, window=window, mode=mode, compact_mode=compact_mode, device=DEV,
-                              lazy=lazy, kv_scale=kv_scale)
+                              lazy=lazy, kv_scale=kv_scale, fixed_tail=fixed_tail)
+
+    def phys_len(l, k_vis, t):
+        """kv_len[b] the device must hold: the end of the tail, which does not move when it is fixed."""
+        return orc.kv_len(w.n_sys, keep[l][0] if fixed_tail else k_vis, w.n_txt, t)
+
     fp8 = {} if kv_scale is None else dict(kv_format="e4m3", k_scale=np.full((B, w.heads), kv_scale, np.float32),
                                            v_scale=np.full((B, w.heads), kv_scale, np.float32))
     ref = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, keep_np, window=window, mode=mode,
@@ -80,8 +85,8 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
         for l in range(w.layers):
             lc = gen.layers[l]
             assert lc.vis_len.cpu().tolist() == [keep[l][t]] * B
-            assert lc.kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, keep[l][t], w.n_txt, t) - 1] * B
-            assert lc.h_kv + 1 == s["kv_len"][l][0]
+            assert lc.kv_len.cpu().tolist() == [phys_len(l, keep[l][t], t) - 1] * B
+            assert gen.kv_lens()[l] + 1 == s["kv_len"][l][0]
             for b in range(B):
                 if not diverged[l, b]:
                     check_sets(l, b, rho_before[l][b], ids_before[l][b], keep[l][t], f"t={t} l={l} b={b}")
@@ -102,7 +107,7 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
             k_next = keep[l][t + 1] if t < T else keep[l][t]
             assert lc.h_vis == k_next
             assert lc.vis_len.cpu().tolist() == [k_next] * B
-            assert lc.kv_len.cpu().tolist() == [orc.kv_len(w.n_sys, k_next, w.n_txt, t)] * B
+            assert lc.kv_len.cpu().tolist() == [phys_len(l, k_next, t)] * B
             ids_after = lc.ids[:, :lc.h_vis].cpu().numpy()
             for b in range(B):
                 if diverged[l, b]:
@@ -125,11 +130,12 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
     return near_ties, diverged
 
 
+@pytest.mark.parametrize("fixed_tail", [True, False])
 @pytest.mark.parametrize("mode", ["static", "current"])
 @pytest.mark.parametrize("compact_mode", [st3.ST3_HOLE_FILL, st3.ST3_STABLE])
-def test_tiny_workload_full(mode, compact_mode):
+def test_tiny_workload_full(mode, compact_mode, fixed_tail):
     w = get_workload("tiny")
-    near, div = _run_and_compare(w, 1, mode=mode, compact_mode=compact_mode)
+    near, div = _run_and_compare(w, 1, mode=mode, compact_mode=compact_mode, fixed_tail=fixed_tail)
     assert not div.any(), "tiny workload resolved a near-tie differently from the oracle"
 
 
@@ -153,12 +159,12 @@ def test_many_layers_whole_step_call_current_mode():
     _run_and_compare(w, 2, mode="current", whole_step=True)
 
 
-def test_large_evictions_whole_step_call():
-    """Evictions above the in-kernel row-move threshold: the separate row-move launch after a plan
-    that rode in the next layer's attention launch."""
+@pytest.mark.parametrize("fixed_tail", [True, False])
+def test_large_evictions_whole_step_call(fixed_tail):
+    """Evictions above the in-kernel row-move threshold: the separate row-move launch after the plans."""
     w = dataclasses.replace(get_workload("llava15_13b"), layers=5, heads=4, steps=3, n_txt=20,
                             step_schedule={"kind": "cos", "tau": 3})
-    _run_and_compare(w, 2, whole_step=True)
+    _run_and_compare(w, 2, whole_step=True, fixed_tail=fixed_tail)
 
 
 def _lazy_workload(name, **kw):
@@ -211,9 +217,11 @@ def test_e4m3_kv_cache_13b_shape_cut_down(whole_step):
     assert div.mean() < 0.5
 
 
-def test_e4m3_kv_cache_with_heredity_group_and_current_mode():
+@pytest.mark.parametrize("fixed_tail", [True, False])
+def test_e4m3_kv_cache_with_heredity_group_and_current_mode(fixed_tail):
     w = _lazy_workload("llava15_7b")
-    _run_and_compare(w, 2, mode="current", whole_step=True, lazy={4: 3, 5: 3}, kv_scale=6 * w.sigma / 448)
+    _run_and_compare(w, 2, mode="current", whole_step=True, lazy={4: 3, 5: 3}, kv_scale=6 * w.sigma / 448,
+                     fixed_tail=fixed_tail)
 
 
 def test_tiny_workload_batched_window():
@@ -221,11 +229,13 @@ def test_tiny_workload_batched_window():
     _run_and_compare(w, 3, window=2)
 
 
-def test_13b_shape_cut_down():
-    """Head dim, token counts and schedule form of the 13B workload; fewer layers, heads, steps."""
+@pytest.mark.parametrize("fixed_tail", [True, False])
+def test_13b_shape_cut_down(fixed_tail):
+    """Head dim, token counts and schedule form of the 13B workload; fewer layers, heads, steps.  With a
+    fixed tail the visual segments empty out while the tail stays 600 rows further on."""
     w = dataclasses.replace(get_workload("llava15_13b"), layers=6, heads=8, steps=12,
                             step_schedule={"kind": "cos", "tau": 12})
-    near, div = _run_and_compare(w, 2)
+    near, div = _run_and_compare(w, 2, fixed_tail=fixed_tail)
     assert div.mean() < 0.5
 
 
