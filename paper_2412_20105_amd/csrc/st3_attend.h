@@ -267,18 +267,6 @@ __device__ __forceinline__ void wave_attend_primed(const float* qf, const T* kba
     }
 }
 
-template <typename T, int D, int U, bool NT>
-__device__ __forceinline__ void wave_attend_pipelined(const float* qf, const T* kbase, const T* vbase,
-                                                      int64_t stride_t, int r0, int r1, int step, int safe_row,
-                                                      float scale_l2, int lane, WaveState<RowMap<T, D>::EPL>& st,
-                                                      float* logit_out, int vis_lo, int vis_hi) {
-    if (r0 >= r1) return;
-    uint4 kr[U], vr[U];
-    issue_tile<T, D, U, NT>(kbase, vbase, stride_t, r0, r1, safe_row, lane, kr, vr);
-    wave_attend_primed<T, D, U, NT>(qf, kbase, vbase, stride_t, r0, r1, step, safe_row, scale_l2, lane, st, logit_out,
-                                    vis_lo, vis_hi, kr, vr);
-}
-
 // One more row for a wave's state, from registers: kraw/vraw hold this lane's 16-byte slices of the
 // row (every row-group holds the same row; only group 0 counts it).
 template <typename T, int D>

@@ -27,9 +27,6 @@
 #ifndef ST3_DECODE_U
 #define ST3_DECODE_U 8              // 16-byte loads of K (and of V) in flight per lane and tile
 #endif
-#ifndef ST3_DECODE_PIPELINED
-#define ST3_DECODE_PIPELINED 1      // 1: issue the next tile's loads before consuming the current one
-#endif
 #ifndef ST3_DECODE_THREADS
 #define ST3_DECODE_THREADS 256      // threads per workgroup of the attend kernel
 #endif
@@ -115,7 +112,6 @@ void decode_attend_kernel(DecodeArgs a) {
     KT* kbase = reinterpret_cast<KT*>(a.k) + b * a.stride_b + h * a.stride_h;
     KT* vbase = reinterpret_cast<KT*>(a.v) + b * a.stride_b + h * a.stride_h;
     if (a.max_kv > 0 && c0 >= a.max_kv) return;     // (the host launches no such chunk; the early loads below rely on it)
-#if ST3_DECODE_PIPELINED
     // The first tile's loads go out before the sequence length has arrived: the host bound keeps
     // them inside the strip (rows the length later rules out are masked when the tile is consumed).
     // Takes one dependent memory round trip off the front of every workgroup.  Where the cache keeps
@@ -124,7 +120,6 @@ void decode_attend_kernel(DecodeArgs a) {
     const RowShift guess{a.hint_base, a.hint_gap};
     issue_tile_within<KT, D, U, true>(kbase, vbase, a.stride_t, c0 + wave * TILE, c0 + a.chunk,
                                      a.max_kv - (a.k_new != nullptr ? 1 : 0), c0, lane, kr, vr, guess);
-#endif
     float qf[EPL];
     load_row_slice<T, KT, D>(qrow, lane, qf);
     // a code unit of K is worth k_scale: folded into the logit scale; V's goes onto the output
@@ -173,7 +168,6 @@ void decode_attend_kernel(DecodeArgs a) {
         vn_raw = NewRow<T, KT, D>::load(reinterpret_cast<const T*>(a.v_new) + bh * D, lane, v_unit);
     }
     // waves take the tiles of the chunk round-robin, so all four stay busy to the end
-#if ST3_DECODE_PIPELINED
     // the early tile placed its rows by the host's guess: fetch it again if that put a row this
     // sequence attends to in the wrong place (a sequence that differs from the guess, in a tile that
     // reaches behind its visual segment or the guessed one)
@@ -191,9 +185,6 @@ void decode_attend_kernel(DecodeArgs a) {
         if (c0 + wave * TILE + u * M::RPL + lane / LPR >= c1_cached) vr[u] = make_uint4(0, 0, 0, 0);
     wave_attend_primed<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
                                        c0, scale_l2, lane, st, lg, vis_lo, vis_hi, kr, vr, sh);
-#else
-#error "the decode kernel is built on the pipelined wave loop"
-#endif
     if (has_new && wave == 0) {
         wave_attend_row<KT, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
                                make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, scale_l2, lane, st, lg, vis_lo,

@@ -90,7 +90,7 @@ __device__ __forceinline__ void stage_tile(const TileRegs<NK, NV>& t, uint16_t* 
     }
 }
 
-// grid (ceil(n/128), H, B); x reversed so the longest query tiles start first.
+// One-dimensional grid of ceil(n/128) * H * B workgroups (the mapping to query tile and strip is in the kernel).
 // Register budget: two waves per SIMD (256 registers each), so that one wave's softmax VALU work
 // overlaps the other's MFMAs.  The 64-key LDS tile is consumed as two 32-key halves, each with its
 // own online-softmax update, which halves the live S/P registers; the accumulator is only rescaled
