@@ -59,6 +59,9 @@ def parse():
     ap.add_argument("--prefill-probe", action="store_true",
                     help="prefill only (all layers with progressive pruning), three passes, for kernel traces and MFMA "
                          "counters of the prefill attention kernel; prints each layer's length and algorithmic flops")
+    ap.add_argument("--select-probe", action="store_true",
+                    help="time the selection and compaction calls alone (top-k, in-place eviction in both modes and both "
+                         "cache layouts, the prefill gather) at the workload's shape and print one JSON line")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="short run for counter collection: prefill, one plain 1 GiB device copy of known size, "
                          "then the decode steps; prints the algorithmic bytes of each attend launch")
@@ -255,6 +258,92 @@ def prefill_probe(w, B, keep, torch, pipeline, st3):
                       "flops_all_layers": sum(x["flops"] for x in layers), "layers": layers}))
 
 
+def select_probe(w, B, torch, st3):
+    """Selection and compaction on their own (the steps between two attentions): microseconds per call
+    from a start/stop event pair around each call, and the bytes the call has to move."""
+    dev = torch.device("cuda:0")
+    H, d, ns, nv, nx = w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    eb = 2 if w.dtype == "bf16" else 4
+    shape = st3.make_shape(B, H, d, st3.ST3_BF16 if w.dtype == "bf16" else st3.ST3_F32)
+    gen = 64                                    # generated rows behind the prompt
+    n0 = ns + nv + nx + gen
+    cap = n0 + 8
+    K = torch.randn((B, H, cap, d), device=dev).to(dt); V = torch.randn((B, H, cap, d), device=dev).to(dt)
+    ws = torch.empty((st3.st3_workspace_bytes(shape, cap, nv, 1),), dtype=torch.uint8, device=dev)
+    st3.st3_workspace_init(shape, cap, ws)
+    score0 = torch.rand((B, nv), device=dev)
+    ids0 = torch.arange(nv, device=dev, dtype=torch.int32).repeat(B, 1).contiguous()
+    score, ids = score0.clone(), ids0.clone()
+    vis_len = torch.empty((B,), dtype=torch.int32, device=dev); kv_len = torch.empty_like(vis_len)
+    tail = torch.full((B,), ns + nv, dtype=torch.int32, device=dev)
+    kv = st3.kv_layer(K, V)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def one(fn, reset, reps=12):
+        """Microseconds per call.  reset=None: the call leaves no state behind, so `reps` calls run back to
+        back between one pair of events.  Otherwise every call gets its own pair (after `reset`), which adds
+        the cost of the pair itself: the row with evicted = 0 shows that floor."""
+        tot = 0.0
+        if reset is None:
+            fn(); fn()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record(); torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e3
+        for r in range(reps + 2):
+            reset()
+            e0.record(); fn(); e1.record()
+            torch.cuda.synchronize()
+            if r >= 2:
+                tot += e0.elapsed_time(e1)
+        return tot / reps * 1e3
+
+    rows = []
+    # top-k alone (Eq. 3): scores of one prune event
+    mask = torch.empty((B, nv), dtype=torch.uint8, device=dev)
+    for k in sorted({nv // 2, nv // 10}):
+        idx = torch.empty((B, k), dtype=torch.int32, device=dev)
+        us = one(lambda: st3.st3_select_topk(score0, ids0, None, nv, k, mask, idx), None)
+        rows.append({"call": "st3_select_topk", "n": nv, "k": k, "us": us, "bytes": B * (8 * nv + nv + 4 * k)})
+    # eviction of e visual rows from one layer's cache (Eq. 7, Sec. 4.3), both modes, both layouts
+    row_bytes = 2 * H * d * eb                  # one cache row of a sequence, K and V over all heads
+    for e in (0, 1, 4, 16, 64, nv // 2):
+        for mode, mname in ((st3.ST3_HOLE_FILL, "hole_fill"), (st3.ST3_STABLE, "stable")):
+            for fixed in (False, True):
+                def reset():
+                    score.copy_(score0); ids.copy_(ids0); vis_len.fill_(nv); kv_len.fill_(n0)
+                seg = st3.segments(ns, nv, n0, vis_len, kv_len, tail if fixed else None, nv, ns + nv if fixed else 0)
+                us = one(lambda: st3.st3_select_compact_layer(shape, kv, seg, score, ids, nv - e, mode, ws), reset)
+                # rows moved, summed over the batch, from the scores (victims = the e lowest scores of a sequence)
+                if e == 0:
+                    moved = 0
+                else:
+                    victim = torch.zeros((B, nv), dtype=torch.bool, device=dev)
+                    victim.scatter_(1, score0.argsort(dim=1)[:, :e], True)
+                    if mode == st3.ST3_HOLE_FILL:   # survivors in the last e places of the segment fill the holes in front of them
+                        moved = int((~victim[:, nv - e:]).sum().item()) + (0 if fixed else B * min(e, nx + gen))
+                    else:                           # every surviving row behind a sequence's first hole is rewritten
+                        first = victim.float().argmax(dim=1)
+                        moved = int((nv - first).sum().item()) - B * e + (0 if fixed else B * (nx + gen))
+                rows.append({"call": "st3_select_compact_layer", "mode": mname, "tail": "fixed" if fixed else "contiguous",
+                             "evicted": e, "us": us, "bytes": 2 * moved * row_bytes})
+    # the prefill gather (Alg. 1: X = [S, V_kept, I]) of a layer's Q, K, V rows
+    n_all = ns + nv + nx
+    src = [torch.randn((B, H, n_all, d), device=dev).to(dt) for _ in range(3)]
+    for k in sorted({nv // 2, nv // 10}):
+        dst = [torch.empty((B, H, ns + k + nx, d), device=dev, dtype=dt) for _ in range(3)]
+        idx = torch.sort(torch.rand((B, nv), device=dev).argsort(dim=1)[:, :k].to(torch.int32), dim=1).values.contiguous()
+        us = one(lambda: st3.st3_gather_rows(list(zip(src, dst)), ns, idx, k, nv, nx), None)
+        rows.append({"call": "st3_gather_rows", "tensors": 3, "n": nv, "k": k, "us": us,
+                     "bytes": 2 * 3 * B * H * (ns + k + nx) * d * eb})
+    for r in rows:
+        r["GBps"] = r["bytes"] / (r["us"] * 1e-6) / 1e9
+    print(json.dumps({"probe": "select", "workload": w.name, "batch": B, "cache_rows": n0, "rows": rows}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -297,6 +386,8 @@ def main():
     def note(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
+    if a.select_probe:
+        return select_probe(w, B, torch, st3)
     if a.prefill_probe:
         return prefill_probe(w, B, keep, torch, pipeline, st3)
     if a.length_probe > 0:

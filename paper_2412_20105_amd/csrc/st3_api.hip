@@ -158,7 +158,7 @@ extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
     EvictArgs ea;
     bool needs_apply = false;
     s = build_evict_args(shape, kv, seg, score_col, id_col, col_stride, keep_after, mode, workspace, workspace_bytes,
-                         1, vis_mass, mass_stride, ea, needs_apply);
+                         1, vis_mass, mass_stride, ea, needs_apply, false);
     if (s != ST3_OK) return s;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     // (1) attention over the cache plus the new token, whose row is read from k_new/v_new and stored on the way
@@ -196,7 +196,7 @@ extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
         // a lazy layer's mass is its source's: finished from the logits in the source's workspace
         const st3_layer_step* S = lazy ? &layers[L.inherit_from] : nullptr;
         s = build_evict_args(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_after, mode,
-                             L.workspace, L.workspace_bytes, 1, L.vis_mass, L.mass_stride, plan[i], na,
+                             L.workspace, L.workspace_bytes, 1, L.vis_mass, L.mass_stride, plan[i], na, true,
                              S ? S->workspace : nullptr, S ? S->kv.capacity : 0);
         if (s != ST3_OK) return s;
         needs_apply[i] = na ? 1 : 0;

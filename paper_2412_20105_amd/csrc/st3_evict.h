@@ -307,11 +307,12 @@ __device__ __forceinline__ void evict_plan_body(const EvictArgs& a, int b, SelSh
 // after the plan (evictions too large for the plan workgroup to move, or STABLE mode).
 // kv->k may be null (a layer that caches V only).  mass_workspace (null: `workspace`) is the
 // workspace whose attend launch left the logits the mass is finished from - a lazy layer's
-// source - and mass_capacity that cache's capacity.
+// source - and mass_capacity that cache's capacity.  batched: the plan will share its launch with
+// the plans of other layers (decides how many row moves the plan workgroup does itself).
 st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                             float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count, int32_t mode,
                             void* workspace, size_t workspace_bytes, int appended, float* mass_dst,
-                            int64_t mass_stride, EvictArgs& ea, bool& needs_apply,
+                            int64_t mass_stride, EvictArgs& ea, bool& needs_apply, bool batched,
                             const void* mass_workspace = nullptr, int32_t mass_capacity = 0);
 void launch_evict_plan(const EvictArgs& ea, int B, hipStream_t st);
 // Plans of n layers (device work of one decode step) with one launch per kPlanBatch layers.

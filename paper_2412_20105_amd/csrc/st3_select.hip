@@ -244,16 +244,22 @@ __global__ __launch_bounds__(256) void evict_apply_kernel(ApplyArgs a) {
 st3_status validate_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
 st3_status validate_kv_value_only(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_segments* seg);
 
-// Rows are moved inside the plan kernel when the mode is HOLE_FILL and at most kInlineEvict rows
-// can be evicted per sequence (one workgroup then moves at most ~100 rows on each strip); larger
-// evictions and STABLE mode go through evict_apply_kernel, which has a workgroup per strip.
-constexpr int kInlineEvict = 48;
+// Rows are moved inside the plan kernel when the mode is HOLE_FILL and few rows can be evicted per
+// sequence; larger evictions and STABLE mode go through evict_apply_kernel, which has a workgroup
+// per strip but is a launch of its own per layer.  A plan workgroup moves a row on all 2*H strips in
+// about 2 us (measured, H = 40, bf16 d = 128), a plan + apply pair costs about 10 us more than a plan
+// alone: so up to 48 evicted rows stay in the plan when the plans of many layers share a launch
+// (the apply launches they save are per layer), and only a handful when a layer is planned alone
+// (each evicted row is one move with a fixed tail, two without).
+constexpr int kInlineEvictBatched = 48;
+constexpr int kInlineEvictAloneFixedTail = 8;
+constexpr int kInlineEvictAlone = 4;
 
 st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                             float* score_col, int32_t* id_col, int64_t col_stride, int32_t keep_count, int32_t mode,
                             void* workspace, size_t workspace_bytes, int appended, float* mass_dst,
-                            int64_t mass_stride, EvictArgs& ea, bool& needs_apply, const void* mass_workspace,
-                            int32_t mass_capacity) {
+                            int64_t mass_stride, EvictArgs& ea, bool& needs_apply, bool batched,
+                            const void* mass_workspace, int32_t mass_capacity) {
     const int B = shape->batch, H = shape->heads, D = shape->head_dim;
     if (seg->max_vis_len > kSelLdsKeys) return ST3_ERR_UNSUPPORTED;
     const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
@@ -270,7 +276,9 @@ st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv,
     ea.moves = reinterpret_cast<int32_t*>(ws + wl.moves);
     ea.max_moves = wl.max_moves;
     ea.appended = appended; ea.capacity = kv->capacity;
-    ea.inline_apply = evicting && mode == ST3_HOLE_FILL && (seg->max_vis_len - keep_count) <= kInlineEvict;
+    const int inline_limit = batched ? kInlineEvictBatched
+                                     : (seg->tail_start != nullptr ? kInlineEvictAloneFixedTail : kInlineEvictAlone);
+    ea.inline_apply = evicting && mode == ST3_HOLE_FILL && (seg->max_vis_len - keep_count) <= inline_limit;
     ea.k = reinterpret_cast<char*>(kv->k); ea.v = reinterpret_cast<char*>(kv->v);
     ea.stride_b = kv->stride_b * eb; ea.stride_h = kv->stride_h * eb; ea.stride_t = kv->stride_t * eb;
     ea.H = H; ea.vecs_per_row = D * eb / 16;
@@ -335,7 +343,7 @@ st3_status enqueue_select_compact(const st3_attn_shape* shape, const st3_kv_laye
     EvictArgs ea;
     bool needs_apply = false;
     st3_status s = build_evict_args(shape, kv, seg, score_col, id_col, col_stride, keep_count, mode, workspace,
-                                    workspace_bytes, appended, mass_dst, mass_stride, ea, needs_apply);
+                                    workspace_bytes, appended, mass_dst, mass_stride, ea, needs_apply, false);
     if (s != ST3_OK) return s;
     launch_evict_plan(ea, shape->batch, st);
     if (needs_apply) launch_evict_apply(ea, shape->batch, st);

@@ -47,3 +47,14 @@ def test_bench_side_configurations_run():
                  "--no-unpruned", *flags)
         assert r.returncode == 0, (flags, r.stderr[-2000:])
         assert json.loads(r.stdout.splitlines()[-1])["value"] > 0
+    r = _run("--batch", "2", "--decode-steps", "4", "--steps", "1", "--warmup", "0", "--no-cpu-baseline",
+             "--no-unpruned", "--contiguous-tail")
+    assert r.returncode == 0 and json.loads(r.stdout.splitlines()[-1])["config"]["tail"] == "contiguous", r.stderr[-2000:]
+
+
+def test_bench_select_probe_runs():
+    r = _run("--select-probe", "--batch", "2")
+    assert r.returncode == 0, r.stderr[-2000:]
+    rows = json.loads(r.stdout.splitlines()[-1])["rows"]
+    assert {x["call"] for x in rows} == {"st3_select_topk", "st3_select_compact_layer", "st3_gather_rows"}
+    assert all(x["us"] > 0 and x["bytes"] >= 0 for x in rows)
