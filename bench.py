@@ -176,7 +176,7 @@ def pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy=None):
     benchmark (first T steps), preceded by a device-to-device copy of exactly 1 GiB whose counter
     reading calibrates the counter's unit."""
     lazy = dict(lazy or {})
-    job = Job(w, B, T, keep, torch, pipeline, st3, lazy=lazy)
+    job = Job(w, B, T, keep, torch, pipeline, st3, lazy=lazy, kv_format=a.kv_format, fixed_tail=not a.contiguous_tail)
     job.run_prefill_only()
     n = 1 << 30
     src = torch.empty((n,), dtype=torch.uint8, device="cuda:0")
@@ -191,14 +191,15 @@ def pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy=None):
     e = 2 if w.dtype == "bf16" else 4
     per_launch, per_lazy = [], []
     hd = w.heads * w.head_dim * e
+    hd_kv = w.heads * w.head_dim * (1 if a.kv_format == "e4m3" else e)      # one cached row over all heads
     for t in range(1, T + 1):
         for l in range(w.layers):
             lkv = w.n_sys + keep[l][t] + w.n_txt + t
             if l in lazy:       # V rows once, one logit per (head, key), v_new in, o out
-                per_lazy.append(B * (hd * lkv + 4 * w.heads * lkv + 2 * hd))
+                per_lazy.append(B * (hd_kv * lkv + 4 * w.heads * lkv + 2 * hd))
             else:
-                per_launch.append(B * (2 * hd * lkv + 2 * hd + 4 * keep[l][t]))
-    print(json.dumps({"probe": "pmc", "workload": w.name, "batch": B, "decode_steps": T,
+                per_launch.append(B * (2 * hd_kv * lkv + 2 * hd + 4 * keep[l][t]))
+    print(json.dumps({"probe": "pmc", "workload": w.name, "batch": B, "decode_steps": T, "kv_format": a.kv_format,
                       "copy_bytes_read": n, "copy_bytes_written": n,
                       "attend_launches": len(per_launch), "alg_bytes_per_launch_mean": sum(per_launch) / len(per_launch),
                       "alg_bytes_first_launches": per_launch[:8],
