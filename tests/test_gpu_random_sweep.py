@@ -119,3 +119,37 @@ def test_decode_layer_step_random_cases(block):
                 assert srcs == src.tolist(), (seed, b)
             for j, r in enumerate(srcs):
                 assert np.array_equal(got_tail_K[:, j], rowK(r)) and np.array_equal(got_tail_V[:, j], rowV(r)), (seed, b, j)
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_prefill_attention_random_cases(block):
+    """Prompt lengths around the tile edges of both prefill kernels (128 queries, 64 keys), every
+    window, visual segments anywhere in the prompt, K and V as strided views of a larger cache."""
+    for seed in range(block * 6, block * 6 + 6):
+        rng = np.random.default_rng(9000 + seed)
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        D = int(rng.choice([64, 128]))
+        B, H = int(rng.integers(1, 3)), int(rng.choice([1, 2, 5]))
+        n = int(rng.choice([1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 192, 193, 255, 256, 257,
+                            int(rng.integers(1, 600))]))
+        ns = int(rng.integers(0, n + 1))
+        nv = int(rng.integers(0, n - ns + 1))
+        W = int(rng.integers(1, min(n, 16) + 1))
+        print(f"prefill sweep seed={seed} dtype={dtype} D={D} B={B} H={H} n={n} ns={ns} nv={nv} W={W}", flush=True)
+        sigma = 1.0 if dtype == "f32" else 1.43
+        Q, K, V = (rand_values(rng, (B, H, n, D), dtype, sigma) for _ in range(3))
+        shape = st3.make_shape(B, H, D, CODE[dtype])
+        cap = n + int(rng.integers(0, 9))
+        dK = torch.full((B, H, cap, D), float("nan"), dtype=TORCH_DTYPE[dtype], device=DEV); dK[:, :, :n] = to_dev(K, dtype)
+        dV = torch.full((B, H, cap, D), float("nan"), dtype=TORCH_DTYPE[dtype], device=DEV); dV[:, :, :n] = to_dev(V, dtype)
+        out = torch.zeros((B, H, n, D), dtype=TORCH_DTYPE[dtype], device=DEV)
+        mass = torch.full((B, nv + 2), -3.0, dtype=torch.float32, device=DEV)
+        n_ws = st3.st3_workspace_bytes(shape, cap, nv, W)
+        ws = torch.empty((n_ws,), dtype=torch.uint8, device=DEV); ws.fill_(0xFF)
+        st3.st3_workspace_init(shape, cap, ws)
+        st3.st3_prefill_attention(shape, to_dev(Q, dtype), dK[:, :, :n], dV[:, :, :n], n, ns, nv, W, out, mass, ws)
+        torch.cuda.synchronize()
+        O, m = orc.prefill_attention(Q, K, V, ns, nv, W)
+        assert_attention_close(to_np64(out), O, dtype, f"seed={seed}")
+        assert_mass_close(to_np64(mass)[:, :nv], m, f"seed={seed}")
+        assert np.all(to_np64(mass)[:, nv:] == -3.0)
