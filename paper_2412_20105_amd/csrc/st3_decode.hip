@@ -20,13 +20,12 @@
 // write-back and invalidate of the XCD-private L2 on this part and were measured to be ruinous.
 #include <hip/hip_ext.h>
 
+#include <cmath>
+
 #include "st3_common.h"
 #include "st3_attend.h"
 #include "st3_decode.h"
 
-#ifndef ST3_DECODE_U
-#define ST3_DECODE_U 8              // 16-byte loads of K (and of V) in flight per lane and tile
-#endif
 #ifndef ST3_DECODE_THREADS
 #define ST3_DECODE_THREADS 256      // threads per workgroup of the attend kernel
 #endif
@@ -478,15 +477,59 @@ __global__ void bump_len_kernel(int32_t* kv_len, int32_t B, int32_t capacity) {
     if (b < B && kv_len[b] >= 0 && kv_len[b] < capacity) kv_len[b] += 1;
 }
 
-// Loads in flight per lane and tile: 8 for two- and four-byte cache elements; 4 for E4M3, whose rows
-// are half as long, so that a tile stays at 32 rows and a wave gets as many tiles to pipeline
-// (measured on the 13B shape: 41 us per launch against 48 us with 8).
-template <typename KT> constexpr int attend_u() { return sizeof(KT) == 1 ? ST3_DECODE_U / 2 : ST3_DECODE_U; }
+// ---------------------------------------------------------------------------------------------
+// Tile size (U = 16-byte loads of K, and of V, in flight per lane and tile).  A tile of 8 KB per wave
+// (U = 4: 16 bf16 rows, 32 E4M3 rows) is the fastest whenever every workgroup of the launch is
+// resident at once: it leaves room for four workgroups per compute unit and pipelines short strips
+// in finer steps (measured at B*H = 40 ... 640 strips: 5-9 % faster than U = 8).  With more
+// workgroups than the device holds, what counts is how full the last round of workgroups is, and
+// larger tiles (fewer, fatter workgroups per unit) can divide the launch more evenly: B*H = 1280
+// runs 1.25 rounds at U = 4 (slowest), 1.67 at U = 6 (fastest), 2.5 at U = 8.  So the launcher asks
+// the runtime how many workgroups of each build fit and takes the one that wastes least of its last
+// round, preferring the smaller tile on ties.
+// ---------------------------------------------------------------------------------------------
+int compute_units() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
 
-template <typename T, typename KT, int D>
-void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
+// Workgroups of `kernel` (256 threads, no dynamic LDS) the current device holds at once.
+template <typename K>
+int resident_workgroups(K kernel, int* cache) {
+    if (*cache == 0) {
+        int per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kDecodeThreads, 0) != hipSuccess || per_cu < 1)
+            per_cu = 1;
+        *cache = per_cu * compute_units();
+    }
+    return *cache;
+}
+
+// Time of a launch of `items` equal workgroups on `slots` concurrent ones, relative to a launch whose
+// last round is full.
+inline double last_round_cost(int64_t items, int slots) {
+    const double rounds = (double)items / (double)slots;
+    return rounds <= 1.0 ? 1.0 : std::ceil(rounds) / rounds;
+}
+
+// Index of the cheapest of n candidates (ordered by preference: the first wins ties).
+inline int cheapest(const double* cost, int n) {
+    int best = 0;
+    for (int i = 1; i < n; ++i)
+        if (cost[i] < cost[best] - 1e-9) best = i;
+    return best;
+}
+
+template <typename T, typename KT, int D, int U>
+void launch_attend_u(const DecodeArgs& da, int B, hipStream_t st) {
     const dim3 grid(da.nsplit, da.H, B);
-    constexpr int U = attend_u<KT>();
     hipEvent_t e0, e1;
     if (profile_take(&e0, &e1))     // timed launch: the events receive the kernel's own start and end
         hipExtLaunchKernelGGL((decode_attend_kernel<T, KT, D, U>), grid, dim3(kDecodeThreads), 0, st, e0, e1, 0, da);
@@ -495,8 +538,35 @@ void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
 }
 
 template <typename T, typename KT, int D>
+void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
+    static int slots[3] = {0, 0, 0};
+    const int64_t items = (int64_t)da.nsplit * da.H * B;
+    const double cost[3] = {
+        last_round_cost(items, resident_workgroups(decode_attend_kernel<T, KT, D, 4>, &slots[0])),
+        last_round_cost(items, resident_workgroups(decode_attend_kernel<T, KT, D, 6>, &slots[1])),
+        last_round_cost(items, resident_workgroups(decode_attend_kernel<T, KT, D, 8>, &slots[2]))};
+    switch (cheapest(cost, 3)) {
+        case 0: launch_attend_u<T, KT, D, 4>(da, B, st); break;
+        case 1: launch_attend_u<T, KT, D, 6>(da, B, st); break;
+        default: launch_attend_u<T, KT, D, 8>(da, B, st); break;
+    }
+}
+
+// The V-only kernel has the registers for twice as many loads per tile (same bytes per tile).
+template <typename T, typename KT, int D>
 void launch_inherit(const InheritArgs& ia, int B, hipStream_t st) {
-    decode_inherit_kernel<T, KT, D, 2 * ST3_DECODE_U><<<dim3(ia.nsplit, ia.H, B), kDecodeThreads, 0, st>>>(ia);
+    static int slots[3] = {0, 0, 0};
+    const int64_t items = (int64_t)ia.nsplit * ia.H * B;
+    const double cost[3] = {
+        last_round_cost(items, resident_workgroups(decode_inherit_kernel<T, KT, D, 8>, &slots[0])),
+        last_round_cost(items, resident_workgroups(decode_inherit_kernel<T, KT, D, 12>, &slots[1])),
+        last_round_cost(items, resident_workgroups(decode_inherit_kernel<T, KT, D, 16>, &slots[2]))};
+    const dim3 grid(ia.nsplit, ia.H, B);
+    switch (cheapest(cost, 3)) {
+        case 0: decode_inherit_kernel<T, KT, D, 8><<<grid, kDecodeThreads, 0, st>>>(ia); break;
+        case 1: decode_inherit_kernel<T, KT, D, 12><<<grid, kDecodeThreads, 0, st>>>(ia); break;
+        default: decode_inherit_kernel<T, KT, D, 16><<<grid, kDecodeThreads, 0, st>>>(ia); break;
+    }
 }
 
 template <typename T, int D>
