@@ -21,6 +21,7 @@
 #include <hip/hip_ext.h>
 
 #include <cmath>
+#include <utility>
 
 #include "st3_common.h"
 #include "st3_attend.h"
@@ -478,15 +479,16 @@ __global__ void bump_len_kernel(int32_t* kv_len, int32_t B, int32_t capacity) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Tile size (U = 16-byte loads of K, and of V, in flight per lane and tile).  A tile of 8 KB per wave
-// (U = 4: 16 bf16 rows, 32 E4M3 rows) is the fastest whenever every workgroup of the launch is
-// resident at once: it leaves room for four workgroups per compute unit and pipelines short strips
-// in finer steps (measured at B*H = 40 ... 640 strips: 5-9 % faster than U = 8).  With more
-// workgroups than the device holds, what counts is how full the last round of workgroups is, and
-// larger tiles (fewer, fatter workgroups per unit) can divide the launch more evenly: B*H = 1280
-// runs 1.25 rounds at U = 4 (slowest), 1.67 at U = 6 (fastest), 2.5 at U = 8.  So the launcher asks
-// the runtime how many workgroups of each build fit and takes the one that wastes least of its last
-// round, preferring the smaller tile on ties.
+// Tile size (U = 16-byte loads of K, and of V, in flight per lane and tile; a wave-wide load is 1 KB).
+// While every workgroup of a launch is resident at once, a tile of 8 KB per wave is the fastest for
+// two- and four-byte caches (U = 4: 16 bf16 rows; room for four workgroups per compute unit, short
+// strips pipelined in finer steps: 5-9 % faster than U = 8 at B*H = 40 ... 640 strips), 6 KB for E4M3
+// (U = 3: 24 rows).  With more workgroups than the device holds, what counts is how full the last
+// round of workgroups is: B*H = 1280 bf16 strips are 1.25 rounds at U = 4 (slowest), 1.67 at U = 6,
+// 2.5 at U = 8, and fit at once at U = 1 (66 registers, seven workgroups per unit: fastest, though
+// much the slowest build for small launches).  So the launcher asks the runtime how many workgroups
+// of each build the device holds and takes the build that wastes least of its last round; the
+// candidate lists below are in order of preference for ties.
 // ---------------------------------------------------------------------------------------------
 int compute_units() {
     static int cached[64] = {0};
@@ -537,19 +539,24 @@ void launch_attend_u(const DecodeArgs& da, int B, hipStream_t st) {
         decode_attend_kernel<T, KT, D, U><<<grid, kDecodeThreads, 0, st>>>(da);
 }
 
+// Takes the cheapest of the builds Us... (in order of preference) for this launch.
+template <typename T, typename KT, int D, int... Us>
+void launch_attend_best(const DecodeArgs& da, int B, hipStream_t st, std::integer_sequence<int, Us...>) {
+    constexpr int N = sizeof...(Us);
+    static int slots[N] = {};
+    const int us[N] = {Us...};
+    const int64_t items = (int64_t)da.nsplit * da.H * B;
+    double cost[N];
+    int i = 0;
+    ((cost[i] = last_round_cost(items, resident_workgroups(decode_attend_kernel<T, KT, D, Us>, &slots[i])), ++i), ...);
+    const int pick = us[cheapest(cost, N)];
+    ((pick == Us ? (launch_attend_u<T, KT, D, Us>(da, B, st), 0) : 0), ...);
+}
+
 template <typename T, typename KT, int D>
 void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
-    static int slots[3] = {0, 0, 0};
-    const int64_t items = (int64_t)da.nsplit * da.H * B;
-    const double cost[3] = {
-        last_round_cost(items, resident_workgroups(decode_attend_kernel<T, KT, D, 4>, &slots[0])),
-        last_round_cost(items, resident_workgroups(decode_attend_kernel<T, KT, D, 6>, &slots[1])),
-        last_round_cost(items, resident_workgroups(decode_attend_kernel<T, KT, D, 8>, &slots[2]))};
-    switch (cheapest(cost, 3)) {
-        case 0: launch_attend_u<T, KT, D, 4>(da, B, st); break;
-        case 1: launch_attend_u<T, KT, D, 6>(da, B, st); break;
-        default: launch_attend_u<T, KT, D, 8>(da, B, st); break;
-    }
+    if constexpr (sizeof(KT) == 1) launch_attend_best<T, KT, D>(da, B, st, std::integer_sequence<int, 3, 4, 1>{});
+    else launch_attend_best<T, KT, D>(da, B, st, std::integer_sequence<int, 4, 6, 8, 1>{});
 }
 
 // The V-only kernel has the registers for twice as many loads per tile (same bytes per tile).
