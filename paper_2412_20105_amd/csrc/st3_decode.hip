@@ -559,21 +559,12 @@ void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
     else launch_attend_best<T, KT, D>(da, B, st, std::integer_sequence<int, 4, 6, 8, 1>{});
 }
 
-// The V-only kernel has the registers for twice as many loads per tile (same bytes per tile).
+// The V-only kernel of lazy layers: 4 loads per lane and tile (4 KB per wave) were the fastest or
+// within 2 % of it at every batch size and for both cache formats (8, 12 and 16 loads lose up to
+// 17 % where the launch has more workgroups than fit at once; 2 loads lose at small batches).
 template <typename T, typename KT, int D>
 void launch_inherit(const InheritArgs& ia, int B, hipStream_t st) {
-    static int slots[3] = {0, 0, 0};
-    const int64_t items = (int64_t)ia.nsplit * ia.H * B;
-    const double cost[3] = {
-        last_round_cost(items, resident_workgroups(decode_inherit_kernel<T, KT, D, 8>, &slots[0])),
-        last_round_cost(items, resident_workgroups(decode_inherit_kernel<T, KT, D, 12>, &slots[1])),
-        last_round_cost(items, resident_workgroups(decode_inherit_kernel<T, KT, D, 16>, &slots[2]))};
-    const dim3 grid(ia.nsplit, ia.H, B);
-    switch (cheapest(cost, 3)) {
-        case 0: decode_inherit_kernel<T, KT, D, 8><<<grid, kDecodeThreads, 0, st>>>(ia); break;
-        case 1: decode_inherit_kernel<T, KT, D, 12><<<grid, kDecodeThreads, 0, st>>>(ia); break;
-        default: decode_inherit_kernel<T, KT, D, 16><<<grid, kDecodeThreads, 0, st>>>(ia); break;
-    }
+    decode_inherit_kernel<T, KT, D, 4><<<dim3(ia.nsplit, ia.H, B), kDecodeThreads, 0, st>>>(ia);
 }
 
 template <typename T, int D>
