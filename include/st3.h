@@ -408,6 +408,13 @@ ST3_EXPORT st3_status st3_profile_read(double* total_ms, int64_t* launches, doub
  * Process-wide; not for production use. */
 ST3_EXPORT void st3_debug_set_prefill_path(int path);
 
+/* Test hook: the decode attention kernel is built for several tile sizes (16-byte loads of K, and
+ * of V, per lane and tile) and picks one per launch from the launch's size.  tile_loads != 0 makes
+ * every later launch use that build when the cache type has it (plain caches: 1, 4, 6, 8; E4M3:
+ * 1, 3, 4; any other value: automatic choice, as with 0).  Results do not depend on the tile size
+ * beyond float32 rounding order.  Process-wide; lets tests and benchmarks run every build. */
+ST3_EXPORT void st3_debug_set_attend_tile(int tile_loads);
+
 #ifdef __cplusplus
 }
 #endif

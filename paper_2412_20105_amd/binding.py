@@ -31,7 +31,7 @@ EXPORTED = [
     "st3_select_topk",
     "st3_compact_rows", "st3_gather_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
     "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
-    "st3_debug_set_prefill_path", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
+    "st3_debug_set_prefill_path", "st3_debug_set_attend_tile", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
     "st3_cosine_similarity",
 ]
 
@@ -153,6 +153,8 @@ def lib() -> C.CDLL:
         L.st3_profile_read.restype = C.c_int
         L.st3_debug_set_prefill_path.argtypes = [C.c_int]
         L.st3_debug_set_prefill_path.restype = None
+        L.st3_debug_set_attend_tile.argtypes = [C.c_int]
+        L.st3_debug_set_attend_tile.restype = None
         _lib = L
     return _lib
 
@@ -387,3 +389,7 @@ def st3_profile_read():
 
 def st3_debug_set_prefill_path(path: int) -> None:
     lib().st3_debug_set_prefill_path(path)
+
+
+def st3_debug_set_attend_tile(tile_loads: int) -> None:
+    lib().st3_debug_set_attend_tile(tile_loads)

@@ -539,12 +539,18 @@ void launch_attend_u(const DecodeArgs& da, int B, hipStream_t st) {
         decode_attend_kernel<T, KT, D, U><<<grid, kDecodeThreads, 0, st>>>(da);
 }
 
+int g_forced_tile = 0;       // st3_debug_set_attend_tile
+
 // Takes the cheapest of the builds Us... (in order of preference) for this launch.
 template <typename T, typename KT, int D, int... Us>
 void launch_attend_best(const DecodeArgs& da, int B, hipStream_t st, std::integer_sequence<int, Us...>) {
     constexpr int N = sizeof...(Us);
     static int slots[N] = {};
     const int us[N] = {Us...};
+    if (g_forced_tile != 0 && ((g_forced_tile == Us) || ...)) {
+        ((g_forced_tile == Us ? (launch_attend_u<T, KT, D, Us>(da, B, st), 0) : 0), ...);
+        return;
+    }
     const int64_t items = (int64_t)da.nsplit * da.H * B;
     double cost[N];
     int i = 0;
@@ -689,6 +695,8 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     return check_launch();
 }
 
+void set_forced_tile(int u) { g_forced_tile = u; }
+
 st3_status enqueue_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                           const void* k_new, const void* v_new, hipStream_t st) {
     const int B = shape->batch, H = shape->heads;
@@ -756,6 +764,8 @@ st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, 
 }
 
 }  // namespace st3
+
+extern "C" void st3_debug_set_attend_tile(int tile_loads) { st3::set_forced_tile(tile_loads); }
 
 extern "C" st3_status st3_decode_attention(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
                                            const st3_segments* seg, void* out, float* vis_mass, int64_t mass_stride,

@@ -446,8 +446,17 @@ def test_quantize_rows_and_append_give_the_oracles_codes(D):
     (64, 2, 3, [1000, 31], 3, 20),
     (128, 26, 40, [200] * 25 + [77], 35, 100),
 ])
-def test_decode_attention_and_heredity_over_an_e4m3_cache(D, B, H, lens, ns, nv):
-    print(f"e4m3 decode D={D} B={B} H={H} lens={lens[:4]}", flush=True)
+@pytest.mark.parametrize("tile", [0, 1, 3, 4])            # 0: the launcher's own choice; else that build of the attend kernel
+def test_decode_attention_and_heredity_over_an_e4m3_cache(D, B, H, lens, ns, nv, tile):
+    print(f"e4m3 decode D={D} B={B} H={H} lens={lens[:4]} tile={tile}", flush=True)
+    st3.st3_debug_set_attend_tile(tile)
+    try:
+        _e4m3_decode_case(D, B, H, lens, ns, nv)
+    finally:
+        st3.st3_debug_set_attend_tile(0)
+
+
+def _e4m3_decode_case(D, B, H, lens, ns, nv):
     rng = np.random.default_rng(zlib.crc32(repr(("e4m3", D, B, H, lens)).encode()))
     cap = max(lens) + 5
     def codes(shape):

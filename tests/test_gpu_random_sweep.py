@@ -46,7 +46,22 @@ def _case(seed):
 
 @pytest.mark.parametrize("block", range(12))
 def test_decode_layer_step_random_cases(block):
-    for seed in range(block * 10, block * 10 + 10):
+    _run_cases(range(block * 10, block * 10 + 10))
+
+
+@pytest.mark.parametrize("tile", [1, 4, 6, 8])
+def test_decode_layer_step_random_cases_with_every_tile_size(tile):
+    """The attend kernel picks one of its builds (loads per lane and tile) from the size of the launch;
+    small launches like these would only ever reach one of them, so each build is forced in turn."""
+    st3.st3_debug_set_attend_tile(tile)
+    try:
+        _run_cases(range(200, 216))
+    finally:
+        st3.st3_debug_set_attend_tile(0)
+
+
+def _run_cases(seeds):
+    for seed in seeds:
         c = _case(seed)
         print("sweep case", {k: c[k] for k in ("seed", "dtype", "D", "B", "H", "ns", "vis", "fixed", "ts", "lens",
                                                "keep_after", "mode", "hint", "want_mass")}, flush=True)
