@@ -41,7 +41,9 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ p, 
 int main() {
     size_t bytes = (size_t)1 << 30;
     uint4 *a, *b; uint32_t* sink;
-    CK(hipMalloc(&a, bytes)); CK(hipMalloc(&b, bytes)); CK(hipMalloc(&sink, 4));
+    uint4* big;                                        // a and b are the two halves of one allocation
+    CK(hipMalloc(&big, 2 * bytes)); CK(hipMalloc(&sink, 4));
+    a = big; b = big + bytes / 16;
     CK(hipMemset(a, 1, bytes)); CK(hipMemset(b, 2, bytes));
     size_t nvec = bytes / 16;
     hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
@@ -68,16 +70,25 @@ int main() {
         float ms; hipEventElapsedTime(&ms, e0, e1);
         printf("read NT U=8 grid=%7d : %.1f GB/s\n", g, bytes * 10 / (ms * 1e-3) / 1e9);
     }
-    // smaller working sets (like one decode launch: ~400 MB)
-    for (size_t mb : {100, 200, 400}) {
-        size_t nv = mb * 1024 * 1024 / 16;
-        int g = (int)(nv / 256 / 8);
-        hipEventRecord(e0);
-        for (int rep = 0; rep < 20; ++rep) read_kernel<8><<<g, 256>>>(a + (rep % 2) * nv, nv, sink);
-        hipEventRecord(e1); hipEventSynchronize(e1);
-        float ms; hipEventElapsedTime(&ms, e0, e1);
-        printf("read %zu MB per launch, one pass grid=%d : %.1f GB/s (%.1f us/launch)\n", mb, g, (double)nv * 16 * 20 / (ms * 1e-3) / 1e9, ms * 1e3 / 20);
-    }
+    // one decode launch streams 100-800 MB: the same amounts per launch, each launch on the next part of
+    // the 2 GiB so that nothing is found in the 256 MB last-level cache, plain and non-temporal loads
+    for (int nt = 0; nt < 2; ++nt)
+        for (size_t mb : {50, 100, 200, 400, 800}) {
+            size_t nv = mb * 1024 * 1024 / 16;
+            int g = (int)(nv / 256 / 8);
+            const int slots = (int)(2 * nvec / nv), reps = 20;
+            for (int rep = 0; rep < 2; ++rep) read_kernel<8><<<g, 256>>>(big, nv, sink);
+            hipEventRecord(e0);
+            for (int rep = 0; rep < reps; ++rep) {
+                const uint4* src = big + (size_t)(rep % slots) * nv;
+                if (nt) read_nt_kernel<8><<<g, 256>>>((const u32x4_t*)src, nv, sink);
+                else read_kernel<8><<<g, 256>>>(src, nv, sink);
+            }
+            hipEventRecord(e1); hipEventSynchronize(e1);
+            float ms; hipEventElapsedTime(&ms, e0, e1);
+            printf("read%s %zu MiB per launch, grid=%d : %.1f GB/s (%.1f us/launch)\n", nt ? " NT" : "", mb, g,
+                   (double)nv * 16 * reps / (ms * 1e-3) / 1e9, ms * 1e3 / reps);
+        }
     for (int g : {256 * 8, 256 * 32, (int)(nvec / 256)}) {
         hipEventRecord(e0);
         for (int rep = 0; rep < 10; ++rep) copy_kernel<<<g, 256>>>(a, b, nvec);
