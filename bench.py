@@ -6,7 +6,8 @@ progressive visual-token pruning (attention + mass, top-k, stable compaction), t
 steps with visual-token annealing (select-and-compact, append, split-KV attention + mass per
 layer).  value = generated tokens per second = B*T / job time, inputs resident in HBM.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (tokens/s), timing fields, a `roofline` object for the decode attention
+kernel (achieved against the 8 TB/s HBM peak), the unpruned run, KV bytes and a `cpu_baseline` object.
 """
 from __future__ import annotations
 
