@@ -60,6 +60,9 @@ def parse():
     ap.add_argument("--prefill-probe", action="store_true",
                     help="prefill only (all layers with progressive pruning), three passes, for kernel traces and MFMA "
                          "counters of the prefill attention kernel; prints each layer's length and algorithmic flops")
+    ap.add_argument("--attend-tile", type=int, default=0, metavar="U",
+                    help="force one build of the decode attention kernel (16-byte loads per lane and tile: 1, 4, 6, 8; "
+                         "E4M3 caches: 1, 3, 4) instead of the launcher's own choice per launch; 0 = automatic")
     ap.add_argument("--select-probe", action="store_true",
                     help="time the selection and compaction calls alone (top-k, in-place eviction in both modes and both "
                          "cache layouts, the prefill gather) at the workload's shape and print one JSON line")
@@ -388,6 +391,7 @@ def main():
     def note(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
+    st3.st3_debug_set_attend_tile(a.attend_tile)
     if a.select_probe:
         return select_probe(w, B, torch, st3)
     if a.prefill_probe:
@@ -420,7 +424,8 @@ def main():
                                f"schedule {w.layer_schedule}/{w.step_schedule}",
                    "batch": B, "decode_steps": T, "step_definition": "prefill (all layers, PVTP) + T decode steps (VTA)",
                    "lazy_layers": {str(l): s for l, s in sorted(lazy.items())}, "kv_format": a.kv_format,
-                   "tail": "contiguous" if a.contiguous_tail else "fixed offset"},
+                   "tail": "contiguous" if a.contiguous_tail else "fixed offset",
+                   "attend_tile": a.attend_tile or "automatic"},
         "prefill_ms": ms_prefill,
         "decode_ms_per_token_step": (ms_job - ms_prefill) / T,
         "decode_only_tokens_per_s": tokens / ((ms_job - ms_prefill) * 1e-3),

@@ -41,7 +41,7 @@ def test_bench_refuses_more_than_one_gpu():
 
 
 def test_bench_side_configurations_run():
-    for flags in (["--lazy", "36:37-39"], ["--kv-format", "e4m3"],
+    for flags in (["--lazy", "36:37-39"], ["--kv-format", "e4m3"], ["--attend-tile", "8"],
                   ["--layer-schedule", "pvtp", "--stride", "4", "--step-schedule", "exp", "--tau", "3"]):
         r = _run("--batch", "2", "--decode-steps", "4", "--steps", "1", "--warmup", "0", "--no-cpu-baseline",
                  "--no-unpruned", *flags)
