@@ -99,7 +99,6 @@ class Job:
 
     def run(self):
         gen, w = self.gen, self.w
-        gen._inherit = None
         for l in range(w.layers):
             q, k, v = self.pre[l]
             gen.prefill_layer(l, q, k, v)
@@ -108,7 +107,6 @@ class Job:
 
     def run_prefill_only(self):
         gen, w = self.gen, self.w
-        gen._inherit = None
         for l in range(w.layers):
             q, k, v = self.pre[l]
             gen.prefill_layer(l, q, k, v)
@@ -128,6 +126,26 @@ class Job:
                 total += self.B * (2 * w.heads * w.head_dim * ekv * lkv + 2 * w.heads * w.head_dim * e
                                    + 4 * self.keep[l][t])
         return total
+
+
+def committed_traffic(workload, batch, kv_format, alg_bytes_per_launch):
+    """HBM bytes per launch of the decode attention kernel from the committed counter summary
+    (two `rocprofv3 --pmc` runs, FETCH_SIZE then WRITE_SIZE, calibrated by a copy of known size):
+    that run's traffic / algorithmic ratio times this run's algorithmic bytes per launch.  Not
+    measured in this run (counters need the profiler attached): None when no summary covers the
+    workload, and the source is always named next to the number."""
+    tag = f"{workload}_b{batch}" + ("" if kv_format == "plain" else f"_{kv_format}")
+    path = os.path.join("profiles", f"decode_attend_kernel_{tag}_pmc.txt")
+    try:
+        with open(os.path.join(ROOT, path)) as f:
+            for line in f:
+                if line.startswith("traffic / algorithmic ="):
+                    ratio = float(line.split("=")[1].split()[0])
+                    return ratio * alg_bytes_per_launch, (f"not measured in this run: ratio {ratio} of the committed "
+                                                          f"rocprofv3 --pmc summary {path} x this run's algorithmic bytes")
+    except (OSError, ValueError, IndexError):
+        pass
+    return None, "no committed rocprofv3 --pmc summary covers this workload"
 
 
 def timed(torch, fn, reps):
@@ -442,17 +460,9 @@ def main():
         tot_ms, cnt, mn, mx = st3.st3_profile_read()
         alg = job.decode_kernel_bytes()
         achieved = alg / (tot_ms * 1e-3) / 1e9 if tot_ms > 0 else 0.0
-        traffic = None
-        try:        # HBM bytes per launch from the committed counter runs, when they cover this workload
-            with open(os.path.join(ROOT, "paper_2412_20105_amd", "measured_traffic.json")) as f:
-                mt = json.load(f)["decode_attend_kernel"]
-            if mt["workload"] == w.name and mt["batch"] == B and a.kv_format == "plain":
-                # measured over the first decode steps: scale the ratio to this job's mean launch
-                traffic = mt["traffic_over_algorithmic"] * alg / max(cnt, 1)
-        except (OSError, KeyError, ValueError):
-            traffic = None
+        traffic, traffic_source = committed_traffic(w.name, B, a.kv_format, alg / max(cnt, 1))
         result["roofline"] = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                              "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                               "kernel": "decode_attend_kernel", "launches": cnt,
                               "avg_launch_us": tot_ms * 1e3 / max(cnt, 1), "min_us": mn * 1e3, "max_us": mx * 1e3,
                               "alg_bytes_per_launch": alg / max(cnt, 1),

@@ -226,9 +226,12 @@ ST3_EXPORT st3_status st3_select_topk(const float* scores, int64_t score_stride,
  * Stable in-place row compaction (Alg. 1/3: V = V[T]; X = [S, V, I] rebuilt, order preserved).
  * For every (b, i) with b < batch, i < inner, on the strip that starts at
  * rows + b*stride_b_bytes + i*stride_inner_bytes:
- *   row[r] <- row[keep_idx[b][r]]   for r in [0, k)      (keep_idx row b at keep_idx + b*idx_stride,
- *                                                          ascending; entries outside [0, n) are skipped)
- *   row[k_b + j] <- row[n + j]      for j in [0, tail_rows)   (k_b = number of valid indices)
+ *   row[r] <- row[keep_idx[b][r]]   for r in [0, k_b)    (keep_idx row b at keep_idx + b*idx_stride,
+ *                                                          ascending)
+ *   row[k_b + j] <- row[n + j]      for j in [0, tail_rows)
+ * where k_b <= k is the length of the leading run of entries inside [0, n): an index list is its
+ * valid entries followed by padding (the -1 entries st3_select_topk appends for a row with fewer
+ * than k candidates); whatever follows the first entry outside [0, n) is ignored.
  * Rows are row_bytes long (multiple of 4), stride_row_bytes apart.  Used for Q/K/V rows of a
  * layer's input, hidden rows, and the score / id columns (row_bytes = 4).
  * ------------------------------------------------------------------------------------------- */
@@ -330,7 +333,8 @@ typedef struct {
                                        source layer: q and k_new are ignored, kv.k may be NULL, the attention
                                        applies the source's probabilities of this step to kv.v and v_new.
                                        The source must be an ordinary layer with the same sys_len, max_*
-                                       bounds and keep_after; score_col/id_col/lengths are this layer's own
+                                       bounds and keep_after, and must pass a vis_mass of its own when
+                                       this layer passes one; score_col/id_col/lengths are this layer's own
                                        copies and must equal the source's, so that both evict alike.
                                        vis_mass (may be NULL) receives the source's mass. */
     const void*  q;
@@ -350,9 +354,9 @@ ST3_EXPORT st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
  * Retention schedules: HOST-only pure functions that fill integer tables.
  * ------------------------------------------------------------------------------------------- */
 
-/* Strided progressive pruning (Sec. 3.2 "avoid pruning in the first three layers"; Alg. 1
- * condition l >= 3 and (l-3) % S == 0; Eq. 9 with P the first event's ratio and R each later
- * event's, both relative to the original count).  Ratios in basis points.  keep_l: HOST [L]. */
+/* Strided progressive pruning (Sec. 3.2: layers 0..2 keep every visual token; Alg. 1: prune
+ * events at layers l >= 3 with (l-3) % S == 0; Eq. 9 with P the first event's ratio and R each
+ * later event's, both relative to the original count).  Ratios in basis points.  keep_l: HOST [L]. */
 ST3_EXPORT st3_status st3_schedule_pvtp(int32_t L, int32_t n_vis, int32_t first_layer, int32_t stride_S,
                              int32_t P_bp, int32_t R_bp, int32_t* keep_l);
 

@@ -59,18 +59,5 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
-PROBE_PATH = os.path.join(HERE, "bw_probe")
-
-
-def build_probe() -> str:
-    """Stand-alone HBM read / copy bandwidth probe (reference for the decode kernel's roofline)."""
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-O3", "-w", os.path.join(CSRC, "bw_probe.hip"), "-o", PROBE_PATH]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed on bw_probe.hip:\n{r.stdout}\n{r.stderr}")
-    return PROBE_PATH
-
-
 if __name__ == "__main__":
     print(build_library(verbose=True))
-    print(build_probe())

@@ -130,6 +130,9 @@ static st3_status check_lazy_step(const st3_attn_shape* shape, const st3_layer_s
         L.seg.max_kv_len != S.seg.max_kv_len || L.keep_after != S.keep_after)
         return ST3_ERR_INVALID_ARG;                                      // both must hold and evict the same rows
     if (L.vis_mass && L.mass_stride < L.seg.max_vis_len) return ST3_ERR_INVALID_ARG;
+    // the lazy layer's mass is finished from what the source's attend launch marks pending, and
+    // that launch only does so when the source asks for its own mass
+    if (L.vis_mass && !S.vis_mass) return ST3_ERR_INVALID_ARG;
     if (L.keep_after >= 0) {
         if (!L.score_col || !L.id_col || L.col_stride < L.seg.max_vis_len) return ST3_ERR_INVALID_ARG;
         if (L.score_col == S.score_col || L.id_col == S.id_col) return ST3_ERR_INVALID_ARG;  // own copies

@@ -88,14 +88,15 @@ __global__ __launch_bounds__(256) void compact_rows_kernel(CompactArgs a) {
     __shared__ int sm_cnt[4];
     const int tid = threadIdx.x, b = blockIdx.z;
     const int32_t* idx = a.idx + (int64_t)b * a.idx_stride;
-    // number of leading valid indices (0 <= idx < n)
-    int local = 0;
-    for (int i = tid; i < a.k; i += 256) local += (idx[i] >= 0 && idx[i] < a.n) ? 1 : 0;
+    // length of the leading run of valid indices (0 <= idx < n): position of the first invalid entry
+    int local = a.k;
+    for (int i = tid; i < a.k; i += 256)
+        if (idx[i] < 0 || idx[i] >= a.n) { local = i; break; }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) local += __shfl_xor(local, off);
+    for (int off = 32; off > 0; off >>= 1) local = min(local, __shfl_xor(local, off));
     if (tid % kWave == 0) sm_cnt[tid / kWave] = local;
     __syncthreads();
-    if (tid == 0) sm_kb = sm_cnt[0] + sm_cnt[1] + sm_cnt[2] + sm_cnt[3];
+    if (tid == 0) sm_kb = min(min(sm_cnt[0], sm_cnt[1]), min(sm_cnt[2], sm_cnt[3]));
     __syncthreads();
     const int kb = sm_kb;
     const int total = kb + a.tail;

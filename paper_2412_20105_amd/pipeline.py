@@ -139,8 +139,10 @@ class Generation:
         src = self.lazy.get(l)
         B, ns, nv, nx = self.B, self.n_sys, self.n_vis, self.n_txt
         k_l = self.keep[l][0]
-        if l == 0:
+        if l == 0:                  # a new job: nothing is inherited from the previous one
             self._alive = nv
+            self._inherit = None
+            self._decoding = False
             lc.ids[:, :nv] = torch.arange(nv, dtype=torch.int32, device=self.device)
         else:
             prev = self.layers[l - 1]

@@ -45,19 +45,46 @@ def _plant_on_device(w, q, k):
     return qf, kb
 
 
-@pytest.mark.parametrize("name,batch,sample_b,oracle_layers,T", [
-    ("llava15_13b", 32, 17, 40, 3),
-    ("llava15_7b", 16, 5, 32, 2),
-    ("skewed_13b", 64, 41, 12, 2),
-    ("llava_next_hr", 8, 3, 5, 2),
-])
-def test_full_shape_one_sequence_replayed_by_oracle(name, batch, sample_b, oracle_layers, T):
+# name, batch, sampled sequence, layers the oracle replays, decode steps, options
+#   tau:     cosine annealing over that many steps instead of the workload's (tau <= T empties the
+#            visual segments: the last steps attend behind a dead gap as long as the layer's prefill keep)
+#   kv:      "e4m3" - caches in FP8 E4M3, scale 6 sigma / 448 per strip
+#   lazy:    QK-heredity groups {lazy layer: source}
+CASES = [
+    ("llava15_13b", 32, 17, 40, 3, {}),
+    ("llava15_7b", 16, 5, 32, 2, {}),
+    ("skewed_13b", 64, 41, 12, 2, {}),
+    ("llava_next_hr", 8, 3, 5, 2, {}),
+    # the named batches whose strips are cut into chunks (B*H < 256): chunk partials + merge + hints
+    ("llava15_13b", 1, 0, 10, 3, {}),
+    ("llava15_13b", 8, 6, 10, 3, {}),
+    ("llava15_7b", 1, 0, 10, 3, {}),
+    # the late state of a job at the benchmark's launch geometry (B*H = 1280): visual segments shrink to
+    # nothing within 6 steps and the tail sits behind a gap of up to 576 dead rows
+    ("llava15_13b", 32, 9, 8, 6, {"tau": 6}),
+    ("llava15_13b", 32, 21, 6, 2, {"kv": "e4m3"}),
+    ("llava15_7b", 16, 11, 32, 2, {"lazy": {29: 28, 30: 28, 31: 28}}),
+]
+
+
+@pytest.mark.parametrize("name,batch,sample_b,oracle_layers,T,opt", CASES,
+                         ids=[f"{c[0]}-B{c[1]}" + "".join(f"-{k}" for k in c[5]) for c in CASES])
+def test_full_shape_one_sequence_replayed_by_oracle(name, batch, sample_b, oracle_layers, T, opt):
+    import dataclasses
     w = get_workload(name)
+    if "tau" in opt:
+        w = dataclasses.replace(w, steps=T, step_schedule={"kind": "cos", "tau": opt["tau"]})
+    lazy = dict(opt.get("lazy", {}))
+    kv_scale = 6 * w.sigma / 448 if opt.get("kv") == "e4m3" else None
     keep_full = pipeline.keep_table_for(w)
-    assert np.array_equal(np.array(keep_full), orc.schedule_for(w))
+    keep_orc = orc.schedule_for(w)
+    assert np.array_equal(np.array(keep_full), keep_orc)
+    for l, src in lazy.items():                       # a lazy layer holds what its source holds
+        keep_full[l] = list(keep_full[src])
+        keep_orc[l] = keep_orc[src]
     keep = [row[:T + 1] for row in keep_full[:oracle_layers]]
     gen = pipeline.Generation(w.layers, w.heads, w.head_dim, torch.bfloat16, batch, w.n_sys, w.n_vis, w.n_txt,
-                              w.steps, keep_full, device=DEV)
+                              w.steps, keep_full, device=DEV, lazy=lazy, kv_scale=kv_scale)
     g = torch.Generator(device=DEV)
     g.manual_seed(20241227)
     shape_p = (batch, w.heads, w.n_prompt, w.head_dim)
@@ -104,7 +131,12 @@ def test_full_shape_one_sequence_replayed_by_oracle(name, batch, sample_b, oracl
 
     # ---- the oracle replays the sampled sequence from the original inputs -----------------------
     print(f"{name}: oracle replay of sequence {sample_b} ({LO} layers, prefill + {T} decode steps)", flush=True)
-    ref = orc.Generation(LO, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, np.array(keep))
+    fp8 = {}
+    if kv_scale is not None:
+        fp8 = dict(kv_format="e4m3", k_scale=np.full((1, w.heads), kv_scale, np.float32),
+                   v_scale=np.full((1, w.heads), kv_scale, np.float32))
+    ref = orc.Generation(LO, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, np.array(keep),
+                         lazy={l: s_ for l, s_ in lazy.items() if l < LO}, **fp8)
     r = ref.prefill(lambda l: pre_host[l])
     n_alive = LO                                      # layers before a near-tie went the other way
     for l in range(LO):
@@ -123,20 +155,26 @@ def test_full_shape_one_sequence_replayed_by_oracle(name, batch, sample_b, oracl
         assert n_alive == LO, "prefill selection diverged on a near-tie; pick another sampled sequence"
     ok = np.zeros(LO, bool)
     ok[:n_alive] = True
+    compared = 0
     for t in range(1, T + 1):
         rho_before = [ref.rho[l][0].copy() for l in range(LO)]
         ids_before = [ref.ids[l][0].copy() for l in range(LO)]
         s = ref.decode_step(lambda l: (dec_host[t - 1][l, 0], dec_host[t - 1][l, 1], dec_host[t - 1][l, 2]))
         for l in range(LO):
             ids = step_ids[t - 1][l]
-            if ok[l]:
+            assert len(ids) == keep[l][t]
+            if ok[l] and keep[l][t] > 0:
                 ok[l] = assert_selection_matches(ids, rho_before[l], ids_before[l], keep[l][t], f"t={t} l={l}")
             if not ok[l]:
                 continue
             assert_attention_close(step_out[t - 1][l], s["out"][l][0], "bf16", f"decode out t={t} l={l}")
             pos = np.searchsorted(s["ids"][l][0], ids)
             assert_mass_close(step_mass[t - 1][l][:len(ids)], s["mass"][l][0][pos], f"decode mass t={t} l={l}")
+            compared += 1
+    total = LO * T
+    print(f"{name} B={batch} {opt}: decode outputs and masses compared on {compared} of {total} (layer, step) pairs of "
+          f"sequence {sample_b}; prefill on {n_alive} of {LO} layers", flush=True)
     if not w.planted:
-        assert ok.mean() > 0.8
+        assert compared >= 0.8 * total, f"only {compared} of {total} (layer, step) pairs were compared"
     del gen
     torch.cuda.empty_cache()

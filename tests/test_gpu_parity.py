@@ -225,6 +225,27 @@ def test_compact_rows_stable(row_bytes, inner, stride_pad):
                 assert np.array_equal(got[b, i, :lead], src[b, i, :lead])
 
 
+def test_compact_rows_takes_the_leading_run_of_valid_indices():
+    """An index list is its valid entries followed by padding: whatever follows the first entry
+    outside [0, n) is ignored, and the tail lands right behind the leading run."""
+    rng = np.random.default_rng(10)
+    n, tail, row_bytes = 12, 3, 32
+    lists = [[3, -1, 5, 7], [1, 4, 12, 6], [0, 2, 9, 11], [-1, 1, 2, 3]]      # valid prefixes of 1, 2, 4, 0 entries
+    B = len(lists)
+    buf = rng.integers(0, 255, (B, 1, n + tail, row_bytes), dtype=np.uint8)
+    d = torch.from_numpy(buf.copy()).to(DEV)
+    d_idx = torch.tensor(lists, dtype=torch.int32, device=DEV)
+    st3.st3_compact_rows(d.data_ptr(), B, 1, (n + tail) * row_bytes, 0, row_bytes, row_bytes, d_idx, 4, n, tail)
+    torch.cuda.synchronize()
+    got = d.cpu().numpy()
+    for b, lst in enumerate(lists):
+        run = 0
+        while run < len(lst) and 0 <= lst[run] < n:
+            run += 1
+        want = np.concatenate([buf[b, 0, lst[:run]], buf[b, 0, n:]])
+        assert np.array_equal(got[b, 0, :run + tail], want), (b, lst)
+
+
 # ---------------------------------------------------------------------------
 # select-and-compact of a layer's cache
 # ---------------------------------------------------------------------------

@@ -17,14 +17,19 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window=1, steps=None, whole_step=False,
-                     lazy=None, kv_scale=None, fixed_tail=True):
+                     lazy=None, kv_scale=None, fixed_tail=True, min_compared=0.8, gen=None):
+    """Runs the workload through the pipeline and the oracle side by side.  A (layer, sequence) pair
+    stops being compared once a near-tie was resolved the other way (values then differ
+    legitimately); the share of pairs compared to the end is printed and must reach min_compared.
+    gen: a Generation of the same shape to run the job on (one that has served other jobs before)."""
     T = w.steps if steps is None else steps
     keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
     keep_np = np.array(keep)
     assert np.array_equal(keep_np, orc.schedule_for(w)[:, :T + 1])
-    gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt,
-                              T, keep, window=window, mode=mode, compact_mode=compact_mode, device=DEV,
-                              lazy=lazy, kv_scale=kv_scale, fixed_tail=fixed_tail)
+    if gen is None:
+        gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt,
+                                  T, keep, window=window, mode=mode, compact_mode=compact_mode, device=DEV,
+                                  lazy=lazy, kv_scale=kv_scale, fixed_tail=fixed_tail)
 
     def phys_len(l, k_vis, t):
         """kv_len[b] the device must hold: the end of the tail, which does not move when it is fixed."""
@@ -127,6 +132,10 @@ def _run_and_compare(w, B, mode="static", compact_mode=st3.ST3_HOLE_FILL, window
     # KV bytes actually held == closed form
     ebytes = 1 if kv_scale is not None else 2 if w.dtype == "bf16" else 4
     assert gen.kv_bytes() == orc.kv_bytes(B, w.heads, w.head_dim, ebytes, ref.cache_lens(), value_only=lazy or ())
+    compared = int((~diverged).sum())
+    print(f"{w.name}: {compared} of {diverged.size} (layer, sequence) pairs compared through the last step, "
+          f"{near_ties} selections resolved a near-tie the other way", flush=True)
+    assert compared >= min_compared * diverged.size, f"only {compared} of {diverged.size} pairs were compared"
     return near_ties, diverged
 
 
@@ -137,6 +146,19 @@ def test_tiny_workload_full(mode, compact_mode, fixed_tail):
     w = get_workload("tiny")
     near, div = _run_and_compare(w, 1, mode=mode, compact_mode=compact_mode, fixed_tail=fixed_tail)
     assert not div.any(), "tiny workload resolved a near-tie differently from the oracle"
+
+
+@pytest.mark.parametrize("whole_step", [False, True])
+def test_one_generation_serves_two_jobs(whole_step):
+    """A second prefill on the same Generation starts clean: the layers before the first prune event
+    rank by their own mass again, not by what the previous job's last prune event left behind."""
+    w = get_workload("tiny")
+    keep = pipeline.keep_table_for(w)
+    gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], 2, w.n_sys, w.n_vis, w.n_txt,
+                              w.steps, keep, device=DEV)
+    for seed in (w.seed, w.seed + 1):
+        near, div = _run_and_compare(dataclasses.replace(w, seed=seed), 2, whole_step=whole_step, gen=gen)
+        assert not div.any()
 
 
 def test_13b_shape_cut_down_current_mode():
@@ -183,8 +205,7 @@ def test_qk_heredity_group(mode, compact_mode):
     """Eq. 6 / Alg. 2: lazy layers take the source's probabilities, at prefill and at every step;
     K-less caches; the group evicts alike.  B*H is small, so the strips are split into chunks."""
     w = _lazy_workload("llava15_7b")
-    near, div = _run_and_compare(w, 2, mode=mode, compact_mode=compact_mode, whole_step=True, lazy={4: 3, 5: 3})
-    assert div.mean() < 0.5
+    _run_and_compare(w, 2, mode=mode, compact_mode=compact_mode, whole_step=True, lazy={4: 3, 5: 3})
 
 
 def test_qk_heredity_fp32_many_heads_no_split_large_evictions():
@@ -213,8 +234,7 @@ def test_e4m3_kv_cache_13b_shape_cut_down(whole_step):
     prompt, its rows and every appended row go through the quantiser, decode reads code x scale."""
     w = dataclasses.replace(get_workload("llava15_13b"), layers=5, heads=8, steps=8,
                             step_schedule={"kind": "cos", "tau": 8})
-    near, div = _run_and_compare(w, 2, whole_step=whole_step, kv_scale=6 * w.sigma / 448)
-    assert div.mean() < 0.5
+    _run_and_compare(w, 2, whole_step=whole_step, kv_scale=6 * w.sigma / 448)
 
 
 @pytest.mark.parametrize("fixed_tail", [True, False])
@@ -235,8 +255,7 @@ def test_13b_shape_cut_down(fixed_tail):
     fixed tail the visual segments empty out while the tail stays 600 rows further on."""
     w = dataclasses.replace(get_workload("llava15_13b"), layers=6, heads=8, steps=12,
                             step_schedule={"kind": "cos", "tau": 12})
-    near, div = _run_and_compare(w, 2, fixed_tail=fixed_tail)
-    assert div.mean() < 0.5
+    _run_and_compare(w, 2, fixed_tail=fixed_tail)
 
 
 def test_7b_shape_cut_down_stable_compaction():
@@ -255,8 +274,7 @@ def test_skewed_workload_ties():
     """Planted exact ties (lowest id must win) and one-ulp near-ties (tolerance rule)."""
     w = dataclasses.replace(get_workload("skewed_13b"), layers=5, heads=4, steps=6,
                             step_schedule={"kind": "cos", "tau": 8})
-    near, div = _run_and_compare(w, 2)
-    print(f"skewed: {near} selections resolved a near-tie differently", flush=True)
+    _run_and_compare(w, 2, min_compared=0.0)        # planted near-ties may go either way
 
 
 def test_pvtp_stride_schedule_with_exp_annealing():

@@ -112,6 +112,20 @@ def test_argument_errors_are_reported_before_any_launch():
                                      None, 0, fake, 1 << 30, None) == st3.ST3_ERR_INVALID_ARG
     assert lib.st3_prefill_attention(C.byref(sh), C.byref(t4), C.byref(t4), C.byref(t4), 100, 8, 64, 17, C.byref(t4),
                                      None, 0, fake, 1 << 30, None) == st3.ST3_ERR_INVALID_ARG
+    # whole-step call: a lazy layer that wants the mass while its source does not ask for one is refused
+    ws_bytes = st3.st3_workspace_bytes(sh, 128, 64, 1)
+    steps = (st3.LayerStep * 2)()
+    for i, s in enumerate(steps):
+        s.kv = st3.KvLayer(None if i else fake, fake, 4 * 128 * 64, 128 * 64, 64, 128)
+        s.seg = st3.Segments(8, 64, 100, fake, fake)
+        s.score_col, s.id_col, s.col_stride = fake + 0x1000 * i, fake + 0x100000 + 0x1000 * i, 64
+        s.keep_after, s.inherit_from = 60, -1 if i == 0 else 0
+        s.q, s.k_new, s.v_new, s.out = fake, fake, fake, fake
+        s.vis_mass, s.mass_stride = (None, 0) if i == 0 else (fake, 64)
+        s.workspace, s.workspace_bytes = fake + 0x10000000 * (i + 1), ws_bytes
+    assert lib.st3_decode_step(C.byref(sh), 2, steps, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_INVALID_ARG
+    steps[1].inherit_from = 1                       # a layer cannot inherit from itself or from a later layer
+    assert lib.st3_decode_step(C.byref(sh), 2, steps, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_INVALID_ARG
     # schedule helpers
     assert lib.st3_schedule_pvtp(32, 576, 3, 0, 5000, 100, fake) == st3.ST3_ERR_INVALID_ARG
     assert lib.st3_schedule_anneal(0, C.c_double(0.0), 4, fake, 2, fake) == st3.ST3_ERR_INVALID_ARG
