@@ -191,6 +191,26 @@ ST3_EXPORT st3_status st3_decode_attention(const st3_attn_shape* shape, const vo
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * st3_decode_attention for callers that cannot allocate device memory or hand over a workspace:
+ * code that runs under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and kernels as st3_decode_attention, without the workspace: the chunk
+ * partials, logits and descriptors of the call live in a device array of
+ * ST3_NOALLOC_SCRATCH_BYTES that is part of the library's code object (every GPU the process uses
+ * holds one copy until the process ends).  The call allocates and frees nothing, on the host or
+ * on the device.  A shape whose workspace (st3_workspace_bytes(shape, kv->capacity, 0, 1)) exceeds
+ * the array returns ST3_ERR_WORKSPACE_TOO_SMALL and enqueues nothing; at the LLaVA-1.5-13B shape
+ * (H = 40, d = 128) a batch of 64 sequences with 1251 cache rows each needs 15 MB.
+ * All calls on one GPU share that GPU's array, which keeps whatever the last call left in it
+ * (nothing in it has to be cleared between calls): two calls whose kernels may overlap on one GPU -
+ * different streams, or different threads - race; serialise them.  What the call leaves in the
+ * array is not available to st3_decode_attention_inherit.
+ * ------------------------------------------------------------------------------------------- */
+#define ST3_NOALLOC_SCRATCH_BYTES (32u << 20)
+ST3_EXPORT st3_status st3_decode_attention_noalloc(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
+                                                   const st3_segments* seg, void* out, float* vis_mass,
+                                                   int64_t mass_stride, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Decode attention of a lazy layer (QK heredity, Eq. 6 and Alg. 2): the layer inherits the softmax
  * probabilities of its source layer l-n and applies them to its own values,
  *   out[b,h,:] = sum_{j<kv_len[b]} p^{src}_j v_j .

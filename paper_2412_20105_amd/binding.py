@@ -28,7 +28,7 @@ ST3_ANNEAL_COS, ST3_ANNEAL_LINEAR, ST3_ANNEAL_EXP, ST3_ANNEAL_DROP, ST3_ANNEAL_N
 EXPORTED = [
     "st3_status_string", "st3_last_hip_error", "st3_version", "st3_workspace_bytes", "st3_workspace_init",
     "st3_prefill_attention", "st3_quantize_rows", "st3_kv_append", "st3_decode_attention", "st3_decode_attention_inherit",
-    "st3_select_topk",
+    "st3_decode_attention_noalloc", "st3_select_topk",
     "st3_compact_rows", "st3_gather_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
     "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
     "st3_debug_set_prefill_path", "st3_debug_set_attend_tile", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
@@ -74,6 +74,7 @@ class GatherPair(C.Structure):
 
 
 ST3_MAX_GATHER = 4
+ST3_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 
 class LayerStep(C.Structure):
@@ -115,6 +116,9 @@ def lib() -> C.CDLL:
         L.st3_decode_attention_inherit.argtypes = [P(AttnShape), P(KvLayer), P(Segments), C.c_void_p, C.c_size_t,
                                                    C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.st3_decode_attention_inherit.restype = C.c_int
+        L.st3_decode_attention_noalloc.argtypes = [P(AttnShape), C.c_void_p, P(KvLayer), P(Segments), C.c_void_p,
+                                                   C.c_void_p, C.c_int64, C.c_void_p]
+        L.st3_decode_attention_noalloc.restype = C.c_int
         L.st3_select_topk.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.st3_compact_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int32,
@@ -267,6 +271,12 @@ def st3_decode_attention(shape, q, kv: KvLayer, seg: Segments, out, vis_mass, wo
                                       _ptr(vis_mass), ms, workspace.data_ptr(),
                                       workspace.numel() * workspace.element_size(), _stream(stream)),
            "st3_decode_attention")
+
+
+def st3_decode_attention_noalloc(shape, q, kv: KvLayer, seg: Segments, out, vis_mass, stream=None):
+    ms = 0 if vis_mass is None else vis_mass.stride(0)
+    _check(lib().st3_decode_attention_noalloc(C.byref(shape), q.data_ptr(), C.byref(kv), C.byref(seg), out.data_ptr(),
+                                              _ptr(vis_mass), ms, _stream(stream)), "st3_decode_attention_noalloc")
 
 
 def st3_decode_attention_inherit(shape, kv: KvLayer, seg: Segments, src_workspace, src_kv_capacity, out, workspace,

@@ -16,7 +16,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libst3.so")
 
-SOURCES = ["st3_api.hip", "st3_decode.hip", "st3_select.hip", "st3_prefill.hip", "st3_prefill_mfma.hip"]
+SOURCES = ["st3_api.hip", "st3_decode.hip", "st3_select.hip", "st3_prefill.hip", "st3_prefill_mfma.hip",
+           "st3_noalloc.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
