@@ -2,22 +2,33 @@
 // W query rows saved for the visual mass (Sec. 3.2).
 //
 // Tiling.  A workgroup of 4 wavefronts owns 128 consecutive query rows (32 per wave) of one (b,h)
-// and walks the key tiles of 64 keys up to its diagonal.  K and V tiles are staged in LDS once
-// per workgroup; V is stored transposed (Vt[d][key]) because both MFMA operands want the
-// contraction index contiguous per lane.
+// and walks the key tiles of 64 keys up to its diagonal.  K and V tiles live in LDS, row-major, in
+// two buffers.  They get there by direct global-to-LDS loads (no staging registers): the tile after
+// the current one is in flight while the current one is consumed, and a tile costs one barrier.
+// A direct load writes the 64 x 16 bytes of a wave to consecutive LDS addresses, so rows cannot be
+// padded against bank conflicts; instead every lane chooses WHICH 16 bytes of its row it fetches,
+// which stores the row's 16-byte units permuted (unit u of row r holds column unit u ^ swz(r)).
 //
-// Per wave and key tile, with v_mfma_f32_32x32x16_bf16 (A: 32 x 16, B: 16 x 32, C: 32 x 32; lane l
-// holds A[l%32][8*(l/32)..+8], B[8*(l/32)..+8][l%32] and C[8*(r/4) + 4*(l/32) + r%4][l%32], r < 16):
-//   S^T = K Q^T   A = K rows from LDS, B = Q fragments kept in registers.  A lane then owns ONE
-//                 query (column l%32) and 16 of the 32 keys of a sub-tile, so the softmax row
-//                 reductions are in-lane plus one exchange with lane l^32.
-//   O^T = V^T P^T A = Vt rows from LDS, B = P^T taken straight from the S^T accumulator registers.
-//                 The accumulator's row pattern fixes which keys a lane holds, so the contraction
-//                 slots are assigned to keys in that pattern and Vt is read in the same pattern.
-// Online softmax in the log2 domain, fp32.  For the second MFMA P is split into two bf16 terms,
-// P = P_hi + P_lo (16 mantissa bits together), and both are multiplied by V: rounding P to one
-// bf16 would put an error of 2^-9 of the row's magnitude on every output element, which is far
-// above the element-wise tolerance for outputs that happen to be small.
+// Per wave, with v_mfma_f32_32x32x16_bf16 (A: 32 x 16, B: 16 x 32, C: 32 x 32; lane l holds
+// A[l%32][8*(l/32)..+8], B[8*(l/32)..+8][l%32] and C[8*(r/4) + 4*(l/32) + r%4][l%32], r < 16):
+//   S^T = K Q^T   A = K rows from LDS (one 16-byte read per lane), B = Q fragments kept in
+//                 registers.  A lane then owns ONE query (column l%32) and 16 of the 32 keys of a
+//                 sub-tile, so the softmax row reductions are in-lane plus one exchange with lane l^32.
+//   O^T = V^T P^T B = P^T taken straight from the S^T accumulator registers, which fixes which keys
+//                 sit in which contraction slot: slots 8g..8g+3 of the MFMA over keys 16kk..16kk+15
+//                 are keys 16kk+4g..+3, slots 8g+4..8g+7 keys 16kk+8+4g..+3.  A = V^T in the same
+//                 pattern: a lane needs, for ONE column d of V, two runs of four consecutive keys,
+//                 which is what the LDS transpose read of gfx950 (ds_read_b64_tr_b16) returns from
+//                 a row-major tile: within 16 lanes, lane i passes the address of elements
+//                 4*(i%4)..+3 of row i/4 of a 4 x 16 block and receives column i of that block
+//                 (layout checked on the device with an index pattern).
+// A tile that lies entirely below a wave's diagonal is consumed whole (64 keys, one softmax
+// update); on the diagonal the 32-key sub-tile that holds it is masked and a sub-tile above it is
+// skipped.  Online softmax in the log2 domain, fp32; the softmax scale is folded into the
+// exponent's multiply-add.  For the second MFMA P is split into two bf16 terms, P = P_hi + P_lo
+// (P_hi the upper 16 bits of the float, P_lo the rounded rest: 16 mantissa bits together), and both
+// are multiplied by V: rounding P to one bf16 would put an error of 2^-9 of the row's magnitude on
+// every output element, far above the element-wise tolerance for outputs that happen to be small.
 #include "st3_prefill.h"
 
 namespace st3 {
@@ -25,87 +36,238 @@ namespace st3 {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBM = 128;            // queries per workgroup
 constexpr int kBN = 64;             // keys per tile
-constexpr int kVPad = kBN + 2;      // Vt row stride in elements: 33 words, so column reads spread over banks
+
+// An LDS tile is kBN rows of D elements, no padding.  The 64 banks are 256 bytes wide together, so
+// RPB rows share one pass over the banks.  K rows are read 16 bytes per lane by lanes holding
+// consecutive rows: unit u ^ ((r / RPB) % UPR) spreads 16 consecutive rows over all banks.  V rows
+// are read by the transpose read, 32 lanes covering 4 consecutive rows x 64 bytes (4 units): the
+// permutation 4 * ((r / RPB) % (UPR / 4)) puts the four rows on disjoint quarters of the banks.
+template <int D> struct TileLayout {
+    static constexpr int UPR = D / 8;                   // 16-byte units per row
+    static constexpr int RPB = 256 / (2 * D);           // rows per 256 bytes: 1 or 2
+    static constexpr int RPI = 1024 / (2 * D);          // rows per wave-wide direct load (1 KB): 4 or 8
+    static constexpr int NI = kBN / (RPI * 4);          // direct loads of K, and of V, per wave and tile
+    static constexpr int TILE = kBN * D;                // elements of one K (or V) tile
+    __device__ static __forceinline__ int k_swz(int row) { return (row / RPB) & (UPR - 1); }
+    __device__ static __forceinline__ int v_swz(int row) { return 4 * ((row / RPB) & (UPR / 4 - 1)); }
+};
 
 union Frag {
     bf16x8 v;
     u32x4 u4;
     uint32_t w[4];
+    i16x4 h[2];
 };
 
-template <int NK, int NV>
-struct TileRegs {
-    u32x4 k[NK], va[NV], vb[NV];
-};
+// One wave-wide direct load: every lane fetches the 16 bytes at `src` (global memory) and the wave's
+// 64 x 16 bytes land at LDS byte address lds_base .. lds_base + 1023 in lane order (gfx950:
+// global_load_lds_dwordx4, LDS base in M0).  Issued through inline assembly: the compiler treats the
+// builtin form as an access that is outstanding on the LDS counter as well, and then makes every
+// later wait for an LDS read a wait for ALL LDS reads in flight, which serialises the fragment
+// reads of the whole tile.  What it does not know about is handled here: wait_direct_loads() before
+// the barrier that publishes a buffer; M0 is declared clobbered; "memory" keeps LDS reads in place.
+__device__ __forceinline__ void direct_load16(const uint16_t* src, const uint16_t* lds_dst) {
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
+        (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const uint16_t*)lds_dst));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base), "v"(src)
+                 : "memory", "m0");
+}
 
-// Issues the global loads of the K/V tile that starts at key k0 (rows past n-1 are clamped).
-template <int D, int NK, int NV>
-__device__ __forceinline__ void fetch_tile(TileRegs<NK, NV>& t, const uint16_t* Kp, const uint16_t* Vp, int64_t k_st,
-                                           int64_t v_st, int k0, int n, int tid) {
-    constexpr int VPR = D / 8;
+// Starts the direct loads of the K/V tile at key k0 into `buf` (K tile, then V tile).  Rows past
+// n-1 are clamped: such keys lie above every valid query's diagonal and are masked there.  Every
+// address read is a row of the caller's tensors; every LDS address written lies inside `buf`.
+// kl / vl: this lane's K and V source at key 0 of its first 1 KB group (row and permuted unit folded in).
+template <int D>
+__device__ __forceinline__ void issue_tile(uint16_t* buf, const uint16_t* kl, const uint16_t* vl, int64_t k_st,
+                                           int64_t v_st, int k0, int n, int lane, int wave) {
+    using L = TileLayout<D>;
+    const int row0 = wave * L::RPI + lane / L::UPR;     // this lane's row in the wave's first group
+    if (k0 + kBN <= n) {                                // all rows of the tile exist: plain strides
 #pragma unroll
-    for (int i = 0; i < NK; ++i) {
-        const int vec = tid + 256 * i;
-        const int key = min(k0 + vec / VPR, n - 1);
-        t.k[i] = *reinterpret_cast<const u32x4*>(Kp + (int64_t)key * k_st + (vec % VPR) * 8);
-    }
+        for (int i = 0; i < L::NI; ++i) {
+            const int grp = 4 * i + wave;               // which 1 KB of the tile this wave-wide load fills
+            const int key = k0 + 4 * i * L::RPI;
+            direct_load16(kl + key * k_st, buf + grp * 512);
+            direct_load16(vl + key * v_st, buf + L::TILE + grp * 512);
+        }
+    } else {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int item = tid + 256 * i;
-        const int cv = item % VPR, kp = item / VPR;
-        const int key_a = min(k0 + 2 * kp, n - 1), key_b = min(k0 + 2 * kp + 1, n - 1);
-        t.va[i] = *reinterpret_cast<const u32x4*>(Vp + (int64_t)key_a * v_st + cv * 8);
-        t.vb[i] = *reinterpret_cast<const u32x4*>(Vp + (int64_t)key_b * v_st + cv * 8);
+        for (int i = 0; i < L::NI; ++i) {
+            const int grp = 4 * i + wave;
+            const int key = max(0, min(k0 + 4 * i * L::RPI, n - 1 - row0));     // this lane's row, key + row0, stays <= n - 1
+            direct_load16(kl + key * k_st, buf + grp * 512);
+            direct_load16(vl + key * v_st, buf + L::TILE + grp * 512);
+        }
     }
 }
 
-__device__ __forceinline__ void put_pair(uint16_t* Vt, int col, int kp, uint32_t wa, uint32_t wb) {
-    *reinterpret_cast<uint32_t*>(&Vt[col * kVPad + 2 * kp]) = (wa & 0xffffu) | (wb << 16);              // (key_a, key_b)
-    *reinterpret_cast<uint32_t*>(&Vt[(col + 1) * kVPad + 2 * kp]) = (wa >> 16) | (wb & 0xffff0000u);
+// All direct loads this wave has issued have landed in LDS (vmcnt(0); other counters untouched).
+__device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// LDS transpose read: 4 consecutive rows of one column (see the header comment for the lane map).
+__device__ __forceinline__ i16x4 lds_read_tr(const uint16_t* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p));
 }
 
-// Writes the staged tile to LDS: K row-major (padded), V transposed (a thread holds 2 adjacent
-// keys x 8 columns and writes 8 words, one per column).
-template <int D, int NK, int NV>
-__device__ __forceinline__ void stage_tile(const TileRegs<NK, NV>& t, uint16_t* Ks, uint16_t* Vt, int tid) {
-    constexpr int VPR = D / 8, KPAD = D + 8;
+// What a lane needs to find its operands in a tile (element offsets, fixed for the whole kernel).
+template <int D>
+struct LaneMap {
+    int koff[D / 16];       // K fragment s of row c: row * D + ((2s + g) ^ k_swz) * 8
+    int voff[D / 32];       // transpose read of d-tile dt: row (4g + (c%16)/4), unit (4dt + 2(c/16) + (c%4)/2) ^ v_swz, half c%2
+    __device__ __forceinline__ void init(int c, int g) {
+        using L = TileLayout<D>;
 #pragma unroll
-    for (int i = 0; i < NK; ++i) {
-        const int vec = tid + 256 * i;
-        *reinterpret_cast<u32x4*>(&Ks[(vec / VPR) * KPAD + (vec % VPR) * 8]) = t.k[i];
-    }
+        for (int s = 0; s < D / 16; ++s) koff[s] = c * D + ((2 * s + g) ^ L::k_swz(c)) * 8;
+        const int row = 4 * g + ((c & 15) >> 2);
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int item = tid + 256 * i;
-        const int cv = item % VPR, kp = item / VPR;
-        put_pair(Vt, cv * 8 + 0, kp, t.va[i].x, t.vb[i].x);
-        put_pair(Vt, cv * 8 + 2, kp, t.va[i].y, t.vb[i].y);
-        put_pair(Vt, cv * 8 + 4, kp, t.va[i].z, t.vb[i].z);
-        put_pair(Vt, cv * 8 + 6, kp, t.va[i].w, t.vb[i].w);
+        for (int dt = 0; dt < D / 32; ++dt)
+            voff[dt] = row * D + ((4 * dt + 2 * (c >> 4) + ((c & 3) >> 1)) ^ L::v_swz(row)) * 8 + 4 * (c & 1);
     }
+};
+
+// NSUB 32-key sub-tiles of the tile in (Kt, Vt) for one wave: S^T, one online-softmax update over
+// all NSUB * 32 keys, O^T += V^T P^T.  DIAG: the last of them lies on the wave's diagonal (its keys
+// start at the wave's first query), the only place where some keys are invisible to some rows.
+template <int D, int NSUB, bool DIAG>
+__device__ __forceinline__ void tile_step(const uint16_t* Kt, const uint16_t* Vt, const Frag* qf, f32x16* oacc,
+                                          float& m_i, float& l_i, float scale_l2, const LaneMap<D>& lm, int c, int g,
+                                          int k0, int myq, float* lg_row, int vis_lo, int vis_hi) {
+    constexpr int KS = D / 16, DT = D / 32;
+    // LDS reads are issued in batches ahead of their use, so that their latency is paid once per
+    // batch and not once per MFMA: all K fragments of the step before its first MFMA.
+    Frag ka[NSUB][KS];
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) ka[sub][s].u4 = *reinterpret_cast<const u32x4*>(Kt + 32 * sub * D + lm.koff[s]);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- S^T = K Q^T ----------------------------------------------------------------------------
+    f32x16 sacc[NSUB];
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][s].v, qf[s].v, sacc[sub], 0, 0, 0);
+    }
+    Frag va[2][DT];                     // V^T fragments of the 16-key group in use and of the next one
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {   // the first group lands while the softmax runs
+        va[0][dt].h[0] = lds_read_tr(Vt + lm.voff[dt]);
+        va[0][dt].h[1] = lds_read_tr(Vt + 8 * D + lm.voff[dt]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- causal mask (diagonal sub-tile only), row maximum ----------------------------------------
+    if (DIAG) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (8 * (r / 4) + 4 * g + (r % 4) > c) sacc[NSUB - 1][r] = -INFINITY;
+    }
+    if (lg_row != nullptr) {            // a row of the score window: keep the scaled logits of its visual keys
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = k0 + 32 * sub + 8 * (r / 4) + 4 * g + (r % 4);
+                if (key >= vis_lo && key < vis_hi && key <= myq) lg_row[key - vis_lo] = sacc[sub][r] * scale_l2;
+            }
+    }
+    float mx = sacc[0][0];
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[sub][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // every row sees the first key of every tile it gets here (k0 <= q0 <= myq), so mx is finite.
+    // The reference point m_i of the exponents only follows the row maximum when that has moved by
+    // more than kLazy (probabilities then reach 2^kLazy at most, far inside fp32 and bf16 range):
+    // a softmax is invariant to the reference point, and the accumulator rescaling it triggers
+    // becomes rare instead of happening in nearly every tile.
+    constexpr float kLazy = 8.0f;
+    const float m_cand = fmaxf(m_i, mx * scale_l2);
+    const bool moved = m_cand - m_i > kLazy;            // m_i = -inf before the first key: moved
+    const float m_new = moved ? m_cand : m_i;
+    const float alpha = exp2_fast(m_i - m_new);         // 1 when not moved; 0 before the first key
+    m_i = m_new;
+    float psum = 0.f;
+    Frag pb[NSUB][2], pl[NSUB][2];
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float p0 = exp2_fast(fmaf(sacc[sub][8 * kk + 2 * j], scale_l2, -m_new));      // masked: exp2(-inf) = 0
+                const float p1 = exp2_fast(fmaf(sacc[sub][8 * kk + 2 * j + 1], scale_l2, -m_new));
+                psum += p0 + p1;
+                const uint32_t b0 = __float_as_uint(p0), b1 = __float_as_uint(p1);
+                pb[sub][kk].w[j] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);      // upper halves of (p0, p1)
+                const f32x2 lo = {p0 - __uint_as_float(b0 & 0xffff0000u), p1 - __uint_as_float(b1 & 0xffff0000u)};
+                pl[sub][kk].w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+            }
+    l_i = l_i * alpha + psum;
+    if (__any(moved)) {                                 // rescale only when some row's maximum moved
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+    }
+    // ---- O^T += V^T P^T, 16 keys (one contraction) at a time ------------------------------------
+#pragma unroll
+    for (int grp = 0; grp < 2 * NSUB; ++grp) {
+        if (grp + 1 < 2 * NSUB) {       // the next group's fragments are on their way while this one is used
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                va[(grp + 1) & 1][dt].h[0] = lds_read_tr(Vt + 16 * (grp + 1) * D + lm.voff[dt]);
+                va[(grp + 1) & 1][dt].h[1] = lds_read_tr(Vt + (16 * (grp + 1) + 8) * D + lm.voff[dt]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[grp & 1][dt].v, pb[grp / 2][grp % 2].v, oacc[dt], 0, 0, 0);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[grp & 1][dt].v, pl[grp / 2][grp % 2].v, oacc[dt], 0, 0, 0);
+        }
+    }
+}
+
+// The part of the tile at k0 that the wave with first query q0 can see (k0 <= q0).
+template <int D>
+__device__ __forceinline__ void consume_tile(const uint16_t* buf, int k0, int q0, const Frag* qf, f32x16* oacc,
+                                             float& m_i, float& l_i, float scale_l2, const LaneMap<D>& lm, int c, int g,
+                                             int myq, float* lg_row, int vis_lo, int vis_hi) {
+    const uint16_t* Kt = buf;
+    const uint16_t* Vt = buf + TileLayout<D>::TILE;
+    if (k0 + kBN <= q0)         // below the diagonal: all 64 keys visible to all 32 rows
+        tile_step<D, 2, false>(Kt, Vt, qf, oacc, m_i, l_i, scale_l2, lm, c, g, k0, myq, lg_row, vis_lo, vis_hi);
+    else if (k0 + 32 == q0)     // first half visible, second half on the diagonal
+        tile_step<D, 2, true>(Kt, Vt, qf, oacc, m_i, l_i, scale_l2, lm, c, g, k0, myq, lg_row, vis_lo, vis_hi);
+    else                        // k0 == q0: first half on the diagonal, second half above it
+        tile_step<D, 1, true>(Kt, Vt, qf, oacc, m_i, l_i, scale_l2, lm, c, g, k0, myq, lg_row, vis_lo, vis_hi);
 }
 
 // One-dimensional grid of ceil(n/128) * H * B workgroups (the mapping to query tile and strip is in the kernel).
 // Register budget: two waves per SIMD (256 registers each), so that one wave's softmax VALU work
-// overlaps the other's MFMAs.  The 64-key LDS tile is consumed as two 32-key halves, each with its
-// own online-softmax update, which halves the live S/P registers; the accumulator is only rescaled
-// when some row's maximum actually moved.  The next tile's global loads are issued before the
-// current tile is consumed and written to LDS after it.
+// overlaps the other's MFMAs; the accumulator is only rescaled when some row's maximum actually moved.
 template <int D>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
+    using L = TileLayout<D>;
     constexpr int KS = D / 16;          // contraction steps of S^T
     constexpr int DT = D / 32;          // 32-row tiles of O^T
-    constexpr int KPAD = D + 8;         // K row stride in LDS (elements)
-    constexpr int VPR = D / 8;          // 16-byte vectors per row
-    constexpr int KV_K = kBN * VPR / 256;           // K vectors staged per thread and tile
-    constexpr int KV_V = (kBN / 2) * VPR / 256;     // V key-pair items per thread and tile
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[kBN * KPAD];
-    __shared__ __attribute__((aligned(16))) uint16_t Vt[D * kVPad];
+    // two buffers as two objects, so that the compiler can tell a direct load into one from the reads of the other
+    __shared__ __attribute__((aligned(1024))) uint16_t buf0[2 * L::TILE];
+    __shared__ __attribute__((aligned(1024))) uint16_t buf1[2 * L::TILE];
 
     // Workgroup -> (query tile, strip).  Workgroups go round-robin by linear id to the 8 XCDs (checked
     // with a probe: XCC id == id % 8) and, within an XCD, in turn to its 4 shader engines; each XCD
@@ -143,12 +305,26 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
     const uint16_t* Kp = reinterpret_cast<const uint16_t*>(a.k) + b * a.k_sb + h * a.k_sh;
     const uint16_t* Vp = reinterpret_cast<const uint16_t*>(a.v) + b * a.v_sb + h * a.v_sh;
 
+    // this lane's source of the direct loads: row (wave * RPI + lane / UPR) of a 1 KB group, and the
+    // 16-byte unit that the permutation assigns to its LDS slot (the permutations repeat every RPI * 4
+    // rows or sooner, so they are the same for every group and every tile)
+    const uint16_t* kl;
+    const uint16_t* vl;
+    {
+        const int row0 = wave * L::RPI + lane / L::UPR, u = lane % L::UPR;
+        const int rowc = min(row0, n - 1);              // a prompt shorter than one group of rows
+        kl = Kp + (int64_t)rowc * a.k_st + (u ^ L::k_swz(row0)) * 8;
+        vl = Vp + (int64_t)rowc * a.v_st + (u ^ L::v_swz(row0)) * 8;
+    }
+    issue_tile<D>(buf0, kl, vl, a.k_st, a.v_st, 0, n, lane, wave);
     Frag qf[KS];
     {
         const uint16_t* qrow = Qp + (int64_t)min(myq, n - 1) * a.q_st;
 #pragma unroll
         for (int s = 0; s < KS; ++s) qf[s].u4 = *reinterpret_cast<const u32x4*>(qrow + 16 * s + 8 * g);
     }
+    LaneMap<D> lm;
+    lm.init(c, g);
     f32x16 oacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -161,99 +337,41 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
     const int w_idx = myq - (n - a.window);
     const bool lane_in_window = wave_has_window && w_idx >= 0 && myq < n;
     float* lg_row = lane_in_window ? a.pre_logits + (bh * a.window + w_idx) * a.vis_len : nullptr;
+    const int vis_lo = a.sys_len, vis_hi = a.sys_len + a.vis_len;
 
-    // global -> register staging of one K/V tile (rows past the end are clamped and masked later)
-    TileRegs<KV_K, KV_V> tr;
     const int k_end = min(n, qt * kBM + kBM);           // keys this workgroup can see
-    fetch_tile<D>(tr, Kp, Vp, a.k_st, a.v_st, 0, n, tid);
-    for (int k0 = 0; k0 < k_end; k0 += kBN) {
-        __syncthreads();                                // previous tile fully consumed
-        stage_tile<D>(tr, Ks, Vt, tid);
+    const int nt = (k_end + kBN - 1) / kBN;
+    const bool wave_live = q0 < n;                      // else all 32 queries lie beyond the prompt (ragged last tile)
+    wait_direct_loads();
+    __syncthreads();
+    // Tiles alternate between the buffers; the loop body handles one pair.  A buffer is refilled one
+    // iteration after its last read, and every wave has passed a barrier in between.
+    for (int t = 0; t < nt; t += 2) {
+        if (t + 1 < nt) issue_tile<D>(buf1, kl, vl, a.k_st, a.v_st, (t + 1) * kBN, n, lane, wave);
+        if (wave_live && t * kBN <= q0)                 // else the tile lies entirely above this wave's diagonal
+            consume_tile<D>(buf0, t * kBN, q0, qf, oacc, m_i, l_i, a.scale_l2, lm, c, g, myq, lg_row, vis_lo, vis_hi);
+        wait_direct_loads();
         __syncthreads();
-        if (k0 + kBN < k_end) fetch_tile<D>(tr, Kp, Vp, a.k_st, a.v_st, k0 + kBN, n, tid);   // in flight while this tile is consumed
-        if (k0 > q0 + 31 || q0 >= n) continue;          // tile entirely above this wave's diagonal, or a wave whose
-                                                        // 32 queries all lie beyond the prompt (ragged last tile)
-
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const int ks0 = k0 + 32 * sub;
-            if (ks0 > q0 + 31) break;                   // this half is above the diagonal too
-            // ---- S^T = K Q^T for 32 keys ------------------------------------------------------
-            f32x16 sacc;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                Frag ka;
-                ka.u4 = *reinterpret_cast<const u32x4*>(&Ks[(32 * sub + c) * KPAD + 16 * s + 8 * g]);
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, qf[s].v, sacc, 0, 0, 0);
-            }
-            // ---- scale, causal / length mask, row maximum -----------------------------------
-            float mx = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = ks0 + 8 * (r / 4) + 4 * g + (r % 4);
-                float s = sacc[r] * a.scale_l2;
-                if (key > myq || key >= n) s = -INFINITY;
-                sacc[r] = s;
-                mx = fmaxf(mx, s);
-            }
-            if (wave_has_window && lg_row != nullptr) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = ks0 + 8 * (r / 4) + 4 * g + (r % 4);
-                    if (key >= a.sys_len && key < a.sys_len + a.vis_len && key <= myq) lg_row[key - a.sys_len] = sacc[r];
-                }
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            // The first half of a tile always holds a visible key for every row (k0 <= q0 <= myq);
-            // the second half may be entirely masked for some rows, then mx = -inf and m stays.
-            const float m_new = fmaxf(m_i, mx);
-            const bool moved = m_new > m_i;
-            const float alpha = exp2_fast(m_i - m_new);     // m_i = -inf only before the first key: alpha = 0
-            m_i = m_new;
-            float psum = 0.f;
-            Frag pb[2], pl[2];
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float p = exp2_fast(sacc[8 * kk + j] - m_new);
-                    psum += p;
-                    const __bf16 hi = (__bf16)p;
-                    pb[kk].v[j] = hi;
-                    pl[kk].v[j] = (__bf16)(p - (float)hi);
-                }
-            l_i = l_i * alpha + psum;
-            if (__any(moved)) {                         // rescale only when some row's maximum moved
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-            }
-            // ---- O^T += V^T P^T ---------------------------------------------------------------
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const int base = 32 * sub + 16 * kk + 4 * g;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const uint16_t* row = &Vt[(32 * dt + c) * kVPad + base];
-                    Frag va;
-                    va.w[0] = *reinterpret_cast<const uint32_t*>(row);
-                    va.w[1] = *reinterpret_cast<const uint32_t*>(row + 2);
-                    va.w[2] = *reinterpret_cast<const uint32_t*>(row + 8);
-                    va.w[3] = *reinterpret_cast<const uint32_t*>(row + 10);
-                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb[kk].v, oacc[dt], 0, 0, 0);
-                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pl[kk].v, oacc[dt], 0, 0, 0);
-                }
-            }
-        }
+        if (t + 1 >= nt) break;
+        if (t + 2 < nt) issue_tile<D>(buf0, kl, vl, a.k_st, a.v_st, (t + 2) * kBN, n, lane, wave);
+        if (wave_live && (t + 1) * kBN <= q0)
+            consume_tile<D>(buf1, (t + 1) * kBN, q0, qf, oacc, m_i, l_i, a.scale_l2, lm, c, g, myq, lg_row, vis_lo, vis_hi);
+        wait_direct_loads();
+        __syncthreads();
     }
     // ---- normalise and store -----------------------------------------------------------------
     const float l_tot = l_i + __shfl_xor(l_i, 32);
     const float rl = 1.0f / l_tot;
-    if (myq < n) {
-        uint16_t* orow = reinterpret_cast<uint16_t*>(a.out) + b * a.o_sb + h * a.o_sh + (int64_t)myq * a.o_st;
+    // The accumulator holds O transposed (a lane owns one query and, per register quad, 4 consecutive
+    // columns): stored straight from there, a wave-wide store would touch 32 rows with 8 bytes each.
+    // So the wave's 32 x D block goes through LDS (both tile buffers are free after the last barrier;
+    // each wave uses a region of its own) and leaves as whole rows, 16 bytes per lane.
+    {
+        constexpr int OSTR = D + 8;                     // padded row, 16-byte aligned
+        constexpr int VPR = D / 8;                      // 16-byte vectors (lanes) per row
+        constexpr int RPI = 64 / VPR;                   // rows per wave-wide store
+        uint16_t* obuf = (wave < 2 ? buf0 : buf1) + (wave & 1) * (32 * OSTR);
+        static_assert(2 * 32 * OSTR <= 2 * L::TILE, "two waves' output blocks fit one tile buffer");
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -262,8 +380,17 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
                 uint2 pk;
                 pk.x = f32_to_bf16_bits(oacc[dt][4 * rq] * rl) | (f32_to_bf16_bits(oacc[dt][4 * rq + 1] * rl) << 16);
                 pk.y = f32_to_bf16_bits(oacc[dt][4 * rq + 2] * rl) | (f32_to_bf16_bits(oacc[dt][4 * rq + 3] * rl) << 16);
-                *reinterpret_cast<uint2*>(orow + dd) = pk;
+                *reinterpret_cast<uint2*>(obuf + c * OSTR + dd) = pk;
             }
+        uint16_t* obase = reinterpret_cast<uint16_t*>(a.out) + b * a.o_sb + h * a.o_sh;
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int r = i * RPI + lane / VPR;
+            const u32x4 val = *reinterpret_cast<const u32x4*>(obuf + r * OSTR + (lane % VPR) * 8);
+            if (q0 + r < n) *reinterpret_cast<u32x4*>(obase + (int64_t)(q0 + r) * a.o_st + (lane % VPR) * 8) = val;
+        }
+    }
+    if (myq < n) {
         if (lane_in_window && g == 0) {
             a.pre_ml[(bh * a.window + w_idx) * 2] = m_i;
             a.pre_ml[(bh * a.window + w_idx) * 2 + 1] = l_tot;
