@@ -22,6 +22,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# the roofline pass times the decode attention kernel through the library's diagnostic block
+# (st3_profile_*), which is inert unless this is set before the library is loaded
+os.environ.setdefault("ST3_DEBUG", "1")
 
 
 def parse():
@@ -35,6 +38,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unpruned", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--no-layer-calls", action="store_true", help="skip the run that makes one library call per layer")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--layer-schedule", default="workload", choices=["workload", "linear", "pvtp", "full"],
                     help="retention over layers: the workload's own, or the paper's strided PVTP (Alg. 1, Eq. 9)")
@@ -105,6 +109,21 @@ class Job:
         for t in range(1, self.T + 1):
             gen.decode_step(t, self.dec[t - 1])
 
+    def run_layer_calls(self):
+        """The same job through the calls a decoder with a dependency between its layers can make:
+        st3_decode_layer_attend once per layer (each could wait for the previous layer's output),
+        then st3_decode_plans once per step."""
+        gen, w = self.gen, self.w
+        for l in range(w.layers):
+            q, k, v = self.pre[l]
+            gen.prefill_layer(l, q, k, v)
+        for t in range(1, self.T + 1):
+            d = self.dec[t - 1]
+            gen.begin_step(t)
+            for l in range(w.layers):
+                gen.attend_layer(l, d[l, 0], d[l, 1], d[l, 2])
+            gen.finish_step()
+
     def run_prefill_only(self):
         gen, w = self.gen, self.w
         for l in range(w.layers):
@@ -158,39 +177,76 @@ def timed(torch, fn, reps):
 
 
 def cpu_baseline(w, keep, T, budget_s):
-    """The oracle's decode step at B = 1 on sampled steps of the same workload, on the host cores."""
+    """The oracle (NumPy fp64, as it stands) on the host cores: its decode step at B = 1 on sampled
+    steps of the same workload, once with the BLAS pool at the cores this process may use and once
+    on one thread; the tiny workload is timed in full (prefill + all decode steps)."""
     import numpy as np
-    from threadpoolctl import threadpool_limits
+    from threadpoolctl import threadpool_info, threadpool_limits
 
     from oracle import st3_oracle as orc
-    cores = min(16, os.cpu_count() or 1)
+    nproc = os.cpu_count() or 1
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except (AttributeError, OSError):
+        usable = nproc
+    want = max(1, min(usable, int(os.environ.get("OMP_NUM_THREADS", usable) or usable)))
     rng = np.random.default_rng(0)
     sample_steps = sorted(set([1, max(1, T // 4), max(1, T // 2), max(1, 3 * T // 4), T]))
-    spent, done, per_step = 0.0, 0, []
-    with threadpool_limits(limits=cores):
-        reps = 0
-        while spent < budget_s and reps < 50:
-            for t in sample_steps:
-                g = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, np.array(keep))
-                for l in range(w.layers):
-                    nv = keep[l][t - 1]
-                    n = w.n_sys + nv + w.n_txt + (t - 1)
-                    g.K.append([rng.standard_normal((w.heads, n, w.head_dim))])
-                    g.V.append([rng.standard_normal((w.heads, n, w.head_dim))])
-                    g.ids.append([np.arange(nv, dtype=np.int64)])
-                    g.rho.append([rng.random(nv)])
-                g.t = t - 1
-                qkv = [tuple(rng.standard_normal((1, w.heads, w.head_dim)) for _ in range(3)) for _ in range(w.layers)]
-                t0 = time.perf_counter()
-                g.decode_step(lambda l: qkv[l])
-                dt = time.perf_counter() - t0
-                per_step.append(dt); spent += dt; done += 1
-            reps += 1
-    mean = sum(per_step) / len(per_step)
-    return {"value": 1.0 / mean, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"B=1, oracle decode step (all {w.layers} layers: evict, append, attention, mass) at "
-                      f"steps t in {sample_steps} of {w.name}, {done} timed steps, {spent:.1f} s; prefill excluded; "
-                      f"cost is linear in B"}
+
+    def one_step(t):
+        g = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, np.array(keep))
+        for l in range(w.layers):
+            nv = keep[l][t - 1]
+            n = w.n_sys + nv + w.n_txt + (t - 1)
+            g.K.append([rng.standard_normal((w.heads, n, w.head_dim))])
+            g.V.append([rng.standard_normal((w.heads, n, w.head_dim))])
+            g.ids.append([np.arange(nv, dtype=np.int64)])
+            g.rho.append([rng.random(nv)])
+        g.t = t - 1
+        qkv = [tuple(rng.standard_normal((1, w.heads, w.head_dim)) for _ in range(3)) for _ in range(w.layers)]
+        t0 = time.perf_counter()
+        g.decode_step(lambda l: qkv[l])
+        return time.perf_counter() - t0
+
+    def whole_job():
+        g = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, np.array(keep))
+        shape_p = (1, w.heads, w.n_prompt, w.head_dim)
+        pre = [tuple(rng.standard_normal(shape_p) for _ in range(3)) for _ in range(w.layers)]
+        dec = [[tuple(rng.standard_normal((1, w.heads, w.head_dim)) for _ in range(3)) for _ in range(w.layers)]
+               for _ in range(T)]
+        t0 = time.perf_counter()
+        g.prefill(lambda l: pre[l])
+        for t in range(T):
+            g.decode_step(lambda l: dec[t][l])
+        return time.perf_counter() - t0
+
+    def measure(threads, budget):
+        with threadpool_limits(limits=threads):
+            pools = [p.get("num_threads", 1) for p in threadpool_info()]
+            used = max(pools) if pools else 1
+            spent, times = 0.0, []
+            reps = 0
+            while spent < budget and reps < 50:
+                if w.name == "tiny":
+                    dt = whole_job(); times.append(dt); spent += dt
+                else:
+                    for t in sample_steps:
+                        dt = one_step(t); times.append(dt); spent += dt
+                reps += 1
+        mean = sum(times) / len(times)
+        per_token = mean / T if w.name == "tiny" else mean      # seconds per generated token at B = 1
+        return {"value": 1.0 / per_token, "cores": used, "timed": len(times), "seconds": round(spent, 1)}
+
+    many = measure(want, budget_s / 2)
+    one = measure(1, budget_s / 2)
+    what = (f"whole job (prefill + {T} decode steps) at B=1, {many['timed']} runs" if w.name == "tiny" else
+            f"B=1, oracle decode step (all {w.layers} layers: evict, append, attention, mass) at steps t in {sample_steps} "
+            f"of {w.name}, {many['timed']} timed steps; prefill excluded")
+    return {"value": many["value"], "unit": "tokens/s", "cores": many["cores"], "kind": "oracle",
+            "sample": f"{what}, {many['seconds']} s on {many['cores']} BLAS threads (host reports {nproc} CPUs, {usable} usable) "
+                      f"and {one['seconds']} s on 1 thread; cost is linear in B",
+            "one_core": {"value": one["value"], "unit": "tokens/s", "cores": 1, "timed": one["timed"]},
+            "host_cpus": nproc, "usable_cpus": usable}
 
 
 def pmc_probe(a, w, B, T, keep, torch, pipeline, st3, lazy=None):
@@ -409,7 +465,8 @@ def main():
     def note(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
-    st3.st3_debug_set_attend_tile(a.attend_tile)
+    if a.attend_tile:
+        st3.st3_debug_set_attend_tile(a.attend_tile)
     if a.select_probe:
         return select_probe(w, B, torch, st3)
     if a.prefill_probe:
@@ -448,6 +505,17 @@ def main():
         "decode_ms_per_token_step": (ms_job - ms_prefill) / T,
         "decode_only_tokens_per_s": tokens / ((ms_job - ms_prefill) * 1e-3),
     }
+
+    # -- the same job through one library call per layer (what a real decoder can call) -----------
+    if not a.no_layer_calls:
+        note("per-layer calls")
+        job.run_layer_calls()
+        ms_lc = timed(torch, job.run_layer_calls, 1) * 1e3
+        result["per_layer_calls"] = {
+            "value": tokens / (ms_lc * 1e-3), "unit": "tokens/s", "ms_per_step": ms_lc,
+            "decode_ms_per_token_step": (ms_lc - ms_prefill) / T,
+            "calls": "st3_decode_layer_attend per layer + st3_decode_plans per step (the headline uses st3_decode_step: "
+                     "the same launches from one host call per step)"}
 
     # -- roofline of the dominant kernel (split-KV decode), from a second, instrumented pass ---------
     note(f"job {ms_job:.1f} ms, prefill {ms_prefill:.1f} ms")

@@ -10,9 +10,16 @@
  * Conventions (all entry points unless stated otherwise)
  *   - extern "C"; every pointer documented as DEVICE points to HIP device memory owned by the
  *     caller; every pointer documented as HOST is ordinary host memory.  The library never
- *     allocates or frees device memory, keeps no per-call state, and never synchronises: work is
- *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream) and results are
- *     valid once the caller has synchronised that stream.
+ *     allocates or frees device memory and never synchronises: work is enqueued on `stream` (a
+ *     hipStream_t passed as void*; NULL = the null stream) and results are valid once the caller
+ *     has synchronised that stream.  Nothing a call computes is kept on the host between calls.
+ *     What the library does keep, process-wide: the last HIP error (thread-local), per-device
+ *     caches of device properties (compute units, resident workgroups per kernel build; written
+ *     once, same value from every thread), the device address of the st3_decode_attention_noalloc
+ *     array, and the diagnostic switches of the st3_debug_* / st3_profile_* block at the end of
+ *     this header, which stay at their defaults unless ST3_DEBUG=1 was in the environment when
+ *     the library was loaded.  Calls from several threads are safe as long as they do not share
+ *     buffers.
  *   - Arguments are checked on the host before anything is enqueued.  On an error the call
  *     returns a non-zero st3_status and enqueues nothing.  A failed HIP launch returns
  *     ST3_ERR_HIP and st3_last_hip_error() gives the hipError_t (thread-local).
@@ -371,6 +378,29 @@ ST3_EXPORT st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
                                       int32_t mode, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * The same step in the two parts a decoder with a data dependency between its layers can call
+ * (Alg. 3, VTA branch: the loop over l visits the layers in order, and layer l+1's query exists
+ * only once layer l's output does).
+ *   st3_decode_layer_attend   part (1) of layer `layer` of the array: append k_new/v_new and attend
+ *                             (a lazy layer: inherit from its source, which must have attended in
+ *                             this step already).  Only that entry (and its source's) is read and
+ *                             checked, plus inherit_from of the later entries, so the q / k_new /
+ *                             v_new of later layers need not exist yet.  out is valid, and complete, as soon as
+ *                             the stream has run the call; the visual mass stays pending in the
+ *                             layer's workspace; kv_len[b] does not yet count the appended row.
+ *   st3_decode_plans          part (2) of ALL layers, once per step after the last layer has
+ *                             attended: finishes the masses, counts the appended rows, ranks and
+ *                             evicts down to keep_after, 16 layers per launch.
+ * Calling st3_decode_layer_attend for layer = 0 .. n_layers-1 and then st3_decode_plans, with the
+ * same array, is what st3_decode_step does.  Between the first attend and the plans of a step the
+ * arrays max_* bounds, keep_after and the buffers of every entry must stay as they are.
+ * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT st3_status st3_decode_layer_attend(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
+                                              int32_t layer, int32_t mode, void* stream);
+ST3_EXPORT st3_status st3_decode_plans(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
+                                       int32_t mode, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Retention schedules: HOST-only pure functions that fill integer tables.
  * ------------------------------------------------------------------------------------------- */
 
@@ -416,28 +446,32 @@ ST3_EXPORT st3_status st3_cosine_similarity(const float* va, const int32_t* ids_
                                             int32_t n_b, int32_t batch, int32_t id_space, float* cosine, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * Diagnostics: timing of the decode attention kernel (the kernel that streams K and V).
+ * Diagnostic block.  Compiled into every build, inert by default: unless the environment held
+ * ST3_DEBUG=1 when the library was loaded, every call below returns ST3_ERR_UNSUPPORTED and
+ * changes nothing (st3_debug_enabled tells which).  The switches are process-wide and meant for
+ * tests and benchmarks: set them while no other thread is inside a library call.
+ *
  * st3_profile_enable(n) creates (host-side) hipEvents for up to n launches and makes the decode
- * calls launch that kernel with an event pair attached that receives the kernel's own start and
- * end on the caller's stream; this stops silently once n launches are used.
+ *   calls launch the decode attention kernel (the kernel that streams K and V) with an event pair
+ *   attached that receives the kernel's own start and end on the caller's stream; this stops
+ *   silently once n launches are used.
  * st3_profile_read waits for the recorded events, returns the summed / min / max kernel time in
- * milliseconds and the number of launches timed, and switches recording off.  HOST pointers, any
- * may be NULL.  Not thread-safe; intended for benchmarks.
+ *   milliseconds and the number of launches timed, and switches recording off.  HOST pointers, any
+ *   may be NULL.
+ * st3_debug_set_prefill_path: which kernel st3_prefill_attention uses for bf16 inputs.  0 =
+ *   automatic (MFMA kernel), 1 = the float32 row kernel, 2 = MFMA or fail.  Lets the two be
+ *   compared on one input.
+ * st3_debug_set_attend_tile: the decode attention kernel is built for several tile sizes (16-byte
+ *   loads of K, and of V, per lane and tile) and picks one per launch from the launch's size.
+ *   tile_loads != 0 makes every later launch use that build when the cache type has it (plain
+ *   caches: 1, 4, 6, 8; E4M3: 1, 3, 4; any other value: automatic choice, as with 0).  Results do
+ *   not depend on the tile size beyond float32 rounding order.
  * ------------------------------------------------------------------------------------------- */
+ST3_EXPORT int st3_debug_enabled(void);
 ST3_EXPORT st3_status st3_profile_enable(int32_t max_launches);
 ST3_EXPORT st3_status st3_profile_read(double* total_ms, int64_t* launches, double* min_ms, double* max_ms);
-
-/* Test hook: which kernel st3_prefill_attention uses for bf16 inputs.  0 = automatic (MFMA
- * kernel), 1 = the float32 row kernel, 2 = MFMA or fail.  Lets the two be compared on one input.
- * Process-wide; not for production use. */
-ST3_EXPORT void st3_debug_set_prefill_path(int path);
-
-/* Test hook: the decode attention kernel is built for several tile sizes (16-byte loads of K, and
- * of V, per lane and tile) and picks one per launch from the launch's size.  tile_loads != 0 makes
- * every later launch use that build when the cache type has it (plain caches: 1, 4, 6, 8; E4M3:
- * 1, 3, 4; any other value: automatic choice, as with 0).  Results do not depend on the tile size
- * beyond float32 rounding order.  Process-wide; lets tests and benchmarks run every build. */
-ST3_EXPORT void st3_debug_set_attend_tile(int tile_loads);
+ST3_EXPORT st3_status st3_debug_set_prefill_path(int path);
+ST3_EXPORT st3_status st3_debug_set_attend_tile(int tile_loads);
 
 #ifdef __cplusplus
 }

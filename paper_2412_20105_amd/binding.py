@@ -30,8 +30,9 @@ EXPORTED = [
     "st3_prefill_attention", "st3_quantize_rows", "st3_kv_append", "st3_decode_attention", "st3_decode_attention_inherit",
     "st3_decode_attention_noalloc", "st3_select_topk",
     "st3_compact_rows", "st3_gather_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
+    "st3_decode_layer_attend", "st3_decode_plans",
     "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
-    "st3_debug_set_prefill_path", "st3_debug_set_attend_tile", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
+    "st3_debug_enabled", "st3_debug_set_prefill_path", "st3_debug_set_attend_tile", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
     "st3_cosine_similarity",
 ]
 
@@ -133,6 +134,10 @@ def lib() -> C.CDLL:
                                             C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
         L.st3_decode_step.argtypes = [P(AttnShape), C.c_int32, P(LayerStep), C.c_int32, C.c_void_p]
         L.st3_decode_step.restype = C.c_int
+        L.st3_decode_layer_attend.argtypes = [P(AttnShape), C.c_int32, P(LayerStep), C.c_int32, C.c_int32, C.c_void_p]
+        L.st3_decode_layer_attend.restype = C.c_int
+        L.st3_decode_plans.argtypes = [P(AttnShape), C.c_int32, P(LayerStep), C.c_int32, C.c_void_p]
+        L.st3_decode_plans.restype = C.c_int
         L.st3_schedule_pvtp.argtypes = [C.c_int32] * 6 + [C.c_void_p]
         L.st3_schedule_linear.argtypes = [C.c_int32] * 4 + [C.c_void_p]
         L.st3_schedule_anneal.argtypes = [C.c_int32, C.c_double, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
@@ -156,9 +161,10 @@ def lib() -> C.CDLL:
         L.st3_profile_read.argtypes = [P(C.c_double), P(C.c_int64), P(C.c_double), P(C.c_double)]
         L.st3_profile_read.restype = C.c_int
         L.st3_debug_set_prefill_path.argtypes = [C.c_int]
-        L.st3_debug_set_prefill_path.restype = None
+        L.st3_debug_set_prefill_path.restype = C.c_int
         L.st3_debug_set_attend_tile.argtypes = [C.c_int]
-        L.st3_debug_set_attend_tile.restype = None
+        L.st3_debug_set_attend_tile.restype = C.c_int
+        L.st3_debug_enabled.restype = C.c_int
         _lib = L
     return _lib
 
@@ -345,6 +351,15 @@ def st3_decode_step(shape, layer_steps, n_layers, mode, stream=None):
     _check(lib().st3_decode_step(C.byref(shape), n_layers, layer_steps, mode, _stream(stream)), "st3_decode_step")
 
 
+def st3_decode_layer_attend(shape, layer_steps, n_layers, layer, mode, stream=None):
+    _check(lib().st3_decode_layer_attend(C.byref(shape), n_layers, layer_steps, layer, mode, _stream(stream)),
+           "st3_decode_layer_attend")
+
+
+def st3_decode_plans(shape, layer_steps, n_layers, mode, stream=None):
+    _check(lib().st3_decode_plans(C.byref(shape), n_layers, layer_steps, mode, _stream(stream)), "st3_decode_plans")
+
+
 # -- host-only schedule helpers ---------------------------------------------------------------
 def st3_schedule_pvtp(L, n_vis, first_layer, stride_S, P_bp, R_bp):
     out = (C.c_int32 * L)()
@@ -397,9 +412,14 @@ def st3_profile_read():
     return tot.value, cnt.value, mn.value, mx.value
 
 
+def st3_debug_enabled() -> bool:
+    """True when ST3_DEBUG=1 was in the environment as the library was loaded (the diagnostic block is live)."""
+    return bool(lib().st3_debug_enabled())
+
+
 def st3_debug_set_prefill_path(path: int) -> None:
-    lib().st3_debug_set_prefill_path(path)
+    _check(lib().st3_debug_set_prefill_path(path), "st3_debug_set_prefill_path")
 
 
 def st3_debug_set_attend_tile(tile_loads: int) -> None:
-    lib().st3_debug_set_attend_tile(tile_loads)
+    _check(lib().st3_debug_set_attend_tile(tile_loads), "st3_debug_set_attend_tile")

@@ -60,5 +60,36 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def build_host_sanitized(driver_src: str, out_path: str) -> str:
+    """The library's sources plus a host driver program as ONE executable whose HOST code runs under
+    AddressSanitizer and UndefinedBehaviorSanitizer (device code is compiled as usual and never
+    launched by such a driver): checks the argument validation and the host-only helpers on a box
+    without a GPU."""
+    hipcc = _hipcc()
+    objdir = os.path.join(HERE, "_build", "san")
+    os.makedirs(objdir, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    flags = [f for f in HIPCC_FLAGS if f != "-fvisibility=hidden"]
+
+    def compile_one(path: str) -> str:
+        obj = os.path.join(objdir, os.path.basename(path) + ".o")
+        lang = ["-x", "hip"] if not path.endswith(".hip") else []
+        r = subprocess.run([hipcc, *flags, *san, *inc, *lang, "-c", path, "-o", obj], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitized) failed on {path}:\n{r.stdout}\n{r.stderr}")
+        return obj
+
+    srcs = [os.path.join(CSRC, f) for f in SOURCES] + [driver_src]
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
+        objs = list(ex.map(compile_one, srcs))
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", *objs, "-o", out_path],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link (sanitized) failed:\n{r.stdout}\n{r.stderr}")
+    return out_path
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))

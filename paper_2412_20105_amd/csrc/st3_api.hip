@@ -1,6 +1,9 @@
 // Status/version queries, workspace sizing, the fused per-layer decode step, and the host-only
 // retention-schedule helpers (Sec. 3.2, Eq. 7-9, Alg. 1 of the paper).
 #include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "st3_evict.h"
@@ -10,11 +13,21 @@ namespace st3 {
 static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 
+DebugState& debug_state() {
+    static DebugState st = [] {
+        const char* e = std::getenv("ST3_DEBUG");
+        return DebugState{e != nullptr && std::strcmp(e, "1") == 0, 0, 0};
+    }();
+    return st;
+}
+static const bool g_debug_state_read_at_load = (debug_state(), true);
+
 // ---------------------------------------------------------------------------------------------
 // Optional timing of the decode attention kernel: a pool of hipEvent pairs attached to that
 // kernel's launches (start and stop of the kernel itself).  Off unless st3_profile_enable().
 // ---------------------------------------------------------------------------------------------
 struct DecodeProfiler {
+    std::mutex mu;
     std::vector<hipEvent_t> ev;     // 2 per launch
     size_t used = 0;                // launches recorded
     bool on = false;
@@ -24,6 +37,8 @@ static DecodeProfiler g_prof;
 // Hands out the next event pair; the caller passes it to hipExtLaunchKernelGGL, which stamps the
 // two events with the kernel's own start and end.
 bool profile_take(hipEvent_t* start, hipEvent_t* stop) {
+    if (!g_prof.on) return false;                   // (never set unless the debug block is enabled)
+    std::lock_guard<std::mutex> lock(g_prof.mu);
     if (!g_prof.on) return false;
     if ((g_prof.used + 1) * 2 > g_prof.ev.size()) { g_prof.on = false; return false; }      // pool exhausted
     *start = g_prof.ev[g_prof.used * 2];
@@ -174,14 +189,19 @@ extern "C" st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
     return check_launch();
 }
 
-extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
-                                      int32_t mode, void* stream) {
-    using namespace st3;
+namespace st3 {
+
+// Host-side checks of every layer of a step and the eviction plans that go with them.  Nothing is
+// enqueued here.  has_heirs[i]: some lazy layer inherits from layer i (its attend launch must then
+// keep the logit of every key).
+static st3_status check_step(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers, int32_t mode,
+                             std::vector<EvictArgs>& plan, std::vector<char>& needs_apply, std::vector<char>& has_heirs) {
     st3_status s = check_shape(shape);
     if (s != ST3_OK) return s;
     if (n_layers <= 0 || !layers) return ST3_ERR_INVALID_ARG;
-    std::vector<EvictArgs> plan((size_t)n_layers);
-    std::vector<char> needs_apply((size_t)n_layers, 0), has_heirs((size_t)n_layers, 0);
+    plan.assign((size_t)n_layers, EvictArgs{});
+    needs_apply.assign((size_t)n_layers, 0);
+    has_heirs.assign((size_t)n_layers, 0);
     for (int i = 0; i < n_layers; ++i)
         if (layers[i].inherit_from >= 0 && layers[i].inherit_from < i) has_heirs[layers[i].inherit_from] = 1;
     for (int i = 0; i < n_layers; ++i) {
@@ -204,32 +224,85 @@ extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
         if (s != ST3_OK) return s;
         needs_apply[i] = na ? 1 : 0;
     }
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const int B = shape->batch;
-    for (int i = 0; i < n_layers; ++i) {
-        const st3_layer_step& L = layers[i];
-        if (L.inherit_from >= 0) {
-            const st3_layer_step& S = layers[L.inherit_from];
-            s = enqueue_inherit(shape, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.v_new, S.workspace, S.workspace_bytes,
-                                S.kv.capacity, L.out, L.workspace, L.workspace_bytes, st);
-        } else {
-            s = enqueue_decode(shape, L.q, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.k_new, L.v_new, L.out, L.vis_mass,
-                               L.mass_stride, L.vis_mass != nullptr, true, has_heirs[i] != 0, L.workspace, L.workspace_bytes,
-                               st);
-        }
-        if (s != ST3_OK) return s;
+    return ST3_OK;
+}
+
+// Append + attention of layer i of a checked step; the mass stays pending for the layer's plan.
+static st3_status enqueue_layer_attend(const st3_attn_shape* shape, const st3_layer_step* layers, int i, bool has_heirs,
+                                       hipStream_t st) {
+    const st3_layer_step& L = layers[i];
+    if (L.inherit_from >= 0) {
+        const st3_layer_step& S = layers[L.inherit_from];
+        return enqueue_inherit(shape, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.v_new, S.workspace, S.workspace_bytes,
+                               S.kv.capacity, L.out, L.workspace, L.workspace_bytes, st);
     }
-    // every layer's plan (finish the mass, count the new row, rank, evict) in one launch per 16
-    // layers: a plan workgroup is latency bound, so the layers' plans are best run side by side
-    launch_evict_plan_batch(plan.data(), n_layers, B, st);
-    for (int i = 0; i < n_layers; ++i)
+    return enqueue_decode(shape, L.q, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.k_new, L.v_new, L.out, L.vis_mass,
+                          L.mass_stride, L.vis_mass != nullptr, true, has_heirs, L.workspace, L.workspace_bytes, st);
+}
+
+// Every layer's plan (finish the mass, count the new row, rank, evict) in one launch per 16
+// layers: a plan workgroup is latency bound, so the layers' plans are best run side by side.
+static st3_status enqueue_plans(const std::vector<EvictArgs>& plan, const std::vector<char>& needs_apply, int B,
+                                hipStream_t st) {
+    launch_evict_plan_batch(plan.data(), (int)plan.size(), B, st);
+    for (size_t i = 0; i < plan.size(); ++i)
         if (needs_apply[i]) launch_evict_apply(plan[i], B, st);
     return check_launch();
 }
 
+}  // namespace st3
+
+extern "C" st3_status st3_decode_layer_attend(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
+                                              int32_t layer, int32_t mode, void* stream) {
+    using namespace st3;
+    st3_status s = check_shape(shape);
+    if (s != ST3_OK) return s;
+    if (n_layers <= 0 || !layers || layer < 0 || layer >= n_layers) return ST3_ERR_INVALID_ARG;
+    // only this layer's entry (and its source's) is checked here; st3_decode_plans checks the whole array
+    const st3_layer_step& L = layers[layer];
+    if (L.inherit_from >= 0) {
+        if (L.inherit_from >= layer) return ST3_ERR_INVALID_ARG;
+        s = check_lazy_step(shape, L, layers[L.inherit_from], mode);
+    } else {
+        s = check_layer_step(shape, &L.kv, &L.seg, L.score_col, L.id_col, L.col_stride, L.keep_after, mode, L.q, L.k_new,
+                             L.v_new, L.out, L.vis_mass, L.mass_stride, L.workspace, L.workspace_bytes);
+    }
+    if (s != ST3_OK) return s;
+    bool has_heirs = false;
+    for (int i = layer + 1; i < n_layers; ++i) has_heirs = has_heirs || layers[i].inherit_from == layer;
+    return enqueue_layer_attend(shape, layers, layer, has_heirs, reinterpret_cast<hipStream_t>(stream));
+}
+
+extern "C" st3_status st3_decode_plans(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
+                                       int32_t mode, void* stream) {
+    using namespace st3;
+    std::vector<EvictArgs> plan;
+    std::vector<char> needs_apply, has_heirs;
+    st3_status s = check_step(shape, n_layers, layers, mode, plan, needs_apply, has_heirs);
+    if (s != ST3_OK) return s;
+    return enqueue_plans(plan, needs_apply, shape->batch, reinterpret_cast<hipStream_t>(stream));
+}
+
+extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
+                                      int32_t mode, void* stream) {
+    using namespace st3;
+    std::vector<EvictArgs> plan;
+    std::vector<char> needs_apply, has_heirs;
+    st3_status s = check_step(shape, n_layers, layers, mode, plan, needs_apply, has_heirs);
+    if (s != ST3_OK) return s;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    for (int i = 0; i < n_layers; ++i) {
+        s = enqueue_layer_attend(shape, layers, i, has_heirs[i] != 0, st);
+        if (s != ST3_OK) return s;
+    }
+    return enqueue_plans(plan, needs_apply, shape->batch, st);
+}
+
 extern "C" st3_status st3_profile_enable(int32_t max_launches) {
     using namespace st3;
+    if (!debug_state().enabled) return ST3_ERR_UNSUPPORTED;
     if (max_launches <= 0 || max_launches > (1 << 22)) return ST3_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_prof.mu);
     while (g_prof.ev.size() < (size_t)max_launches * 2) {
         hipEvent_t e;
         hipError_t err = hipEventCreate(&e);
@@ -243,6 +316,8 @@ extern "C" st3_status st3_profile_enable(int32_t max_launches) {
 
 extern "C" st3_status st3_profile_read(double* total_ms, int64_t* launches, double* min_ms, double* max_ms) {
     using namespace st3;
+    if (!debug_state().enabled) return ST3_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_prof.mu);
     g_prof.on = false;
     double tot = 0.0, mn = 1e30, mx = 0.0;
     for (size_t i = 0; i < g_prof.used; ++i) {
@@ -257,6 +332,21 @@ extern "C" st3_status st3_profile_read(double* total_ms, int64_t* launches, doub
     if (min_ms) *min_ms = g_prof.used ? mn : 0.0;
     if (max_ms) *max_ms = mx;
     g_prof.used = 0;
+    return ST3_OK;
+}
+
+extern "C" int st3_debug_enabled(void) { return st3::debug_state().enabled ? 1 : 0; }
+
+extern "C" st3_status st3_debug_set_prefill_path(int path) {
+    if (!st3::debug_state().enabled) return ST3_ERR_UNSUPPORTED;
+    if (path < 0 || path > 2) return ST3_ERR_INVALID_ARG;
+    st3::debug_state().prefill_path = path;
+    return ST3_OK;
+}
+
+extern "C" st3_status st3_debug_set_attend_tile(int tile_loads) {
+    if (!st3::debug_state().enabled) return ST3_ERR_UNSUPPORTED;
+    st3::debug_state().attend_tile = tile_loads < 0 ? 0 : tile_loads;
     return ST3_OK;
 }
 

@@ -13,6 +13,18 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 void set_last_hip_error(hipError_t e);
 
+// Process-wide diagnostic switches (st3_debug_* / st3_profile_* of st3.h).  They exist in every build
+// but stay at their defaults - and the calls that set them return ST3_ERR_UNSUPPORTED - unless the
+// environment held ST3_DEBUG=1 when the library was loaded.  Plain ints read by the launch code;
+// set them only while no other thread is inside a library call.
+struct DebugState {
+    bool enabled;           // ST3_DEBUG=1 at load
+    int prefill_path;       // 0 = automatic, 1 = float32 row kernel, 2 = MFMA kernel or fail
+    int attend_tile;        // 0 = automatic, else the forced tile size of the decode attention kernel
+};
+DebugState& debug_state();  // st3_api.hip
+constexpr int kMaxDevices = 64;     // per-device caches (occupancy, scratch addresses) are indexed by the HIP device id
+
 // Launch-error capture used by every entry point after enqueueing its kernels.
 inline st3_status check_launch() {
     hipError_t e = hipGetLastError();

@@ -20,6 +20,7 @@
 // write-back and invalidate of the XCD-private L2 on this part and were measured to be ruinous.
 #include <hip/hip_ext.h>
 
+#include <atomic>
 #include <cmath>
 #include <utility>
 
@@ -490,28 +491,34 @@ __global__ void bump_len_kernel(int32_t* kv_len, int32_t B, int32_t capacity) {
 // of each build the device holds and takes the build that wastes least of its last round; the
 // candidate lists below are in order of preference for ties.
 // ---------------------------------------------------------------------------------------------
-int compute_units() {
-    static int cached[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-        cached[dev] = n;
-    }
-    return cached[dev];
+// The current device's id when it indexes the per-device caches below, else -1 (then nothing is cached).
+int current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    return dev;
 }
 
-// Workgroups of `kernel` (256 threads, no dynamic LDS) the current device holds at once.
+int compute_units(int dev) {
+    static std::atomic<int> cached[kMaxDevices];    // 0 = not asked yet; a race only repeats the query
+    if (dev >= 0 && cached[dev].load(std::memory_order_relaxed) != 0) return cached[dev].load(std::memory_order_relaxed);
+    int n = 0;
+    if (dev < 0 || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    if (dev >= 0) cached[dev].store(n, std::memory_order_relaxed);
+    return n;
+}
+
+// Workgroups of `kernel` (256 threads, no dynamic LDS) the current device holds at once; `cache` is
+// the kernel's own array of one entry per device.
 template <typename K>
-int resident_workgroups(K kernel, int* cache) {
-    if (*cache == 0) {
-        int per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kDecodeThreads, 0) != hipSuccess || per_cu < 1)
-            per_cu = 1;
-        *cache = per_cu * compute_units();
-    }
-    return *cache;
+int resident_workgroups(K kernel, std::atomic<int>* cache) {
+    const int dev = current_device();
+    if (dev >= 0 && cache[dev].load(std::memory_order_relaxed) != 0) return cache[dev].load(std::memory_order_relaxed);
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kDecodeThreads, 0) != hipSuccess || per_cu < 1)
+        per_cu = 1;
+    const int n = per_cu * compute_units(dev);
+    if (dev >= 0) cache[dev].store(n, std::memory_order_relaxed);
+    return n;
 }
 
 // Time of a launch of `items` equal workgroups on `slots` concurrent ones, relative to a launch whose
@@ -539,14 +546,13 @@ void launch_attend_u(const DecodeArgs& da, int B, hipStream_t st) {
         decode_attend_kernel<T, KT, D, U><<<grid, kDecodeThreads, 0, st>>>(da);
 }
 
-int g_forced_tile = 0;       // st3_debug_set_attend_tile
-
 // Takes the cheapest of the builds Us... (in order of preference) for this launch.
 template <typename T, typename KT, int D, int... Us>
 void launch_attend_best(const DecodeArgs& da, int B, hipStream_t st, std::integer_sequence<int, Us...>) {
     constexpr int N = sizeof...(Us);
-    static int slots[N] = {};
+    static std::atomic<int> slots[N][kMaxDevices];  // resident workgroups of each build, per device
     const int us[N] = {Us...};
+    const int g_forced_tile = debug_state().attend_tile;    // 0 unless the debug block is enabled
     if (g_forced_tile != 0 && ((g_forced_tile == Us) || ...)) {
         ((g_forced_tile == Us ? (launch_attend_u<T, KT, D, Us>(da, B, st), 0) : 0), ...);
         return;
@@ -554,7 +560,7 @@ void launch_attend_best(const DecodeArgs& da, int B, hipStream_t st, std::intege
     const int64_t items = (int64_t)da.nsplit * da.H * B;
     double cost[N];
     int i = 0;
-    ((cost[i] = last_round_cost(items, resident_workgroups(decode_attend_kernel<T, KT, D, Us>, &slots[i])), ++i), ...);
+    ((cost[i] = last_round_cost(items, resident_workgroups(decode_attend_kernel<T, KT, D, Us>, slots[i])), ++i), ...);
     const int pick = us[cheapest(cost, N)];
     ((pick == Us ? (launch_attend_u<T, KT, D, Us>(da, B, st), 0) : 0), ...);
 }
@@ -695,8 +701,6 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     return check_launch();
 }
 
-void set_forced_tile(int u) { g_forced_tile = u; }
-
 st3_status enqueue_append(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                           const void* k_new, const void* v_new, hipStream_t st) {
     const int B = shape->batch, H = shape->heads;
@@ -764,8 +768,6 @@ st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, 
 }
 
 }  // namespace st3
-
-extern "C" void st3_debug_set_attend_tile(int tile_loads) { st3::set_forced_tile(tile_loads); }
 
 extern "C" st3_status st3_decode_attention(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
                                            const st3_segments* seg, void* out, float* vis_mass, int64_t mass_stride,

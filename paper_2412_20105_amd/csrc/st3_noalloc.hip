@@ -23,7 +23,6 @@ namespace {
 constexpr size_t kScratchBytes = ST3_NOALLOC_SCRATCH_BYTES;
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
-constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mu;
 void* g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on each device, once looked up
 

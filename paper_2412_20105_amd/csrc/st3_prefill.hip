@@ -99,11 +99,6 @@ bool tensor_ok(const st3_tensor4* t, int eb, int d) {
 }  // namespace
 }  // namespace st3
 
-// Selects the kernel: 0 = automatic, 1 = force the row kernel (also for bf16), 2 = force MFMA.
-// Test hook only: lets the two kernels be compared on the same input.
-static int g_prefill_path = 0;
-extern "C" void st3_debug_set_prefill_path(int path) { g_prefill_path = path; }
-
 extern "C" st3_status st3_prefill_attention(const st3_attn_shape* shape, const st3_tensor4* q, const st3_tensor4* k,
                                             const st3_tensor4* v, int32_t n, int32_t sys_len, int32_t vis_len,
                                             int32_t score_window, const st3_tensor4* out, float* vis_mass,
@@ -142,6 +137,9 @@ extern "C" st3_status st3_prefill_attention(const st3_attn_shape* shape, const s
         a.pre_logits = reinterpret_cast<float*>(ws + wl.pre_logits);
         a.pre_ml = reinterpret_cast<float*>(ws + wl.pre_ml);
     }
+    // diagnostic override of the kernel choice (0 unless the debug block is enabled): 1 = the row
+    // kernel also for bf16, 2 = the MFMA kernel or fail
+    const int g_prefill_path = debug_state().prefill_path;
     bool use_mfma = shape->dtype == ST3_BF16;
     if (g_prefill_path == 1) use_mfma = false;
     if (g_prefill_path == 2 && shape->dtype != ST3_BF16) return ST3_ERR_UNSUPPORTED;

@@ -239,12 +239,7 @@ class Generation:
         lc.h_vis = target
         return self.dec_out, mass_dst[:, :n_attn]
 
-    def decode_step(self, t: int, qkv: torch.Tensor):
-        """All layers of decode step t from one library call.  qkv: device [L, 3, B, H, d]
-        (q, k_new, v_new per layer).  Returns dec_out_all [L, B, H, d] (reused buffer)."""
-        assert qkv.is_contiguous() and tuple(qkv.shape) == (self.L, 3, self.B, self.H, self.d)
-        if not getattr(self, "_decoding", False):
-            self.begin_decode()
+    def _step_array(self):
         if self._steps is None:
             arr = (st3.LayerStep * self.L)()
             for l, lc in enumerate(self.layers):
@@ -258,20 +253,69 @@ class Generation:
                 s.workspace, s.workspace_bytes = lc.ws.data_ptr(), lc.ws.numel()
                 s.inherit_from = self.lazy.get(l, -1)
             self._steps = arr
-        arr = self._steps
-        base = qkv.data_ptr()
-        one = self.B * self.H * self.d * self._eb
+        return self._steps
+
+    def _set_step_bounds(self, t: int):
+        """Per-step scalars of every entry: what each layer keeps after this step's attention and the
+        host-side bounds of its lengths before it."""
+        arr = self._step_array()
         for l, lc in enumerate(self.layers):
             s = arr[l]
             target = self._keep_after(l, t)
             s.keep_after = target if target < lc.h_vis else -1
             s.seg.max_vis_len, s.seg.max_kv_len = lc.h_vis, lc.h_kv
             s.seg.vis_len_hint, s.seg.tail_start_hint = lc.h_vis, lc.h_tail     # every sequence holds these (equal images)
-            s.q, s.k_new, s.v_new = base + (3 * l) * one, base + (3 * l + 1) * one, base + (3 * l + 2) * one
+        return arr
+
+    def _advance_host_lengths(self, t: int):
+        for l, lc in enumerate(self.layers):
+            target = self._keep_after(l, t)
             lc.h_kv = lc.h_kv + 1 - (0 if self.fixed_tail else lc.h_vis - target)
             lc.h_vis = target
+
+    def decode_step(self, t: int, qkv: torch.Tensor):
+        """All layers of decode step t from one library call.  qkv: device [L, 3, B, H, d]
+        (q, k_new, v_new per layer).  Returns dec_out_all [L, B, H, d] (reused buffer)."""
+        assert qkv.is_contiguous() and tuple(qkv.shape) == (self.L, 3, self.B, self.H, self.d)
+        if not getattr(self, "_decoding", False):
+            self.begin_decode()
+        arr = self._set_step_bounds(t)
+        base = qkv.data_ptr()
+        one = self.B * self.H * self.d * self._eb
+        for l in range(self.L):
+            s = arr[l]
+            s.q, s.k_new, s.v_new = base + (3 * l) * one, base + (3 * l + 1) * one, base + (3 * l + 2) * one
+        self._advance_host_lengths(t)
         st3.st3_decode_step(self.shape, arr, self.L, self.compact_mode)
         return self.dec_out_all
+
+    # -- the same step as a decoder with a dependency between its layers calls it --------------------
+    def begin_step(self, t: int):
+        """Opens decode step t for attend_layer() calls (Alg. 3, VTA branch, the loop over l)."""
+        if not getattr(self, "_decoding", False):
+            self.begin_decode()
+        self._set_step_bounds(t)
+        self._open_step = t
+
+    def attend_layer(self, l: int, q: Optional[torch.Tensor], k_new: Optional[torch.Tensor], v_new: torch.Tensor):
+        """Layer l of the open step: append k_new/v_new and attend.  q, k_new, v_new: device [B,H,d], alive until
+        the stream has run the call (a lazy layer ignores q and k_new).  Returns out [B,H,d], complete once the
+        stream has run the call - before any later layer's inputs need to exist."""
+        arr = self._steps
+        s = arr[l]
+        any_ptr = v_new.data_ptr()
+        s.q = any_ptr if q is None else q.data_ptr()
+        s.k_new = any_ptr if k_new is None else k_new.data_ptr()
+        s.v_new = v_new.data_ptr()
+        st3.st3_decode_layer_attend(self.shape, arr, self.L, l, self.compact_mode)
+        return self.dec_out_all[l]
+
+    def finish_step(self):
+        """Closes the open step: masses, appended rows counted, evictions of every layer."""
+        t = self._open_step
+        st3.st3_decode_plans(self.shape, self._steps, self.L, self.compact_mode)
+        self._advance_host_lengths(t)
+        self._open_step = None
 
     def kv_lens(self) -> List[int]:
         """Keys each layer holds (dead rows between a visual segment and a fixed tail do not count)."""

@@ -3,6 +3,10 @@ import sys
 
 import pytest
 
+# the tests use the library's diagnostic block (forced kernel builds, kernel timing): it is inert
+# unless this is in the environment when the library is loaded
+os.environ.setdefault("ST3_DEBUG", "1")
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)

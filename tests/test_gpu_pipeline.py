@@ -283,3 +283,69 @@ def test_pvtp_stride_schedule_with_exp_annealing():
                             layer_schedule={"kind": "pvtp", "S": 4, "P_bp": 5000, "R_bp": 500},
                             step_schedule={"kind": "exp", "sigma": 3})
     _run_and_compare(w, 1)
+
+
+@pytest.mark.parametrize("name,kw,B,lazy", [
+    ("tiny", {}, 2, None),
+    ("llava15_13b", dict(layers=6, heads=8, steps=5, step_schedule={"kind": "cos", "tau": 5}), 2, None),
+    ("llava15_7b", dict(layers=6, heads=4, steps=4, n_vis=120, n_txt=9,
+                        layer_schedule={"kind": "table", "keep": [120, 120, 100, 80, 80, 80]},
+                        step_schedule={"kind": "cos", "tau": 6}), 2, {4: 3, 5: 3}),
+])
+def test_layers_called_one_at_a_time_with_a_data_dependency(name, kw, B, lazy):
+    """The step as a real decoder calls it (Alg. 3, loop over l): st3_decode_layer_attend per layer, the next
+    layer's query formed on the HOST from the previous layer's output after it was read back, then
+    st3_decode_plans once.  The oracle replays the step with the queries the device path used."""
+    w = dataclasses.replace(get_workload(name), **kw)
+    T = w.steps
+    keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
+    for l, src in (lazy or {}).items():
+        assert keep[l] == keep[src]
+    gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt, T, keep,
+                              device=DEV, lazy=lazy)
+    ref = orc.Generation(w.layers, w.heads, w.head_dim, w.n_sys, w.n_vis, w.n_txt, np.array(keep), lazy=lazy)
+    pre = [prefill_qkv(w, l, B) for l in range(w.layers)]
+    r = ref.prefill(lambda l: pre[l])
+    for l in range(w.layers):
+        q, k, v = (to_dev(x, w.dtype) for x in pre[l])
+        gen.prefill_layer(l, q, k, v)
+    compared = 0
+    alive = np.ones((w.layers, B), bool)
+    for t in range(1, T + 1):
+        dec = [list(decode_qkv(w, l, t, B)) for l in range(w.layers)]
+        gen.begin_step(t)
+        torch.cuda.synchronize()
+        ids_attn = [gen.layers[l].ids[:, :gen.layers[l].h_vis].cpu().numpy() for l in range(w.layers)]
+        rho_before = [[x.copy() for x in ref.rho[l]] for l in range(w.layers)]
+        ids_before = [[x.copy() for x in ref.ids[l]] for l in range(w.layers)]
+        outs, keepalive = [], []
+        prev = None
+        for l in range(w.layers):
+            if prev is not None:        # the data dependency: this layer's query needs the previous layer's output
+                dec[l][0] = dec[l][0] + 0.25 * prev
+            q, k, v = (to_dev(x, w.dtype) for x in dec[l])
+            dec[l][0] = q.float().cpu().numpy().astype(np.float64)     # what the device path really used (rounded to dtype)
+            keepalive.append((q, k, v))
+            out = gen.attend_layer(l, q, k, v)
+            torch.cuda.synchronize()
+            prev = out.float().cpu().numpy()                            # read back before the next layer's inputs exist
+            outs.append(to_np64(out))
+        gen.finish_step()
+        torch.cuda.synchronize()
+        s = ref.decode_step(lambda l: tuple(dec[l]))
+        for l in range(w.layers):
+            lc = gen.layers[l]
+            for b in range(B):
+                if alive[l, b]:
+                    alive[l, b] = assert_selection_matches(ids_attn[l][b], rho_before[l][b], ids_before[l][b], keep[l][t],
+                                                           f"t={t} l={l} b={b}")
+                if not alive[l, b]:
+                    continue
+                assert_attention_close(outs[l][b], s["out"][l][b], w.dtype, f"out t={t} l={l} b={b}")
+                pos = np.searchsorted(s["ids"][l][b], ids_attn[l][b])
+                assert_mass_close(to_np64(lc.mass[b, :len(pos)]), s["mass"][l][b][pos], f"mass t={t} l={l} b={b}")
+                compared += 1
+            k_next = keep[l][t + 1] if t < T else keep[l][t]
+            assert lc.vis_len.cpu().tolist() == [k_next] * B
+    print(f"{w.name}: {compared} of {w.layers * B * T} (layer, sequence, step) triples compared", flush=True)
+    assert compared >= 0.8 * w.layers * B * T

@@ -30,6 +30,23 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert b"workspace" in lib.st3_status_string(3)
 
 
+def test_diagnostic_block_is_inert_without_the_environment_switch():
+    """A process that loads the library without ST3_DEBUG=1 cannot flip its process-wide switches."""
+    import subprocess
+    import sys
+    code = ("import ctypes as C; L = C.CDLL(%r); L.st3_debug_enabled.restype = C.c_int; "
+            "print(L.st3_debug_enabled(), L.st3_debug_set_attend_tile(8), L.st3_debug_set_prefill_path(1), "
+            "L.st3_profile_enable(4), L.st3_profile_read(None, None, None, None))" % st3.LIB_PATH)
+    env = {k: v for k, v in os.environ.items() if k != "ST3_DEBUG"}
+    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, check=True).stdout.split()
+    assert out == ["0", "2", "2", "2", "2"]                 # ST3_ERR_UNSUPPORTED from every setter
+    env["ST3_DEBUG"] = "1"
+    out = subprocess.run([sys.executable, "-c", code.replace("L.st3_profile_enable(4), L.st3_profile_read(None, None, None, None)", "0, 0")],
+                         env=env, capture_output=True, text=True, check=True).stdout.split()
+    assert out[:3] == ["1", "0", "0"]
+    assert st3.st3_debug_enabled()                          # this process: switched on by conftest.py
+
+
 def test_schedule_helpers_match_oracle_on_all_workloads():
     for w in WORKLOADS.values():
         assert np.array_equal(np.array(pipeline.keep_table_for(w)), orc.schedule_for(w)), w.name
