@@ -380,6 +380,11 @@ def select_probe(w, B, torch, st3):
                 tot += e0.elapsed_time(e1)
         return tot / reps * 1e3
 
+    # one plain device-to-device copy of exactly 1 GiB: what FETCH_SIZE / WRITE_SIZE read for it calibrates
+    # those counters when this probe runs under rocprofv3 --pmc
+    cal_src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev); cal_dst = torch.empty_like(cal_src)
+    cal_src.fill_(1); torch.cuda.synchronize(); cal_dst.copy_(cal_src); torch.cuda.synchronize()
+    del cal_src, cal_dst
     rows = []
     # top-k alone (Eq. 3): scores of one prune event
     mask = torch.empty((B, nv), dtype=torch.uint8, device=dev)
