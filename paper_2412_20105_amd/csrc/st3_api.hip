@@ -56,7 +56,9 @@ st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, 
 st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
                           const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
                           void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
-                          bool keep_all_logits, void* workspace, size_t workspace_bytes, hipStream_t st);
+                          bool keep_all_logits, void* workspace, size_t workspace_bytes, hipStream_t st,
+                          bool defer_merge = false);
+bool decode_is_split(const st3_attn_shape* shape, const st3_kv_layer* kv, int32_t max_kv_len);
 
 }  // namespace st3
 
@@ -228,8 +230,10 @@ static st3_status check_step(const st3_attn_shape* shape, int32_t n_layers, cons
 }
 
 // Append + attention of layer i of a checked step; the mass stays pending for the layer's plan.
+// merge_in_plan: strips cut into chunks leave their partials for the layer's plan to merge (the
+// whole-step call); else a merge launch follows the attention and `out` is complete right after it.
 static st3_status enqueue_layer_attend(const st3_attn_shape* shape, const st3_layer_step* layers, int i, bool has_heirs,
-                                       hipStream_t st) {
+                                       hipStream_t st, bool merge_in_plan) {
     const st3_layer_step& L = layers[i];
     if (L.inherit_from >= 0) {
         const st3_layer_step& S = layers[L.inherit_from];
@@ -237,7 +241,8 @@ static st3_status enqueue_layer_attend(const st3_attn_shape* shape, const st3_la
                                S.kv.capacity, L.out, L.workspace, L.workspace_bytes, st);
     }
     return enqueue_decode(shape, L.q, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.k_new, L.v_new, L.out, L.vis_mass,
-                          L.mass_stride, L.vis_mass != nullptr, true, has_heirs, L.workspace, L.workspace_bytes, st);
+                          L.mass_stride, L.vis_mass != nullptr, true, has_heirs, L.workspace, L.workspace_bytes, st,
+                          merge_in_plan);
 }
 
 // Every layer's plan (finish the mass, count the new row, rank, evict) in one launch per 16
@@ -270,7 +275,7 @@ extern "C" st3_status st3_decode_layer_attend(const st3_attn_shape* shape, int32
     if (s != ST3_OK) return s;
     bool has_heirs = false;
     for (int i = layer + 1; i < n_layers; ++i) has_heirs = has_heirs || layers[i].inherit_from == layer;
-    return enqueue_layer_attend(shape, layers, layer, has_heirs, reinterpret_cast<hipStream_t>(stream));
+    return enqueue_layer_attend(shape, layers, layer, has_heirs, reinterpret_cast<hipStream_t>(stream), false);
 }
 
 extern "C" st3_status st3_decode_plans(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
@@ -291,8 +296,24 @@ extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
     st3_status s = check_step(shape, n_layers, layers, mode, plan, needs_apply, has_heirs);
     if (s != ST3_OK) return s;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    // All of a step's inputs are here, so nothing needs a layer's output before the step ends: where
+    // the strips are cut into chunks (B*H alone does not fill the chip) the chunk partials are merged
+    // by the layer's plan instead of by a launch of their own behind every attention.
     for (int i = 0; i < n_layers; ++i) {
-        s = enqueue_layer_attend(shape, layers, i, has_heirs[i] != 0, st);
+        const st3_layer_step& L = layers[i];
+        const bool in_plan = L.inherit_from < 0 && decode_is_split(shape, &L.kv, L.seg.max_kv_len + 1);
+        if (in_plan) {
+            const DecodeWs wl = decode_ws(shape->batch, shape->heads, shape->head_dim, L.kv.capacity);
+            char* ws = reinterpret_cast<char*>(L.workspace);
+            plan[i].merge_part_o = reinterpret_cast<const float*>(ws + wl.part_o);
+            plan[i].merge_out = L.out;
+            plan[i].merge_D = shape->head_dim;
+            plan[i].merge_bf16 = shape->dtype == ST3_BF16 ? 1 : 0;
+            plan[i].part_ml = reinterpret_cast<const float*>(ws + wl.part_ml);
+            plan[i].pending = reinterpret_cast<const int32_t*>(ws + wl.pending);
+            plan[i].nsplit_cap = wl.nsplit_cap;
+        }
+        s = enqueue_layer_attend(shape, layers, i, has_heirs[i] != 0, st, in_plan);
         if (s != ST3_OK) return s;
     }
     return enqueue_plans(plan, needs_apply, shape->batch, st);

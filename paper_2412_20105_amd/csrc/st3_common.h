@@ -71,13 +71,22 @@ constexpr int kMaxWindow = 16;
 #define ST3_DECODE_TARGET_WGS 256      // one workgroup per compute unit; 512-1024 measured 5-14 % slower at B*H = 320-512
 #endif
 constexpr int kDecodeTargetWgs = ST3_DECODE_TARGET_WGS;     // split the KV range until about this many workgroups exist
+#ifndef ST3_DECODE_TARGET_WGS_MERGED
+#define ST3_DECODE_TARGET_WGS_MERGED 1024
+#endif
+// ... and this many when the chunk partials are merged inside the step's plan launch, where a split costs no launch of
+// its own (13B shape, attend launch: B = 4 14.1 -> 11.7 us, B = 8 21.7 -> 20.2 us; 256, 512, 1024, 1536, 2048 measured),
+// unless B*H alone reaches half of it (B*H >= 512 ran the same or slower when cut)
+constexpr int kDecodeTargetWgsMerged = ST3_DECODE_TARGET_WGS_MERGED;
+constexpr int kDecodeTargetWgsMax = kDecodeTargetWgs > kDecodeTargetWgsMerged ? kDecodeTargetWgs : kDecodeTargetWgsMerged;
 constexpr int kDecodeMaxSplit = 64;
 constexpr int kDecodeMinChunk = 64;        // never cut a (b,h) strip into chunks shorter than this
 
 // Number of chunks each (b,h) strip is cut into for a given upper bound on its length.
-inline int decode_nsplit(int B, int H, int max_kv) {
+inline int decode_nsplit(int B, int H, int max_kv, int target_wgs = kDecodeTargetWgs) {
     const int64_t bh = (int64_t)B * H;
-    int64_t want = (kDecodeTargetWgs + bh - 1) / bh;
+    int64_t want = (target_wgs + bh - 1) / bh;
+    if (target_wgs > kDecodeTargetWgs && 2 * bh >= target_wgs) want = 1;
     int64_t by_len = ((int64_t)max_kv + kDecodeMinChunk - 1) / kDecodeMinChunk;
     int64_t ns = want < by_len ? want : by_len;
     if (ns > kDecodeMaxSplit) ns = kDecodeMaxSplit;
@@ -99,7 +108,7 @@ struct DecodeWs {
 inline DecodeWs decode_ws(int B, int H, int D, int capacity) {
     DecodeWs w{};
     if (capacity < 1) capacity = 1;
-    w.nsplit_cap = decode_nsplit(B, H, capacity);
+    w.nsplit_cap = decode_nsplit(B, H, capacity, kDecodeTargetWgsMax);
     w.max_moves = capacity;                 // a stable shift moves every row at most once
     size_t off = 0;
     const size_t BH = (size_t)B * H;

@@ -62,7 +62,7 @@ struct DecodeArgs {
     float* part_o;          // [B,H,nsplit_cap,D]   (nsplit > 1 only)
     float* part_ml;         // [B,H,nsplit_cap,2]
     float* logits;          // [B,H,capacity]; null when no mass is wanted
-    int32_t* pending;       // [B][4]: {mass still to be finished, nsplit, chunk, logits of this call present}
+    int32_t* pending;       // [B][4]: {mass still to be finished | rows attended << 1, nsplit, chunk, logits of this call present}
     const void* k_new;      // [B,H,D] rows of the token being appended (null: none); the cache row
     const void* v_new;      //         kv_len[b] is then taken from here and written to the cache
     void* out;              // [B,H,D]
@@ -134,7 +134,8 @@ void decode_attend_kernel(DecodeArgs a) {
     const int len = lay.vlen;
     const RowShift sh = lay.shift();
     if (split == 0 && h == 0 && tid == 0 && a.pending != nullptr) {
-        a.pending[b * 4 + 0] = (a.logits != nullptr && len > 0 && a.defer) ? 1 : 0;
+        // bit 0: the mass of this launch is still to be finished; above it: the rows this launch attends over
+        a.pending[b * 4 + 0] = ((a.logits != nullptr && len > 0 && a.defer) ? 1 : 0) | (max(len, 0) << 1);
         a.pending[b * 4 + 1] = a.nsplit;
         a.pending[b * 4 + 2] = a.chunk;
         a.pending[b * 4 + 3] = (a.logits != nullptr && len > 0 && a.keep_all_logits) ? 1 : 0;
@@ -644,13 +645,23 @@ st3_status check_kv(const st3_attn_shape* s, const st3_kv_layer* kv, const st3_s
 
 }  // namespace
 
+// Whether a launch over kv_len <= max_kv_len rows cuts its strips into chunks (partials to merge).
+bool decode_is_split(const st3_attn_shape* shape, const st3_kv_layer* kv, int32_t max_kv_len) {
+    const DecodeWs wl = decode_ws(shape->batch, shape->heads, shape->head_dim, kv->capacity);
+    int nsplit = decode_nsplit(shape->batch, shape->heads, max_kv_len, kDecodeTargetWgsMerged);
+    if (nsplit > wl.nsplit_cap) nsplit = wl.nsplit_cap;
+    const int chunk = decode_chunk(max_kv_len, nsplit);
+    return (max_kv_len + chunk - 1) / chunk > 1;
+}
+
 // Enqueues attention (+ the finish kernel when it is needed).  max_kv_len bounds the length the
 // kernels will see (kv_len[b], plus one when a token is appended: k_new/v_new non-null).
 // defer_mass: leave the head reduction of the mass to the eviction plan that follows.
 st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
                           const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
                           void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
-                          bool keep_all_logits, void* workspace, size_t workspace_bytes, hipStream_t st) {
+                          bool keep_all_logits, void* workspace, size_t workspace_bytes, hipStream_t st,
+                          bool defer_merge) {
     const int B = shape->batch, H = shape->heads, D = shape->head_dim;
     const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
     if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
@@ -668,7 +679,7 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
         const int ts = std::min(seg->tail_start_hint, kv->capacity);    // (keeps row + gap far from overflow)
         if (ts > base) { da.hint_base = base; da.hint_gap = ts - base; }
     }
-    da.nsplit = decode_nsplit(B, H, max_kv_len);
+    da.nsplit = decode_nsplit(B, H, max_kv_len, defer_merge ? kDecodeTargetWgsMerged : kDecodeTargetWgs);
     if (da.nsplit > wl.nsplit_cap) da.nsplit = wl.nsplit_cap;
     da.nsplit_cap = wl.nsplit_cap;
     da.chunk = decode_chunk(max_kv_len, da.nsplit);
@@ -687,14 +698,15 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     da.defer = (want_mass && defer_mass) ? 1 : 0;
     ST3_DISPATCH_KV(launch_attend, shape, kv, da, B, st);
     const bool mass_now = want_mass && !defer_mass;
-    if (da.nsplit > 1 || mass_now) {
+    // defer_merge: the caller's eviction plan merges the chunk partials (whole-step call)
+    if ((da.nsplit > 1 && !defer_merge) || mass_now) {
         FinishArgs fa{};
         fa.part_o = da.part_o; fa.part_ml = da.part_ml; fa.logits = da.logits;
         fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len; fa.tail_start = seg->tail_start;
         fa.H = H; fa.nsplit = da.nsplit; fa.nsplit_cap = wl.nsplit_cap; fa.chunk = da.chunk;
         fa.capacity = kv->capacity; fa.max_vis = seg->max_vis_len; fa.max_kv = max_kv_len; fa.sys_len = seg->sys_len;
         fa.appended = k_new != nullptr ? 1 : 0;
-        fa.out = da.nsplit > 1 ? out : nullptr;
+        fa.out = (da.nsplit > 1 && !defer_merge) ? out : nullptr;
         fa.mass = mass_now ? vis_mass : nullptr; fa.mass_stride = mass_stride;
         ST3_DISPATCH(launch_finish, shape, fa, B, st);
     }
@@ -781,7 +793,7 @@ extern "C" st3_status st3_decode_attention(const st3_attn_shape* shape, const vo
     if (vis_mass && mass_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
     return st3::enqueue_decode(shape, q, kv, seg, seg->max_kv_len, nullptr, nullptr, out, vis_mass, mass_stride,
                                vis_mass != nullptr, false, true, workspace, workspace_bytes,
-                               reinterpret_cast<hipStream_t>(stream));
+                               reinterpret_cast<hipStream_t>(stream), false);
 }
 
 extern "C" st3_status st3_decode_attention_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv,

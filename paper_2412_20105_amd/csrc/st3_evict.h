@@ -129,6 +129,11 @@ struct EvictArgs {
     int32_t nsplit_cap;
     float* mass_dst;
     int64_t mass_stride;
+    // chunk partials of the attention output that the attend launch left for this plan to merge
+    // (whole-step call with strips cut into chunks; null: the output is complete already)
+    const float* merge_part_o;  // [B,H,nsplit_cap,D]
+    void* merge_out;            // [B,H,D]
+    int32_t merge_D, merge_bf16;
 };
 
 __device__ __forceinline__ bool flag_at(const SelShared& sm, int p) { return (sm.flags[p >> 5] >> (p & 31)) & 1u; }
@@ -167,6 +172,36 @@ __device__ __forceinline__ void copy_rows_all_strips(const EvictArgs& a, int b, 
     }
 }
 
+// Merges the chunk partials of the output rows of heads [h0, h1) of sequence b in chunk order (what
+// decode_finish_kernel does when the attention is called on its own).  Runs beside the plan
+// workgroup of the same sequence, which rewrites the lengths: the number of rows the attend launch
+// saw therefore comes from the descriptor that launch left, not from the lengths.
+__device__ __forceinline__ void merge_chunks(const EvictArgs& a, int b, int h0, int h1) {
+    const int nsplit = min(a.pending[b * 4 + 1], a.nsplit_cap);
+    const int chunk = max(a.pending[b * 4 + 2], 32);
+    const int seen = a.pending[b * 4] >> 1;
+    const int ns = seen > 0 ? min((seen + chunk - 1) / chunk, nsplit) : 0;
+    if (ns <= 0) return;                                // an empty sequence had its zeros written by the attend launch
+    const int D = a.merge_D;
+    h1 = min(h1, a.H);
+    for (int idx = threadIdx.x; idx < (h1 - h0) * D; idx += blockDim.x) {
+        const int h = h0 + idx / D, d = idx % D;
+        const int64_t bh = (int64_t)b * a.H + h;
+        const float* ml = a.part_ml + bh * a.nsplit_cap * 2;
+        float m = ml[0];
+        for (int s = 1; s < ns; ++s) m = fmaxf(m, ml[2 * s]);
+        float l = 0.f, o = 0.f;
+        for (int s = 0; s < ns; ++s) {
+            const float f = exp2_fast(ml[2 * s] - m);
+            l = fmaf(ml[2 * s + 1], f, l);
+            o = fmaf(a.merge_part_o[(bh * a.nsplit_cap + s) * D + d], f, o);
+        }
+        const float r = o / l;
+        if (a.merge_bf16) reinterpret_cast<uint16_t*>(a.merge_out)[bh * D + d] = (uint16_t)f32_to_bf16_bits(r);
+        else reinterpret_cast<float*>(a.merge_out)[bh * D + d] = r;
+    }
+}
+
 // The whole per-sequence plan, run by one workgroup of kSelThreads threads for sequence b:
 //   1. finish the visual mass the attention kernel left pending (head reduction in head order),
 //   2. rank the visual rows by score_col and evict down to keep_count (columns, and - when
@@ -181,7 +216,7 @@ __device__ __forceinline__ void evict_plan_body(const EvictArgs& a, int b, SelSh
     if (a.pending != nullptr && a.mass_dst != nullptr) {
         // finish the mass the attention call left pending: `len` and `n` are the lengths it saw
         __shared__ float sm_hm[1024], sm_hrl[1024];
-        const int valid = a.pending[b * 4];
+        const int valid = a.pending[b * 4] & 1;
         if (valid) {
             const int nsplit = min(a.pending[b * 4 + 1], a.nsplit_cap);
             const int chunk = max(a.pending[b * 4 + 2], 32);

@@ -312,18 +312,34 @@ struct EvictBatch {
 };
 static_assert(sizeof(EvictBatch) <= 4000, "plans of one batch must fit the kernel argument segment");
 
+constexpr int kMergeHeads = 8;      // heads whose chunk partials one merge workgroup combines
+
+// grid (B, layers of the batch, 1 + merge workgroups): z = 0 runs the plan of (sequence x, layer y);
+// z >= 1 merges the chunk partials of that layer's attention output for kMergeHeads heads (only
+// launched when some layer of the batch left partials to merge).
 __global__ __launch_bounds__(kSelThreads) void evict_plan_batch_kernel(EvictBatch batch) {
     __shared__ SelShared sm;
-    evict_plan_body(batch.layer[blockIdx.y], blockIdx.x, sm);
+    const EvictArgs& a = batch.layer[blockIdx.y];
+    if (blockIdx.z == 0) {
+        evict_plan_body(a, blockIdx.x, sm);
+    } else if (a.merge_out != nullptr && a.pending != nullptr) {
+        const int h0 = ((int)blockIdx.z - 1) * kMergeHeads;
+        if (h0 < a.H) merge_chunks(a, blockIdx.x, h0, h0 + kMergeHeads);
+    }
 }
 
 void launch_evict_plan_batch(const EvictArgs* plans, int n, int B, hipStream_t st) {
     for (int i0 = 0; i0 < n; i0 += kPlanBatch) {
         const int cnt = n - i0 < kPlanBatch ? n - i0 : kPlanBatch;
         EvictBatch batch;
-        for (int i = 0; i < cnt; ++i) batch.layer[i] = plans[i0 + i];
+        int merge_heads = 0;
+        for (int i = 0; i < cnt; ++i) {
+            batch.layer[i] = plans[i0 + i];
+            if (plans[i0 + i].merge_out != nullptr && plans[i0 + i].H > merge_heads) merge_heads = plans[i0 + i].H;
+        }
         for (int i = cnt; i < kPlanBatch; ++i) batch.layer[i] = EvictArgs{};
-        evict_plan_batch_kernel<<<dim3(B, cnt), kSelThreads, 0, st>>>(batch);
+        const int merge_wgs = (merge_heads + kMergeHeads - 1) / kMergeHeads;
+        evict_plan_batch_kernel<<<dim3(B, cnt, 1 + merge_wgs), kSelThreads, 0, st>>>(batch);
     }
 }
 
