@@ -3,8 +3,9 @@
 //
 // Tiling.  A workgroup of 4 wavefronts owns 128 consecutive query rows (32 per wave) of one (b,h)
 // and walks the key tiles of 64 keys up to its diagonal.  K and V tiles live in LDS, row-major, in
-// two buffers.  They get there by direct global-to-LDS loads (no staging registers): the tile after
-// the current one is in flight while the current one is consumed, and a tile costs one barrier.
+// two buffers.  They get there by direct global-to-LDS loads (no staging registers; a strip's base
+// address in scalar registers, 32 bits of offset per lane): the tile after the current one is in
+// flight while the current one is consumed, and a tile costs one barrier.
 // A direct load writes the 64 x 16 bytes of a wave to consecutive LDS addresses, so rows cannot be
 // padded against bank conflicts; instead every lane chooses WHICH 16 bytes of its row it fetches,
 // which stores the row's 16-byte units permuted (unit u of row r holds column unit u ^ swz(r)).
@@ -67,46 +68,63 @@ union Frag {
     i16x4 h[2];
 };
 
-// One wave-wide direct load: every lane fetches the 16 bytes at `src` (global memory) and the wave's
-// 64 x 16 bytes land at LDS byte address lds_base .. lds_base + 1023 in lane order (gfx950:
+// One wave-wide direct load: every lane fetches the 16 bytes at base + lane_byte_off (global memory;
+// the base is the same for all lanes and sits in scalar registers, the offset is 32 bits wide) and
+// the wave's 64 x 16 bytes land at LDS byte address lds_byte_addr .. + 1023 in lane order (gfx950:
 // global_load_lds_dwordx4, LDS base in M0).  Issued through inline assembly: the compiler treats the
 // builtin form as an access that is outstanding on the LDS counter as well, and then makes every
 // later wait for an LDS read a wait for ALL LDS reads in flight, which serialises the fragment
 // reads of the whole tile.  What it does not know about is handled here: wait_direct_loads() before
 // the barrier that publishes a buffer; M0 is declared clobbered; "memory" keeps LDS reads in place.
-__device__ __forceinline__ void direct_load16(const uint16_t* src, const uint16_t* lds_dst) {
-    const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
-        (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const uint16_t*)lds_dst));
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+__device__ __forceinline__ void direct_load16(const uint16_t* base, uint32_t lane_byte_off, uint32_t lds_byte_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_base), "v"(src)
+                 : "s"(lds_byte_addr), "v"(lane_byte_off), "s"(base)
                  : "memory", "m0");
 }
 
-// Starts the direct loads of the K/V tile at key k0 into `buf` (K tile, then V tile).  Rows past
-// n-1 are clamped: such keys lie above every valid query's diagonal and are masked there.  Every
-// address read is a row of the caller's tensors; every LDS address written lies inside `buf`.
-// kl / vl: this lane's K and V source at key 0 of its first 1 KB group (row and permuted unit folded in).
+// A value that is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ const uint16_t* uniform_ptr(const uint16_t* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const uint16_t*>(((uint64_t)hi << 32) | lo);
+}
+
+// LDS byte address of a __shared__ object.
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)p);
+}
+
+// Starts the direct loads of the K/V tile at key k0 into the buffer at LDS byte address `lds_buf` (K
+// tile, then V tile).  Rows past n-1 are clamped: such keys lie above every valid query's diagonal
+// and are masked there.  Every address read is a row of the caller's tensors; every LDS address
+// written lies inside the buffer.
+// Kp / Vp: row 0 of the strip (uniform).  k_lane / v_lane: byte offset of this lane's 16 bytes within
+// the first 1 KB group of a tile at key 0 (row min(row0, n-1) and permuted unit folded in).
+// Offsets from the strip's row 0 fit 32 bits (checked by the launcher).  wave_s: the wave's index, scalar.
 template <int D>
-__device__ __forceinline__ void issue_tile(uint16_t* buf, const uint16_t* kl, const uint16_t* vl, int64_t k_st,
-                                           int64_t v_st, int k0, int n, int lane, int wave) {
+__device__ __forceinline__ void issue_tile(uint32_t lds_buf, const uint16_t* Kp, const uint16_t* Vp, uint32_t k_lane,
+                                           uint32_t v_lane, int64_t k_st, int64_t v_st, int k0, int n, int lane, int wave,
+                                           int wave_s) {
     using L = TileLayout<D>;
     const int row0 = wave * L::RPI + lane / L::UPR;     // this lane's row in the wave's first group
     if (k0 + kBN <= n) {                                // all rows of the tile exist: plain strides
 #pragma unroll
         for (int i = 0; i < L::NI; ++i) {
-            const int grp = 4 * i + wave;               // which 1 KB of the tile this wave-wide load fills
+            const uint32_t dst = lds_buf + (4 * i + wave_s) * 1024;    // which 1 KB of the tile this wave-wide load fills
             const int key = k0 + 4 * i * L::RPI;
-            direct_load16(kl + key * k_st, buf + grp * 512);
-            direct_load16(vl + key * v_st, buf + L::TILE + grp * 512);
+            direct_load16(uniform_ptr(Kp + key * k_st), k_lane, dst);
+            direct_load16(uniform_ptr(Vp + key * v_st), v_lane, dst + 2 * L::TILE);
         }
     } else {
+        const uint16_t* Ku = uniform_ptr(Kp);
+        const uint16_t* Vu = uniform_ptr(Vp);
 #pragma unroll
         for (int i = 0; i < L::NI; ++i) {
-            const int grp = 4 * i + wave;
+            const uint32_t dst = lds_buf + (4 * i + wave_s) * 1024;
             const int key = max(0, min(k0 + 4 * i * L::RPI, n - 1 - row0));     // this lane's row, key + row0, stays <= n - 1
-            direct_load16(kl + key * k_st, buf + grp * 512);
-            direct_load16(vl + key * v_st, buf + L::TILE + grp * 512);
+            direct_load16(Ku, k_lane + (uint32_t)key * (uint32_t)(2 * k_st), dst);
+            direct_load16(Vu, v_lane + (uint32_t)key * (uint32_t)(2 * v_st), dst + 2 * L::TILE);
         }
     }
 }
@@ -144,22 +162,31 @@ __device__ __forceinline__ void tile_step(const uint16_t* Kt, const uint16_t* Vt
                                           int k0, int myq, float* lg_row, int vis_lo, int vis_hi) {
     constexpr int KS = D / 16, DT = D / 32;
     // LDS reads are issued in batches ahead of their use, so that their latency is paid once per
-    // batch and not once per MFMA: all K fragments of the step before its first MFMA.
-    Frag ka[NSUB][KS];
+    // batch and not once per MFMA: K fragments in groups of four contraction steps, the next group on
+    // its way while the current one is multiplied.
+    // ---- S^T = K Q^T ----------------------------------------------------------------------------
+    constexpr int KG = 4, GPS = KS / KG, NG = NSUB * GPS;       // steps per group, groups per sub-tile, groups
+    Frag ka[2][KG];
+    f32x16 sacc[NSUB];
 #pragma unroll
     for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
-        for (int s = 0; s < KS; ++s) ka[sub][s].u4 = *reinterpret_cast<const u32x4*>(Kt + 32 * sub * D + lm.koff[s]);
-    __builtin_amdgcn_sched_barrier(0);
-    // ---- S^T = K Q^T ----------------------------------------------------------------------------
-    f32x16 sacc[NSUB];
-#pragma unroll
-    for (int sub = 0; sub < NSUB; ++sub) {
-#pragma unroll
         for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
 #pragma unroll
-        for (int s = 0; s < KS; ++s)
-            sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[sub][s].v, qf[s].v, sacc[sub], 0, 0, 0);
+    for (int s = 0; s < KG; ++s) ka[0][s].u4 = *reinterpret_cast<const u32x4*>(Kt + lm.koff[s]);
+#pragma unroll
+    for (int grp = 0; grp < NG; ++grp) {
+        if (grp + 1 < NG) {
+            const int sub = (grp + 1) / GPS, s0 = ((grp + 1) % GPS) * KG;
+#pragma unroll
+            for (int s = 0; s < KG; ++s)
+                ka[(grp + 1) & 1][s].u4 = *reinterpret_cast<const u32x4*>(Kt + 32 * sub * D + lm.koff[s0 + s]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const int sub = grp / GPS, s0 = (grp % GPS) * KG;
+#pragma unroll
+        for (int s = 0; s < KG; ++s)
+            sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[grp & 1][s].v, qf[s0 + s].v, sacc[sub], 0, 0, 0);
     }
     Frag va[2][DT];                     // V^T fragments of the 16-key group in use and of the next one
 #pragma unroll
@@ -305,18 +332,19 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
     const uint16_t* Kp = reinterpret_cast<const uint16_t*>(a.k) + b * a.k_sb + h * a.k_sh;
     const uint16_t* Vp = reinterpret_cast<const uint16_t*>(a.v) + b * a.v_sb + h * a.v_sh;
 
-    // this lane's source of the direct loads: row (wave * RPI + lane / UPR) of a 1 KB group, and the
+    // this lane's part of the direct loads' source: row (wave * RPI + lane / UPR) of a 1 KB group, and the
     // 16-byte unit that the permutation assigns to its LDS slot (the permutations repeat every RPI * 4
-    // rows or sooner, so they are the same for every group and every tile)
-    const uint16_t* kl;
-    const uint16_t* vl;
+    // rows or sooner, so they are the same for every group and every tile), as a byte offset
+    uint32_t k_lane, v_lane;
     {
         const int row0 = wave * L::RPI + lane / L::UPR, u = lane % L::UPR;
         const int rowc = min(row0, n - 1);              // a prompt shorter than one group of rows
-        kl = Kp + (int64_t)rowc * a.k_st + (u ^ L::k_swz(row0)) * 8;
-        vl = Vp + (int64_t)rowc * a.v_st + (u ^ L::v_swz(row0)) * 8;
+        k_lane = (uint32_t)(2 * (rowc * a.k_st + (u ^ L::k_swz(row0)) * 8));
+        v_lane = (uint32_t)(2 * (rowc * a.v_st + (u ^ L::v_swz(row0)) * 8));
     }
-    issue_tile<D>(buf0, kl, vl, a.k_st, a.v_st, 0, n, lane, wave);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);     // for scalar address arithmetic only
+    const uint32_t lds0 = lds_addr(buf0), lds1 = lds_addr(buf1);
+    issue_tile<D>(lds0, Kp, Vp, k_lane, v_lane, a.k_st, a.v_st, 0, n, lane, wave, wave_s);
     Frag qf[KS];
     {
         const uint16_t* qrow = Qp + (int64_t)min(myq, n - 1) * a.q_st;
@@ -347,13 +375,13 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
     // Tiles alternate between the buffers; the loop body handles one pair.  A buffer is refilled one
     // iteration after its last read, and every wave has passed a barrier in between.
     for (int t = 0; t < nt; t += 2) {
-        if (t + 1 < nt) issue_tile<D>(buf1, kl, vl, a.k_st, a.v_st, (t + 1) * kBN, n, lane, wave);
+        if (t + 1 < nt) issue_tile<D>(lds1, Kp, Vp, k_lane, v_lane, a.k_st, a.v_st, (t + 1) * kBN, n, lane, wave, wave_s);
         if (wave_live && t * kBN <= q0)                 // else the tile lies entirely above this wave's diagonal
             consume_tile<D>(buf0, t * kBN, q0, qf, oacc, m_i, l_i, a.scale_l2, lm, c, g, myq, lg_row, vis_lo, vis_hi);
         wait_direct_loads();
         __syncthreads();
         if (t + 1 >= nt) break;
-        if (t + 2 < nt) issue_tile<D>(buf0, kl, vl, a.k_st, a.v_st, (t + 2) * kBN, n, lane, wave);
+        if (t + 2 < nt) issue_tile<D>(lds0, Kp, Vp, k_lane, v_lane, a.k_st, a.v_st, (t + 2) * kBN, n, lane, wave, wave_s);
         if (wave_live && (t + 1) * kBN <= q0)
             consume_tile<D>(buf1, (t + 1) * kBN, q0, qf, oacc, m_i, l_i, a.scale_l2, lm, c, g, myq, lg_row, vis_lo, vis_hi);
         wait_direct_loads();
@@ -377,9 +405,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 const int dd = 32 * dt + 8 * rq + 4 * g;
-                uint2 pk;
-                pk.x = f32_to_bf16_bits(oacc[dt][4 * rq] * rl) | (f32_to_bf16_bits(oacc[dt][4 * rq + 1] * rl) << 16);
-                pk.y = f32_to_bf16_bits(oacc[dt][4 * rq + 2] * rl) | (f32_to_bf16_bits(oacc[dt][4 * rq + 3] * rl) << 16);
+                const f32x2 o01 = {oacc[dt][4 * rq] * rl, oacc[dt][4 * rq + 1] * rl};
+                const f32x2 o23 = {oacc[dt][4 * rq + 2] * rl, oacc[dt][4 * rq + 3] * rl};
+                uint2 pk;                               // packed conversion, round to nearest even
+                pk.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(o01, bf16x2));
+                pk.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(o23, bf16x2));
                 *reinterpret_cast<uint2*>(obuf + c * OSTR + dd) = pk;
             }
         uint16_t* obase = reinterpret_cast<uint16_t*>(a.out) + b * a.o_sb + h * a.o_sh;
@@ -407,6 +437,8 @@ st3_status launch_prefill_mfma(const PrefillArgs& a, int B, int D, hipStream_t s
     pa.B = B;
     const int64_t wgs = (int64_t)pa.n_qt * a.H * B;
     if (wgs > 0x7fffffff) return ST3_ERR_UNSUPPORTED;
+    // the direct loads address a strip as a scalar base plus a 32-bit byte offset
+    if ((int64_t)a.n * a.k_st * 2 >= (int64_t)1 << 31 || (int64_t)a.n * a.v_st * 2 >= (int64_t)1 << 31) return ST3_ERR_UNSUPPORTED;
     dim3 grid((unsigned)wgs);
     if (D == 128) prefill_mfma_kernel<128><<<grid, 256, 0, st>>>(pa);
     else if (D == 64) prefill_mfma_kernel<64><<<grid, 256, 0, st>>>(pa);
