@@ -13,6 +13,7 @@ struct PrefillArgs {
     int64_t o_sb, o_sh, o_st;
     int32_t n, sys_len, vis_len, window, H;
     int32_t B, n_qt;                // batch and query tiles per strip (filled in by the MFMA launcher)
+    int32_t q_shift;                // rows by which the query tiles start before row 0 (MFMA launcher)
     float scale_l2;                 // softmax scale times log2(e)
     float* pre_logits;              // [B,H,W,vis_len] log2-domain logits of the last W rows (null: no mass)
     float* pre_ml;                  // [B,H,W,2] row max and row sum of those rows

@@ -324,7 +324,12 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, c = lane & 31;
     const int n = a.n;
-    const int q0 = qt * kBM + wave * 32;
+    // Query tiles are cut from the END of the prompt in whole 32-row blocks: the blocks that a prompt
+    // of no multiple of 128 rows leaves empty then sit at the front of a strip's FIRST tile, the one
+    // that walks the fewest key tiles, and not behind its last (the one that walks them all).  Such a
+    // wave has q0 < 0 and only helps to load tiles.  (Blocks stay aligned to 32 rows and key tiles to
+    // 64, which is what the diagonal handling relies on.)
+    const int q0 = qt * kBM + wave * 32 - a.q_shift;
     const int myq = q0 + c;
     const int64_t bh = (int64_t)b * a.H + h;
 
@@ -347,7 +352,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
     issue_tile<D>(lds0, Kp, Vp, k_lane, v_lane, a.k_st, a.v_st, 0, n, lane, wave, wave_s);
     Frag qf[KS];
     {
-        const uint16_t* qrow = Qp + (int64_t)min(myq, n - 1) * a.q_st;
+        const uint16_t* qrow = Qp + (int64_t)max(0, min(myq, n - 1)) * a.q_st;
 #pragma unroll
         for (int s = 0; s < KS; ++s) qf[s].u4 = *reinterpret_cast<const u32x4*>(qrow + 16 * s + 8 * g);
     }
@@ -361,15 +366,15 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
     float m_i = -INFINITY, l_i = 0.f;
 
     // window rows (the last W queries) held by this wave?
-    const bool wave_has_window = a.pre_logits != nullptr && q0 + 31 >= n - a.window && q0 < n;
+    const bool wave_has_window = a.pre_logits != nullptr && q0 + 31 >= n - a.window && q0 < n && q0 >= 0;
     const int w_idx = myq - (n - a.window);
     const bool lane_in_window = wave_has_window && w_idx >= 0 && myq < n;
     float* lg_row = lane_in_window ? a.pre_logits + (bh * a.window + w_idx) * a.vis_len : nullptr;
     const int vis_lo = a.sys_len, vis_hi = a.sys_len + a.vis_len;
 
-    const int k_end = min(n, qt * kBM + kBM);           // keys this workgroup can see
+    const int k_end = min(n, qt * kBM + kBM - a.q_shift);   // keys this workgroup can see
     const int nt = (k_end + kBN - 1) / kBN;
-    const bool wave_live = q0 < n;                      // else all 32 queries lie beyond the prompt (ragged last tile)
+    const bool wave_live = q0 >= 0 && q0 < n;           // else all 32 queries lie outside the prompt
     wait_direct_loads();
     __syncthreads();
     // Tiles alternate between the buffers; the loop body handles one pair.  A buffer is refilled one
@@ -417,7 +422,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
         for (int i = 0; i < 32 / RPI; ++i) {
             const int r = i * RPI + lane / VPR;
             const u32x4 val = *reinterpret_cast<const u32x4*>(obuf + r * OSTR + (lane % VPR) * 8);
-            if (q0 + r < n) *reinterpret_cast<u32x4*>(obase + (int64_t)(q0 + r) * a.o_st + (lane % VPR) * 8) = val;
+            if (wave_live && q0 + r < n) *reinterpret_cast<u32x4*>(obase + (int64_t)(q0 + r) * a.o_st + (lane % VPR) * 8) = val;
         }
     }
     if (myq < n) {
@@ -434,6 +439,7 @@ st3_status launch_prefill_mfma(const PrefillArgs& a, int B, int D, hipStream_t s
     // 8-byte output stores and 16-byte input loads need these alignments (rows are 16-byte aligned already)
     PrefillArgs pa = a;
     pa.n_qt = (a.n + kBM - 1) / kBM;
+    pa.q_shift = (pa.n_qt * kBM - a.n) / 32 * 32;       // whole empty 32-row blocks, moved to the front
     pa.B = B;
     const int64_t wgs = (int64_t)pa.n_qt * a.H * B;
     if (wgs > 0x7fffffff) return ST3_ERR_UNSUPPORTED;
