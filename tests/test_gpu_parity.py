@@ -690,6 +690,27 @@ def test_prefill_attention_matches_oracle(dtype, D, B, H, n, ns, nv, W):
     assert np.all(to_np64(mass)[:, nv:] == -3.0)
 
 
+@pytest.mark.parametrize("n", [129, 160, 161, 224, 257, 289, 321, 353, 385, 416, 449, 512, 513])
+def test_prefill_query_tiles_cut_from_the_end(n):
+    """The MFMA kernel cuts its 128-row query tiles from the end of the prompt in 32-row blocks, so a strip's
+    first tile starts 0, 32, 64 or 96 rows before row 0: every such offset, with one to four tiles behind it."""
+    print(f"prefill end-aligned tiles n={n}", flush=True)
+    rng = np.random.default_rng(7700 + n)
+    B, H, D, ns, W = 1, 2, 128, 5, 2
+    nv = n - ns - 3
+    Q, K, V = (rand_values(rng, (B, H, n, D), "bf16", 1.43) for _ in range(3))
+    shape = st3.make_shape(B, H, D, CODE["bf16"])
+    out = torch.full((B, H, n + 1, D), 7.0, dtype=torch.bfloat16, device=DEV)     # one guard row behind the prompt
+    mass = torch.zeros((B, nv), dtype=torch.float32, device=DEV)
+    st3.st3_prefill_attention(shape, to_dev(Q, "bf16"), to_dev(K, "bf16"), to_dev(V, "bf16"), n, ns, nv, W,
+                              out[:, :, :n], mass, _ws(shape, n, nv, W))
+    torch.cuda.synchronize()
+    O, m = orc.prefill_attention(Q, K, V, ns, nv, W)
+    assert_attention_close(to_np64(out[:, :, :n]), O, "bf16")
+    assert_mass_close(to_np64(mass), m)
+    assert np.all(to_np64(out[:, :, n]) == 7.0)
+
+
 # ---------------------------------------------------------------------------
 # diagnostics: Overlap_n (Eq. 10), cosine similarity (Eq. 4-5)
 # ---------------------------------------------------------------------------
