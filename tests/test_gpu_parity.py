@@ -711,6 +711,27 @@ def test_prefill_query_tiles_cut_from_the_end(n):
     assert np.all(to_np64(out[:, :, n]) == 7.0)
 
 
+def test_prefill_rows_two_gib_apart_take_the_row_kernel():
+    """The MFMA kernel addresses a strip as a scalar base plus 32 bits of offset; K and V whose rows lie so far
+    apart that a strip spans 2 GiB or more must still come out right (the row kernel serves them)."""
+    n, B, H, D, ns, nv, W = 3, 1, 2, 128, 0, 3, 1
+    stride_t = 1 << 29                                              # elements: 1 GiB between consecutive rows
+    print(f"prefill with stride_t={stride_t} elements", flush=True)
+    rng = np.random.default_rng(4242)
+    Q, K, V = (rand_values(rng, (B, H, n, D), "bf16", 1.43) for _ in range(3))
+    shape = st3.make_shape(B, H, D, CODE["bf16"])
+    big = [torch.zeros(((n - 1) * stride_t + H * D,), dtype=torch.bfloat16, device=DEV) for _ in range(2)]
+    views = [b.as_strided((B, H, n, D), (0, D, stride_t, 1)) for b in big]
+    views[0].copy_(to_dev(K, "bf16")); views[1].copy_(to_dev(V, "bf16"))
+    out = torch.zeros((B, H, n, D), dtype=torch.bfloat16, device=DEV)
+    mass = torch.zeros((B, nv), dtype=torch.float32, device=DEV)
+    st3.st3_prefill_attention(shape, to_dev(Q, "bf16"), views[0], views[1], n, ns, nv, W, out, mass, _ws(shape, n, nv, W))
+    torch.cuda.synchronize()
+    O, m = orc.prefill_attention(Q, K, V, ns, nv, W)
+    assert_attention_close(to_np64(out), O, "bf16")
+    assert_mass_close(to_np64(mass), m)
+
+
 # ---------------------------------------------------------------------------
 # diagnostics: Overlap_n (Eq. 10), cosine similarity (Eq. 4-5)
 # ---------------------------------------------------------------------------
