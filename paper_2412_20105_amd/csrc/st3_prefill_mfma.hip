@@ -285,8 +285,9 @@ __device__ __forceinline__ void consume_tile(const uint16_t* buf, int k0, int q0
 }
 
 // One-dimensional grid of ceil(n/128) * H * B workgroups (the mapping to query tile and strip is in the kernel).
-// Register budget: two waves per SIMD (256 registers each), so that one wave's softmax VALU work
-// overlaps the other's MFMAs; the accumulator is only rescaled when some row's maximum actually moved.
+// Register budget: two waves per SIMD (256 registers each; the kernel takes 214), i.e. two workgroups
+// per compute unit: while one waits for a tile, a barrier or its first loads, the other one runs.
+// (MFMA and VALU work of the two waves of a SIMD add up rather than overlap on this part: measured.)
 template <int D>
 __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
     using L = TileLayout<D>;
