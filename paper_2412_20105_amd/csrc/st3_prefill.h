@@ -17,7 +17,6 @@ struct PrefillArgs {
     float scale_l2;                 // softmax scale times log2(e)
     float* pre_logits;              // [B,H,W,vis_len] log2-domain logits of the last W rows (null: no mass)
     float* pre_ml;                  // [B,H,W,2] row max and row sum of those rows
-    unsigned int* tickets;          // item counters of the persistent MFMA kernel (filled in by its launcher)
 };
 
 // bf16 only; returns ST3_ERR_UNSUPPORTED for shapes it does not handle.

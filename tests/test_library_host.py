@@ -143,6 +143,28 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.st3_decode_step(C.byref(sh), 2, steps, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_INVALID_ARG
     steps[1].inherit_from = 1                       # a layer cannot inherit from itself or from a later layer
     assert lib.st3_decode_step(C.byref(sh), 2, steps, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_INVALID_ARG
+    # the step in two parts: the same refusals, layer by layer and for the plans; a layer index outside the array
+    assert lib.st3_decode_layer_attend(C.byref(sh), 2, steps, 1, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_INVALID_ARG
+    assert lib.st3_decode_layer_attend(C.byref(sh), 2, steps, 2, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_INVALID_ARG
+    assert lib.st3_decode_layer_attend(C.byref(sh), 2, steps, -1, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_INVALID_ARG
+    assert lib.st3_decode_layer_attend(C.byref(bad), 2, steps, 0, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_UNSUPPORTED
+    assert lib.st3_decode_plans(C.byref(sh), 2, steps, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_INVALID_ARG
+    assert lib.st3_decode_plans(C.byref(sh), 0, steps, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_INVALID_ARG
+    steps[1].inherit_from = -1
+    steps[1].kv = steps[0].kv
+    assert lib.st3_decode_plans(C.byref(sh), 2, steps, 7, None) == st3.ST3_ERR_INVALID_ARG            # no such mode
+    steps[0].seg = st3.Segments(8, 64, 128, fake, fake)                                                 # no room for the appended row
+    assert lib.st3_decode_layer_attend(C.byref(sh), 2, steps, 0, st3.ST3_HOLE_FILL, None) == st3.ST3_ERR_INVALID_ARG
+    # the allocation-free decode attention: null query; a shape whose scratch does not fit the library's array
+    assert lib.st3_decode_attention_noalloc(C.byref(sh), None, C.byref(kv), C.byref(seg), fake, None, 0,
+                                            None) == st3.ST3_ERR_INVALID_ARG
+    big = st3.make_shape(64, 40, 128, st3.ST3_BF16)
+    cap = 4096
+    kv_big = st3.KvLayer(fake, fake, 40 * cap * 128, cap * 128, 128, cap)
+    seg_b = st3.Segments(8, 64, 100, fake, fake)
+    assert st3.st3_workspace_bytes(big, cap, 64, 1) > st3.ST3_NOALLOC_SCRATCH_BYTES
+    assert lib.st3_decode_attention_noalloc(C.byref(big), fake, C.byref(kv_big), C.byref(seg_b), fake, None, 0,
+                                            None) == st3.ST3_ERR_WORKSPACE_TOO_SMALL
     # schedule helpers
     assert lib.st3_schedule_pvtp(32, 576, 3, 0, 5000, 100, fake) == st3.ST3_ERR_INVALID_ARG
     assert lib.st3_schedule_anneal(0, C.c_double(0.0), 4, fake, 2, fake) == st3.ST3_ERR_INVALID_ARG
