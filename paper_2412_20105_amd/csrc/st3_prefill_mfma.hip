@@ -129,6 +129,15 @@ __device__ __forceinline__ void issue_tile(uint32_t lds_buf, const uint16_t* Kp,
     }
 }
 
+// x of this lane and x of lane ^ 32 (v_permlane32_swap: lanes 32..63 of its first operand trade places
+// with lanes 0..31 of its second; with both operands x, the one ends up holding the lower half's
+// values in both halves and the other the upper half's).  No LDS round trip, unlike a shuffle.
+__device__ __forceinline__ void both_halves(float x, float& a, float& b) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+
 // All direct loads this wave has issued have landed in LDS (vmcnt(0); other counters untouched).
 __device__ __forceinline__ void wait_direct_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
@@ -215,7 +224,11 @@ __device__ __forceinline__ void tile_step(const uint16_t* Kt, const uint16_t* Vt
     for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[sub][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    {
+        float lo_half, hi_half;
+        both_halves(mx, lo_half, hi_half);
+        mx = fmaxf(lo_half, hi_half);
+    }
     // every row sees the first key of every tile it gets here (k0 <= q0 <= myq), so mx is finite.
     // The reference point m_i of the exponents only follows the row maximum when that has moved by
     // more than kLazy (probabilities then reach 2^kLazy at most, far inside fp32 and bf16 range):
@@ -394,7 +407,9 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(PrefillArgs a) {
         __syncthreads();
     }
     // ---- normalise and store -----------------------------------------------------------------
-    const float l_tot = l_i + __shfl_xor(l_i, 32);
+    float l_lo, l_hi;
+    both_halves(l_i, l_lo, l_hi);
+    const float l_tot = l_lo + l_hi;
     const float rl = 1.0f / l_tot;
     // The accumulator holds O transposed (a lane owns one query and, per register quad, 4 consecutive
     // columns): stored straight from there, a wave-wide store would touch 32 rows with 8 bytes each.
