@@ -120,11 +120,12 @@ class Job:
         for l in range(w.layers):
             q, k, v = self.pre[l]
             gen.prefill_layer(l, q, k, v)
+        one = self.B * w.heads * w.head_dim * self.dec[0].element_size()        # bytes of one [B,H,d] input
         for t in range(1, self.T + 1):
-            d = self.dec[t - 1]
+            base = self.dec[t - 1].data_ptr()                                   # [L, 3, B, H, d]: q, k_new, v_new per layer
             gen.begin_step(t)
             for l in range(w.layers):
-                gen.attend_layer(l, d[l, 0], d[l, 1], d[l, 2])
+                gen.attend_layer(l, base + 3 * l * one, base + (3 * l + 1) * one, base + (3 * l + 2) * one)
             gen.finish_step()
 
     def run_prefill_only(self):

@@ -296,24 +296,28 @@ class Generation:
             self.begin_decode()
         self._set_step_bounds(t)
         self._open_step = t
+        self._step_stream = torch.cuda.current_stream().cuda_stream    # looked up once per step, not once per layer
+        if getattr(self, "_out_views", None) is None:
+            self._out_views = [self.dec_out_all[l] for l in range(self.L)]
 
-    def attend_layer(self, l: int, q: Optional[torch.Tensor], k_new: Optional[torch.Tensor], v_new: torch.Tensor):
-        """Layer l of the open step: append k_new/v_new and attend.  q, k_new, v_new: device [B,H,d], alive until
-        the stream has run the call (a lazy layer ignores q and k_new).  Returns out [B,H,d], complete once the
-        stream has run the call - before any later layer's inputs need to exist."""
+    def attend_layer(self, l: int, q, k_new, v_new):
+        """Layer l of the open step: append k_new/v_new and attend.  q, k_new, v_new: device [B,H,d] tensors or
+        their device addresses, alive until the stream has run the call (a lazy layer ignores q and k_new, which
+        may be None).  Returns out [B,H,d], complete once the stream has run the call - before any later layer's
+        inputs need to exist."""
         arr = self._steps
         s = arr[l]
-        any_ptr = v_new.data_ptr()
-        s.q = any_ptr if q is None else q.data_ptr()
-        s.k_new = any_ptr if k_new is None else k_new.data_ptr()
-        s.v_new = v_new.data_ptr()
-        st3.st3_decode_layer_attend(self.shape, arr, self.L, l, self.compact_mode)
-        return self.dec_out_all[l]
+        v_ptr = v_new if isinstance(v_new, int) else v_new.data_ptr()
+        s.q = v_ptr if q is None else (q if isinstance(q, int) else q.data_ptr())
+        s.k_new = v_ptr if k_new is None else (k_new if isinstance(k_new, int) else k_new.data_ptr())
+        s.v_new = v_ptr
+        st3.st3_decode_layer_attend(self.shape, arr, self.L, l, self.compact_mode, self._step_stream)
+        return self._out_views[l]
 
     def finish_step(self):
         """Closes the open step: masses, appended rows counted, evictions of every layer."""
         t = self._open_step
-        st3.st3_decode_plans(self.shape, self._steps, self.L, self.compact_mode)
+        st3.st3_decode_plans(self.shape, self._steps, self.L, self.compact_mode, self._step_stream)
         self._advance_host_lengths(t)
         self._open_step = None
 
