@@ -62,6 +62,7 @@ struct DecodeArgs {
     float* part_o;          // [B,H,nsplit_cap,D]   (nsplit > 1 only)
     float* part_ml;         // [B,H,nsplit_cap,2]
     float* logits;          // [B,H,capacity]; null when no mass is wanted
+    int32_t stage_rows;     // logits a workgroup keeps are collected in this many floats of LDS (0: stored one by one)
     int32_t* pending;       // [B][4]: {mass still to be finished | rows attended << 1, nsplit, chunk, logits of this call present}
     const void* k_new;      // [B,H,D] rows of the token being appended (null: none); the cache row
     const void* v_new;      //         kv_len[b] is then taken from here and written to the cache
@@ -185,12 +186,29 @@ void decode_attend_kernel(DecodeArgs a) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (c0 + wave * TILE + u * M::RPL + lane / LPR >= c1_cached) vr[u] = make_uint4(0, 0, 0, 0);
-    wave_attend_primed<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
-                                       c0, scale_l2, lane, st, lg, vis_lo, vis_hi, kr, vr, sh);
+    // The logits this workgroup keeps (rows [lg_lo, lg_hi) of its chunk) are collected in LDS and leave
+    // as whole lines after the waves have merged: stored one by one from the loop (16 bytes per wave
+    // and tile) they cost 2 us of a 66 us launch at the 13B shape.  A chunk that keeps more rows than
+    // the staging area holds (stage_rows == 0, decided by the launcher) stores them directly.
+    extern __shared__ float sm_lg[];
+    const bool staged = lg != nullptr && a.stage_rows > 0;
+    const int lg_lo = max(c0, vis_lo), lg_hi = min(c1, vis_hi);
+    if (staged) {
+        wave_attend_primed<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
+                                           c0, scale_l2, lane, st, sm_lg, lg_lo, vis_hi, kr, vr, sh);
+    } else {
+        wave_attend_primed<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
+                                           c0, scale_l2, lane, st, lg, vis_lo, vis_hi, kr, vr, sh);
+    }
     if (has_new && wave == 0) {
-        wave_attend_row<KT, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
-                               make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, scale_l2, lane, st, lg, vis_lo,
-                              vis_hi);
+        if (staged)
+            wave_attend_row<KT, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
+                                   make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, scale_l2, lane, st, sm_lg,
+                                   lg_lo, vis_hi);
+        else
+            wave_attend_row<KT, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
+                                   make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, scale_l2, lane, st, lg,
+                                   vis_lo, vis_hi);
         if (lane < 2 * LPR) {                       // store the row into the cache: lanes [0,LPR) K, [LPR,2*LPR) V
             KT* dst = (lane < LPR ? kbase : vbase) + (int64_t)(len_phys - 1) * a.stride_t + (lane % LPR) * EPL;
             *reinterpret_cast<u32x4_t*>(dst) = lane < LPR ? kn_raw : vn_raw;
@@ -206,6 +224,9 @@ void decode_attend_kernel(DecodeArgs a) {
     }
     if (lane == 0) { sm_m[wave] = st.m; sm_l[wave] = st.l; }
     __syncthreads();
+    if (staged) {
+        for (int i = tid; i < lg_hi - lg_lo; i += kDecodeThreads) lg[lg_lo - vis_lo + i] = sm_lg[i];
+    }
     if (tid < D) {
         float m = sm_m[0];
 #pragma unroll
@@ -522,6 +543,10 @@ int resident_workgroups(K kernel, std::atomic<int>* cache) {
     return n;
 }
 
+// Largest logit staging area of a decode_attend_kernel workgroup (floats): 16 KB, so that the seven workgroups a
+// compute unit holds at most still fit its 160 KB of LDS; chunks that keep more logits store them directly.
+constexpr int kLogitStageMaxRows = 4096;
+
 // Time of a launch of `items` equal workgroups on `slots` concurrent ones, relative to a launch whose
 // last round is full.
 inline double last_round_cost(int64_t items, int slots) {
@@ -540,11 +565,12 @@ inline int cheapest(const double* cost, int n) {
 template <typename T, typename KT, int D, int U>
 void launch_attend_u(const DecodeArgs& da, int B, hipStream_t st) {
     const dim3 grid(da.nsplit, da.H, B);
+    const size_t lds = (size_t)da.stage_rows * sizeof(float);       // dynamic LDS: the logit staging area
     hipEvent_t e0, e1;
     if (profile_take(&e0, &e1))     // timed launch: the events receive the kernel's own start and end
-        hipExtLaunchKernelGGL((decode_attend_kernel<T, KT, D, U>), grid, dim3(kDecodeThreads), 0, st, e0, e1, 0, da);
+        hipExtLaunchKernelGGL((decode_attend_kernel<T, KT, D, U>), grid, dim3(kDecodeThreads), lds, st, e0, e1, 0, da);
     else
-        decode_attend_kernel<T, KT, D, U><<<grid, kDecodeThreads, 0, st>>>(da);
+        decode_attend_kernel<T, KT, D, U><<<grid, kDecodeThreads, lds, st>>>(da);
 }
 
 // Takes the cheapest of the builds Us... (in order of preference) for this launch.
@@ -692,6 +718,10 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     da.part_ml = reinterpret_cast<float*>(ws + wl.part_ml);
     da.logits = (want_mass || keep_all_logits) ? reinterpret_cast<float*>(ws + wl.logits) : nullptr;
     da.keep_all_logits = keep_all_logits ? 1 : 0;
+    if (da.logits != nullptr) {     // a workgroup keeps at most this many logits: all rows of its chunk, or the visual ones
+        const int rows = keep_all_logits ? da.chunk : std::min(da.chunk, seg->max_vis_len);
+        da.stage_rows = rows <= kLogitStageMaxRows ? rows : 0;
+    }
     da.pending = reinterpret_cast<int32_t*>(ws + wl.pending);
     da.k_new = k_new; da.v_new = v_new;
     da.out = out;

@@ -106,6 +106,29 @@ def test_decode_attention_over_a_long_cache_cut_into_the_maximum_number_of_chunk
     assert_mass_close(to_np64(mass)[0], m[0], "long cache")
 
 
+def test_decode_attention_with_more_visual_keys_per_chunk_than_the_logit_staging_holds():
+    """A workgroup collects the logits it keeps for the mass in LDS (up to 4096 of them) and stores them directly
+    when its chunk keeps more: 256 strips, so no strip is cut, with 4150 visual keys each, ragged lengths."""
+    B, H, D, ns, nv, tail = 8, 32, 64, 4, 4150, 46
+    L = ns + nv + tail
+    rng = np.random.default_rng(35)
+    K = rand_values(rng, (B, H, L, D), "bf16", 1.2); V = rand_values(rng, (B, H, L, D), "bf16", 1.2)
+    q = rand_values(rng, (B, H, D), "bf16", 1.2)
+    vis = [nv, nv - 1, 4097, 4096, 4095, 2000, 1, 0]
+    lens = [ns + v + tail - (b % 3) for b, v in enumerate(vis)]
+    shape = st3.make_shape(B, H, D, st3.ST3_BF16)
+    out = torch.zeros((B, H, D), dtype=torch.bfloat16, device=DEV)
+    mass = torch.full((B, nv), -2.0, dtype=torch.float32, device=DEV)
+    seg = st3.segments(ns, nv, L, _i32(vis), _i32(lens))
+    st3.st3_decode_attention(shape, to_dev(q, "bf16"), st3.kv_layer(to_dev(K, "bf16"), to_dev(V, "bf16")), seg, out, mass,
+                             _ws(shape, L, nv))
+    torch.cuda.synchronize()
+    for b in range(B):
+        o, m, _ = orc.decode_attention(q[b:b + 1], K[b:b + 1, :, :lens[b]], V[b:b + 1, :, :lens[b]], ns, vis[b])
+        assert_attention_close(to_np64(out)[b], o[0], "bf16", f"b={b}")
+        assert_mass_close(to_np64(mass)[b, :vis[b]], m[0], f"b={b}")
+
+
 def test_prefill_attention_at_a_long_prompt():
     B, H, D, n, ns, nv, W = 1, 2, 64, 4100, 10, 3000, 2
     rng = np.random.default_rng(34)
