@@ -80,6 +80,9 @@ constexpr int kDecodeTargetWgs = ST3_DECODE_TARGET_WGS;     // split the KV rang
 constexpr int kDecodeTargetWgsMerged = ST3_DECODE_TARGET_WGS_MERGED;
 constexpr int kDecodeTargetWgsMax = kDecodeTargetWgs > kDecodeTargetWgsMerged ? kDecodeTargetWgs : kDecodeTargetWgsMerged;
 constexpr int kDecodeMaxSplit = 64;
+// Largest chunk of a strip (rows): a decode_attend_kernel workgroup collects the logits it keeps in LDS, 4 bytes per row
+// of its chunk at most: 16 KB, so that the seven workgroups a compute unit can hold still fit its 160 KB.
+constexpr int kLogitStageMaxRows = 4096;
 constexpr int kDecodeMinChunk = 64;        // never cut a (b,h) strip into chunks shorter than this
 
 // Number of chunks each (b,h) strip is cut into for a given upper bound on its length.
@@ -89,6 +92,8 @@ inline int decode_nsplit(int B, int H, int max_kv, int target_wgs = kDecodeTarge
     if (target_wgs > kDecodeTargetWgs && 2 * bh >= target_wgs) want = 1;
     int64_t by_len = ((int64_t)max_kv + kDecodeMinChunk - 1) / kDecodeMinChunk;
     int64_t ns = want < by_len ? want : by_len;
+    const int64_t by_stage = ((int64_t)max_kv + kLogitStageMaxRows - 1) / kLogitStageMaxRows;      // chunks no longer than the staging area
+    if (ns < by_stage) ns = by_stage;
     if (ns > kDecodeMaxSplit) ns = kDecodeMaxSplit;
     return ns < 1 ? 1 : (int)ns;
 }

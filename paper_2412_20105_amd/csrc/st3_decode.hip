@@ -62,7 +62,7 @@ struct DecodeArgs {
     float* part_o;          // [B,H,nsplit_cap,D]   (nsplit > 1 only)
     float* part_ml;         // [B,H,nsplit_cap,2]
     float* logits;          // [B,H,capacity]; null when no mass is wanted
-    int32_t stage_rows;     // logits a workgroup keeps are collected in this many floats of LDS (0: stored one by one)
+    int32_t stage_rows;     // floats of LDS in which a workgroup collects the logits it keeps (0 when it keeps none)
     int32_t* pending;       // [B][4]: {mass still to be finished | rows attended << 1, nsplit, chunk, logits of this call present}
     const void* k_new;      // [B,H,D] rows of the token being appended (null: none); the cache row
     const void* v_new;      //         kv_len[b] is then taken from here and written to the cache
@@ -188,27 +188,17 @@ void decode_attend_kernel(DecodeArgs a) {
         if (c0 + wave * TILE + u * M::RPL + lane / LPR >= c1_cached) vr[u] = make_uint4(0, 0, 0, 0);
     // The logits this workgroup keeps (rows [lg_lo, lg_hi) of its chunk) are collected in LDS and leave
     // as whole lines after the waves have merged: stored one by one from the loop (16 bytes per wave
-    // and tile) they cost 2 us of a 66 us launch at the 13B shape.  A chunk that keeps more rows than
-    // the staging area holds (stage_rows == 0, decided by the launcher) stores them directly.
+    // and tile) they cost 2 us of a 66 us launch at the 13B shape.  The launcher cuts strips so that a
+    // chunk's rows fit the staging area (kLogitStageMaxRows) whenever logits are kept.
     extern __shared__ float sm_lg[];
-    const bool staged = lg != nullptr && a.stage_rows > 0;
     const int lg_lo = max(c0, vis_lo), lg_hi = min(c1, vis_hi);
-    if (staged) {
-        wave_attend_primed<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
-                                           c0, scale_l2, lane, st, sm_lg, lg_lo, vis_hi, kr, vr, sh);
-    } else {
-        wave_attend_primed<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
-                                           c0, scale_l2, lane, st, lg, vis_lo, vis_hi, kr, vr, sh);
-    }
+    float* lg_stage = lg != nullptr ? sm_lg : nullptr;
+    wave_attend_primed<KT, D, U, true>(qf, kbase, vbase, a.stride_t, c0 + wave * TILE, c1_cached, kDecodeWaves * TILE,
+                                       c0, scale_l2, lane, st, lg_stage, lg_lo, vis_hi, kr, vr, sh);
     if (has_new && wave == 0) {
-        if (staged)
-            wave_attend_row<KT, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
-                                   make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, scale_l2, lane, st, sm_lg,
-                                   lg_lo, vis_hi);
-        else
-            wave_attend_row<KT, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
-                                   make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, scale_l2, lane, st, lg,
-                                   vis_lo, vis_hi);
+        wave_attend_row<KT, D>(qf, make_uint4(kn_raw.x, kn_raw.y, kn_raw.z, kn_raw.w),
+                               make_uint4(vn_raw.x, vn_raw.y, vn_raw.z, vn_raw.w), len - 1, scale_l2, lane, st, lg_stage, lg_lo,
+                               vis_hi);
         if (lane < 2 * LPR) {                       // store the row into the cache: lanes [0,LPR) K, [LPR,2*LPR) V
             KT* dst = (lane < LPR ? kbase : vbase) + (int64_t)(len_phys - 1) * a.stride_t + (lane % LPR) * EPL;
             *reinterpret_cast<u32x4_t*>(dst) = lane < LPR ? kn_raw : vn_raw;
@@ -224,7 +214,7 @@ void decode_attend_kernel(DecodeArgs a) {
     }
     if (lane == 0) { sm_m[wave] = st.m; sm_l[wave] = st.l; }
     __syncthreads();
-    if (staged) {
+    if (lg != nullptr) {
         for (int i = tid; i < lg_hi - lg_lo; i += kDecodeThreads) lg[lg_lo - vis_lo + i] = sm_lg[i];
     }
     if (tid < D) {
@@ -543,10 +533,6 @@ int resident_workgroups(K kernel, std::atomic<int>* cache) {
     return n;
 }
 
-// Largest logit staging area of a decode_attend_kernel workgroup (floats): 16 KB, so that the seven workgroups a
-// compute unit holds at most still fit its 160 KB of LDS; chunks that keep more logits store them directly.
-constexpr int kLogitStageMaxRows = 4096;
-
 // Time of a launch of `items` equal workgroups on `slots` concurrent ones, relative to a launch whose
 // last round is full.
 inline double last_round_cost(int64_t items, int slots) {
@@ -718,10 +704,9 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     da.part_ml = reinterpret_cast<float*>(ws + wl.part_ml);
     da.logits = (want_mass || keep_all_logits) ? reinterpret_cast<float*>(ws + wl.logits) : nullptr;
     da.keep_all_logits = keep_all_logits ? 1 : 0;
-    if (da.logits != nullptr) {     // a workgroup keeps at most this many logits: all rows of its chunk, or the visual ones
-        const int rows = keep_all_logits ? da.chunk : std::min(da.chunk, seg->max_vis_len);
-        da.stage_rows = rows <= kLogitStageMaxRows ? rows : 0;
-    }
+    // a workgroup keeps at most this many logits: all rows of its chunk, or the visual ones (chunk <= kLogitStageMaxRows)
+    if (da.logits != nullptr) da.stage_rows = keep_all_logits ? da.chunk : std::min(da.chunk, seg->max_vis_len);
+    if (da.stage_rows > 4 * kLogitStageMaxRows) return ST3_ERR_UNSUPPORTED;    // a cache of more than 64 x 4096 rows
     da.pending = reinterpret_cast<int32_t*>(ws + wl.pending);
     da.k_new = k_new; da.v_new = v_new;
     da.out = out;

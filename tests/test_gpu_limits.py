@@ -106,9 +106,9 @@ def test_decode_attention_over_a_long_cache_cut_into_the_maximum_number_of_chunk
     assert_mass_close(to_np64(mass)[0], m[0], "long cache")
 
 
-def test_decode_attention_with_more_visual_keys_per_chunk_than_the_logit_staging_holds():
-    """A workgroup collects the logits it keeps for the mass in LDS (up to 4096 of them) and stores them directly
-    when its chunk keeps more: 256 strips, so no strip is cut, with 4150 visual keys each, ragged lengths."""
+def test_decode_attention_with_strips_longer_than_the_logit_staging_holds():
+    """A workgroup collects the logits it keeps for the mass in LDS, 4096 rows at most, so a strip longer than that is
+    cut even where the batch alone fills the chip: 256 strips with 4150 visual keys each, ragged lengths."""
     B, H, D, ns, nv, tail = 8, 32, 64, 4, 4150, 46
     L = ns + nv + tail
     rng = np.random.default_rng(35)
