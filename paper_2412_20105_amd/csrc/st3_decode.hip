@@ -2,10 +2,11 @@
 // cached key) with the visual mass of Sec. 3.2, plus KV append.
 //
 // decode_attend_kernel streams K and V exactly once.  Each (b,h) strip is cut into `nsplit`
-// chunks (one workgroup each); nsplit is 1 as soon as B*H alone fills the chip, and then the
-// workgroup writes the finished output row itself.  With nsplit > 1 the workgroups leave
+// chunks (one workgroup each); nsplit is 1 as soon as B*H alone fills the chip and the strip is no
+// longer than the logit staging area, and then the workgroup writes the finished output row itself.  With nsplit > 1 the workgroups leave
 // un-normalised partials that decode_finish_kernel merges in chunk order.  For the visual mass the
-// attend kernel saves the scaled logits of the visual keys and every chunk's (max, sum); turning
+// attend kernel saves the scaled logits of the visual keys (collected in LDS, written out as whole
+// lines at the end of the workgroup) and every chunk's (max, sum); turning
 // them into probabilities and adding them over heads - in head order, so the sum is the same on
 // every run - is done by finish_mass(): in decode_finish_kernel for the stand-alone call, and by
 // the layer's eviction-plan workgroup in the fused step (it needs the scores only then).
