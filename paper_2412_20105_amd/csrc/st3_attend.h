@@ -112,8 +112,7 @@ __device__ __forceinline__ void wave_attend(const float* qf, const T* kbase, con
             s[u] = ok[u] ? part : -INFINITY;
             mt = fmaxf(mt, s[u]);
         }
-#pragma unroll
-        for (int off = LPR; off < kWave; off <<= 1) mt = fmaxf(mt, __shfl_xor(mt, off));
+        mt = wave_max_from<LPR>(mt);
         float m_new = fmaxf(st.m, mt);
         float alpha = exp2_fast(st.m - m_new);       // first tile: exp2(-inf) = 0
         st.m = m_new;
@@ -243,8 +242,7 @@ __device__ __forceinline__ void wave_attend_primed(const float* qf, const T* kba
             s[u] = ok ? part : -INFINITY;
             mt = fmaxf(mt, s[u]);
         }
-#pragma unroll
-        for (int off = LPR; off < kWave; off <<= 1) mt = fmaxf(mt, __shfl_xor(mt, off));
+        mt = wave_max_from<LPR>(mt);
         float m_new = fmaxf(st.m, mt);
         float alpha = exp2_fast(st.m - m_new);
         st.m = m_new;
@@ -298,12 +296,9 @@ __device__ __forceinline__ void wave_attend_row(const float* qf, uint4 kraw, uin
 template <typename T, int D>
 __device__ __forceinline__ void finish_wave(WaveState<RowMap<T, D>::EPL>& st) {
     using M = RowMap<T, D>;
+    st.l = wave_sum_from<M::LPR>(st.l);
 #pragma unroll
-    for (int off = M::LPR; off < kWave; off <<= 1) {
-        st.l += __shfl_xor(st.l, off);
-#pragma unroll
-        for (int e = 0; e < M::EPL; ++e) st.acc[e] += __shfl_xor(st.acc[e], off);
-    }
+    for (int e = 0; e < M::EPL; ++e) st.acc[e] = wave_sum_from<M::LPR>(st.acc[e]);
 }
 
 }  // namespace st3

@@ -229,6 +229,29 @@ __device__ __forceinline__ uint32_t f32_to_e4m3(float t) {
 // x / scale as the quantiser defines it: one correctly rounded float32 division.
 __device__ __forceinline__ uint32_t quantize_e4m3(float x, float scale) { return f32_to_e4m3(__fdiv_rn(x, scale)); }
 
+// x of this lane and x of lane ^ OFF, as the pair (a, b) in an order that depends on the lane: enough
+// for any symmetric combination (max, sum).  OFF = 32 and 16 use the swap instructions of gfx950
+// (v_permlane32_swap trades lanes 32..63 of its first operand for lanes 0..31 of its second,
+// v_permlane16_swap does the same with the odd and even rows of 16 lanes; with both operands x one
+// result holds the lower partner's value in both places and the other the upper partner's): no LDS
+// round trip, which a shuffle across rows of 16 lanes takes.
+template <int OFF>
+__device__ __forceinline__ void lane_pair(float x, float& a, float& b) {
+    if constexpr (OFF == 32) {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+        a = __uint_as_float(r[0]); b = __uint_as_float(r[1]);
+    } else if constexpr (OFF == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+        a = __uint_as_float(r[0]); b = __uint_as_float(r[1]);
+    } else {
+        a = x; b = __shfl_xor(x, OFF);
+    }
+}
+template <int OFF>
+__device__ __forceinline__ float pair_max(float x) { float a, b; lane_pair<OFF>(x, a, b); return fmaxf(a, b); }
+template <int OFF>
+__device__ __forceinline__ float pair_sum(float x) { float a, b; lane_pair<OFF>(x, a, b); return a + b; }
+
 // Sum over aligned groups of G consecutive lanes (G in {4,8,16,32}); every lane of a group ends
 // with the group's total.  Steps below 16 lanes use DPP row operations; they rely on all lanes
 // of the already-reduced sub-group holding the same value, so a mirror acts as the XOR step.
@@ -241,11 +264,31 @@ __device__ __forceinline__ float group_sum(float v) {
         v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
     if (G >= 16)  // row_mirror: lane i <-> 15-i within 16 lanes
         v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
-    if (G >= 32) v += __shfl_xor(v, 16);
+    if (G >= 32) v = pair_sum<16>(v);
     return v;
 }
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Maximum / sum over the lanes l, l ^ FROM, l ^ 2 FROM, ... up to the whole wave of 64.
+template <int FROM>
+__device__ __forceinline__ float wave_max_from(float x) {
+    if constexpr (FROM <= 1) x = pair_max<1>(x);
+    if constexpr (FROM <= 2) x = pair_max<2>(x);
+    if constexpr (FROM <= 4) x = pair_max<4>(x);
+    if constexpr (FROM <= 8) x = pair_max<8>(x);
+    if constexpr (FROM <= 16) x = pair_max<16>(x);
+    return pair_max<32>(x);
+}
+template <int FROM>
+__device__ __forceinline__ float wave_sum_from(float x) {
+    if constexpr (FROM <= 1) x = pair_sum<1>(x);
+    if constexpr (FROM <= 2) x = pair_sum<2>(x);
+    if constexpr (FROM <= 4) x = pair_sum<4>(x);
+    if constexpr (FROM <= 8) x = pair_sum<8>(x);
+    if constexpr (FROM <= 16) x = pair_sum<16>(x);
+    return pair_sum<32>(x);
+}
 
 #endif  // __HIPCC__
 
