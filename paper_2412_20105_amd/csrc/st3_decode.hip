@@ -707,7 +707,7 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     da.keep_all_logits = keep_all_logits ? 1 : 0;
     // a workgroup keeps at most this many logits: all rows of its chunk, or the visual ones (chunk <= kLogitStageMaxRows)
     if (da.logits != nullptr) da.stage_rows = keep_all_logits ? da.chunk : std::min(da.chunk, seg->max_vis_len);
-    if (da.stage_rows > 4 * kLogitStageMaxRows) return ST3_ERR_UNSUPPORTED;    // a cache of more than 64 x 4096 rows
+    if (da.stage_rows > 3 * kLogitStageMaxRows) return ST3_ERR_UNSUPPORTED;    // 48 KB of LDS: a cache of more than 64 x 3 x 4096 rows
     da.pending = reinterpret_cast<int32_t*>(ws + wl.pending);
     da.k_new = k_new; da.v_new = v_new;
     da.out = out;
