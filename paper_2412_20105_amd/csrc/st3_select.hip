@@ -306,7 +306,6 @@ void launch_evict_plan(const EvictArgs& ea, int B, hipStream_t st) {
 }
 
 // Up to kPlanBatch plans travel by value in the kernel arguments; grid (B, layers of the batch).
-constexpr int kPlanBatch = 16;
 struct EvictBatch {
     EvictArgs layer[kPlanBatch];
 };

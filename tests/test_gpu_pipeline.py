@@ -181,6 +181,57 @@ def test_many_layers_whole_step_call_current_mode():
     _run_and_compare(w, 2, mode="current", whole_step=True)
 
 
+def _many_layers_with_a_group_across_the_fork():
+    """34 layers; layers 15-17 inherit from layer 14, so the group lies on both sides of layer 16."""
+    keep = [120] * 3 + [100] * 11 + [80] * 4 + [60] * 16
+    w = dataclasses.replace(get_workload("llava15_7b"), layers=34, heads=2, steps=4, n_vis=120, n_txt=9,
+                            layer_schedule={"kind": "table", "keep": keep}, step_schedule={"kind": "cos", "tau": 5})
+    return w, {15: 14, 16: 14, 17: 14}
+
+
+@pytest.mark.parametrize("mode", ["static", "current"])
+def test_plans_run_beside_the_attention_of_later_layers(mode):
+    """With more than 16 layers the whole-step call hands the plans of layers 0-15 and 16-31 to the library's side
+    stream while later layers attend; the last two layers' plans stay on the caller's stream."""
+    w, lazy = _many_layers_with_a_group_across_the_fork()
+    st3.st3_debug_set_plan_overlap(2)               # in every step, not only in those the library would pick
+    try:
+        _run_and_compare(w, 2, mode=mode, whole_step=True, lazy=lazy)
+    finally:
+        st3.st3_debug_set_plan_overlap(0)
+
+
+def test_plans_beside_the_attention_change_no_bit():
+    """The same job with the side stream in use and with every launch on the caller's stream: outputs, masses, kept
+    ids and lengths are equal bit for bit at every step."""
+    w, lazy = _many_layers_with_a_group_across_the_fork()
+    B, T = 3, w.steps
+    keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
+    runs = []
+    for overlap in (2, 1):                           # always, never
+        st3.st3_debug_set_plan_overlap(overlap)
+        try:
+            gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt, T,
+                                      keep, mode="current", device=DEV, lazy=lazy)
+            for l in range(w.layers):
+                gen.prefill_layer(l, *(to_dev(x, w.dtype) for x in prefill_qkv(w, l, B)))
+            seen = []
+            for t in range(1, T + 1):
+                qkv = torch.stack([torch.stack([to_dev(x, w.dtype) for x in decode_qkv(w, l, t, B)])
+                                   for l in range(w.layers)]).contiguous()
+                outs = gen.decode_step(t, qkv)
+                torch.cuda.synchronize()
+                seen.append([outs.clone()] + [x.clone() for lc in gen.layers
+                                              for x in (lc.ids, lc.score, lc.mass, lc.vis_len, lc.kv_len)])
+            runs.append(seen)
+        finally:
+            st3.st3_debug_set_plan_overlap(0)
+    for t, (a, b) in enumerate(zip(*runs)):
+        assert len(a) == len(b)
+        for i, (x, y) in enumerate(zip(a, b)):
+            assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), f"step {t + 1}, tensor {i}"
+
+
 @pytest.mark.parametrize("fixed_tail", [True, False])
 def test_large_evictions_whole_step_call(fixed_tail):
     """Evictions above the in-kernel row-move threshold: the separate row-move launch after the plans."""
