@@ -201,35 +201,78 @@ def test_plans_run_beside_the_attention_of_later_layers(mode):
         st3.st3_debug_set_plan_overlap(0)
 
 
+def _run_job_whole_steps(w, lazy, B, stream=None):
+    """The job through whole-step calls (no oracle): per step the outputs and every layer's columns and lengths."""
+    T = w.steps
+    keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
+    with torch.cuda.stream(stream if stream is not None else torch.cuda.current_stream()):
+        gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt, T,
+                                  keep, mode="current", device=DEV, lazy=lazy)
+        for l in range(w.layers):
+            gen.prefill_layer(l, *(to_dev(x, w.dtype) for x in prefill_qkv(w, l, B)))
+        seen = []
+        for t in range(1, T + 1):
+            qkv = torch.stack([torch.stack([to_dev(x, w.dtype) for x in decode_qkv(w, l, t, B)])
+                               for l in range(w.layers)]).contiguous()
+            outs = gen.decode_step(t, qkv)
+            torch.cuda.current_stream().synchronize()
+            seen.append([outs.clone()] + [x.clone() for lc in gen.layers
+                                          for x in (lc.ids, lc.score, lc.mass, lc.vis_len, lc.kv_len)])
+        torch.cuda.current_stream().synchronize()
+    return seen
+
+
+def _assert_same_bits(a_steps, b_steps, what):
+    assert len(a_steps) == len(b_steps)
+    for t, (a, b) in enumerate(zip(a_steps, b_steps)):
+        assert len(a) == len(b)
+        for i, (x, y) in enumerate(zip(a, b)):
+            assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), f"{what}: step {t + 1}, tensor {i}"
+
+
 def test_plans_beside_the_attention_change_no_bit():
     """The same job with the side stream in use and with every launch on the caller's stream: outputs, masses, kept
     ids and lengths are equal bit for bit at every step."""
     w, lazy = _many_layers_with_a_group_across_the_fork()
-    B, T = 3, w.steps
-    keep = [row[:T + 1] for row in pipeline.keep_table_for(w)]
     runs = []
     for overlap in (2, 1):                           # always, never
         st3.st3_debug_set_plan_overlap(overlap)
         try:
-            gen = pipeline.Generation(w.layers, w.heads, w.head_dim, TORCH_DTYPE[w.dtype], B, w.n_sys, w.n_vis, w.n_txt, T,
-                                      keep, mode="current", device=DEV, lazy=lazy)
-            for l in range(w.layers):
-                gen.prefill_layer(l, *(to_dev(x, w.dtype) for x in prefill_qkv(w, l, B)))
-            seen = []
-            for t in range(1, T + 1):
-                qkv = torch.stack([torch.stack([to_dev(x, w.dtype) for x in decode_qkv(w, l, t, B)])
-                                   for l in range(w.layers)]).contiguous()
-                outs = gen.decode_step(t, qkv)
-                torch.cuda.synchronize()
-                seen.append([outs.clone()] + [x.clone() for lc in gen.layers
-                                              for x in (lc.ids, lc.score, lc.mass, lc.vis_len, lc.kv_len)])
-            runs.append(seen)
+            runs.append(_run_job_whole_steps(w, lazy, 3))
         finally:
             st3.st3_debug_set_plan_overlap(0)
-    for t, (a, b) in enumerate(zip(*runs)):
-        assert len(a) == len(b)
-        for i, (x, y) in enumerate(zip(a, b)):
-            assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), f"step {t + 1}, tensor {i}"
+    _assert_same_bits(runs[0], runs[1], "forked against not forked")
+
+
+def test_two_threads_share_the_side_stream():
+    """Two host threads run a job each, on streams of their own, through whole-step calls that fork into the one side
+    stream of the device: both get the bits a job gets alone."""
+    import threading
+    w, lazy = _many_layers_with_a_group_across_the_fork()
+    st3.st3_debug_set_plan_overlap(2)
+    try:
+        alone = _run_job_whole_steps(w, lazy, 2)
+        streams = [torch.cuda.Stream(device=DEV) for _ in range(2)]
+        got, errors = [None, None], []
+
+        def job(i):
+            try:
+                torch.cuda.set_device(DEV)
+                got[i] = _run_job_whole_steps(w, lazy, 2, streams[i])
+            except Exception as e:                  # surfaced in the main thread below
+                errors.append(e)
+
+        threads = [threading.Thread(target=job, args=(i,)) for i in range(2)]
+        for th in threads:
+            th.start()
+        for th in threads:
+            th.join()
+        torch.cuda.synchronize()
+        assert not errors, errors
+    finally:
+        st3.st3_debug_set_plan_overlap(0)
+    for i in range(2):
+        _assert_same_bits(alone, got[i], f"thread {i} against a job alone")
 
 
 @pytest.mark.parametrize("fixed_tail", [True, False])
