@@ -443,3 +443,58 @@ def test_layers_called_one_at_a_time_with_a_data_dependency(name, kw, B, lazy):
             assert lc.vis_len.cpu().tolist() == [k_next] * B
     print(f"{w.name}: {compared} of {w.layers * B * T} (layer, sequence, step) triples compared", flush=True)
     assert compared >= 0.8 * w.layers * B * T
+
+
+def _random_generation(seed):
+    """A whole job of random shape, retention tables, heredity groups and options (seeded)."""
+    rng = np.random.default_rng(77000 + seed)
+    base = "tiny" if rng.random() < 0.35 else "llava15_7b"              # float32 / bf16 values
+    L = int(rng.integers(2, 12)) if rng.random() < 0.8 else int(rng.integers(17, 36))
+    H, D, B = int(rng.choice([1, 2, 3, 4, 8])), int(rng.choice([64, 128])), int(rng.integers(1, 4))
+    n_sys, n_vis, n_txt, T = int(rng.integers(0, 40)), int(rng.integers(4, 200)), int(rng.integers(1, 40)), int(rng.integers(2, 6))
+    keep = [n_vis] * int(rng.integers(1, 4))                             # full for the first layers, then never growing
+    while len(keep) < L:
+        keep.append(int(rng.integers(0, keep[-1] + 1)) if rng.random() < 0.6 else keep[-1])
+    keep = keep[:L]
+    lazy = {}
+    if rng.random() < 0.4:                                               # heredity groups of 1-3 lazy layers
+        l = int(rng.integers(1, L))
+        while l < L:
+            src = lazy.get(l - 1, l - 1)
+            n = int(rng.integers(1, 4))
+            for j in range(l, min(l + n, L)):
+                lazy[j] = src
+            l += n + int(rng.integers(1, 6))
+        for j in range(1, L):
+            keep[j] = keep[lazy[j]] if j in lazy else min(keep[j], keep[j - 1])
+    ss = {"cos": {"kind": "cos", "tau": int(rng.integers(max(T - 1, 1), 2 * T + 1))},
+          "linear": {"kind": "linear", "tau": int(rng.integers(max(T - 1, 1), 2 * T + 1))},
+          "exp": {"kind": "exp", "sigma": float(rng.uniform(0.5, 3 * T))},
+          "drop": {"kind": "drop", "per_step": int(rng.integers(1, 30))},
+          "none": {"kind": "none"}}[str(rng.choice(["cos", "linear", "exp", "drop", "none"]))]
+    w = dataclasses.replace(get_workload(base), layers=L, heads=H, head_dim=D, n_sys=n_sys, n_vis=n_vis, n_txt=n_txt, steps=T,
+                            layer_schedule={"kind": "table", "keep": keep}, step_schedule=ss)
+    opts = dict(mode=str(rng.choice(["static", "current"])), compact_mode=int(rng.choice([st3.ST3_HOLE_FILL, st3.ST3_STABLE])),
+                fixed_tail=bool(rng.random() < 0.5), whole_step=bool(lazy) or bool(rng.random() < 0.5),
+                window=min(int(rng.choice([1, 1, 2, 4])), n_txt), lazy=lazy or None,
+                kv_scale=6 * w.sigma / 448 if (w.dtype == "bf16" and rng.random() < 0.3) else None)
+    return w, B, opts, int(rng.choice([0, 2]))
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_whole_generations_of_random_shape_and_options(block):
+    """Shapes, retention tables, annealing kinds, heredity groups, both cache layouts and compaction modes, both ways of
+    calling a step, score windows, E4M3 caches, 2 to 35 layers, with the whole-step call's plans forked or not."""
+    compared = total = 0
+    for seed in range(block * 20, block * 20 + 20):
+        w, B, opts, overlap = _random_generation(seed)
+        print("generation case", seed, w.layers, w.heads, w.head_dim, B, (w.n_sys, w.n_vis, w.n_txt), w.steps,
+              w.layer_schedule["keep"], w.step_schedule, opts, overlap, flush=True)
+        st3.st3_debug_set_plan_overlap(overlap)
+        try:
+            _, div = _run_and_compare(w, B, min_compared=0.0, **opts)
+        finally:
+            st3.st3_debug_set_plan_overlap(0)
+        compared += int((~div).sum())
+        total += div.size
+    assert compared >= 0.9 * total, f"only {compared} of {total} (layer, sequence) pairs were compared to the end"
