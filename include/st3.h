@@ -1,8 +1,8 @@
 /*
  * st3.h - C ABI of the ST3 attention / visual-token-trimming hot path for AMD MI355X (gfx950).
  *
- * The calls follow the problem statement of "ST3: Spatial-Temporal Visual Token Trimming"
- * (Alg. 3, "PVTP+VTA (KV cache implementation)"): per decoder layer, causal attention over a
+ * The calls follow the problem statement of the ST3 paper (spatial-temporal visual token
+ * trimming; Alg. 3, the KV-cache form of PVTP with VTA): per decoder layer, causal attention over a
  * sequence laid out [S, V, I, O] (Eq. 1) whose visual segment V shrinks over layers at prefill
  * (Progressive Visual Token Pruning, Eq. 3) and over decode steps (Visual Token Annealing,
  * Eq. 7-8), driven by the attention the last query row pays to each visual key (Sec. 3.2).
