@@ -93,6 +93,14 @@ inline int decode_nsplit(int B, int H, int max_kv, int target_wgs = kDecodeTarge
     if (target_wgs > kDecodeTargetWgs && 2 * bh >= target_wgs) want = 1;
     int64_t by_len = ((int64_t)max_kv + kDecodeMinChunk - 1) / kDecodeMinChunk;
     int64_t ns = want < by_len ? want : by_len;
+    // A small even number of chunks runs slower than the odd number below it (attend launch, whole-step call, 1 / 2 / 3 /
+    // 4 / 5 / 6 / 8 chunks: high-resolution prompt at batch 8, B*H = 256, 31.8 / 33.9 / 31.4 / 35.7 / 32.6 / 34.2 / 38.5 us;
+    // 13B shape at batch 8, B*H = 320, 21.5 / 21.2 / 19.3 / 19.9 / 19.8 / 20.1 / 23.0 us): workgroup ids go round-robin to
+    // the 8 XCDs, so with an even count a chunk index always meets the same XCDs (rotating the chunk index over the strips
+    // recovers part of it, 35.7 -> 34.3 and 19.9 -> 19.3 us).  Where a cut costs a launch of its own (the lower target) one
+    // chunk fewer is taken always - two chunks become none, and the merge launch goes; where it is free, only if enough
+    // workgroups remain (at B*H = 40 the late, short layers of the 13B shape lost 2 % with 3 chunks instead of 4).
+    if (ns > 1 && ns % 2 == 0 && (target_wgs <= kDecodeTargetWgs || bh * (ns - 1) >= 2 * kDecodeTargetWgs)) ns -= 1;
     const int64_t by_stage = ((int64_t)max_kv + kLogitStageMaxRows - 1) / kLogitStageMaxRows;      // chunks no longer than the staging area
     if (ns < by_stage) ns = by_stage;
     if (ns > kDecodeMaxSplit) ns = kDecodeMaxSplit;
