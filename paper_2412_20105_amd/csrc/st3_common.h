@@ -84,7 +84,11 @@ constexpr int kDecodeMaxSplit = 64;
 // Largest chunk of a strip (rows): a decode_attend_kernel workgroup collects the logits it keeps in LDS, 4 bytes per row
 // of its chunk at most: 16 KB, so that the seven workgroups a compute unit can hold still fit its 160 KB.
 constexpr int kLogitStageMaxRows = 4096;
-constexpr int kDecodeMinChunk = 64;        // never cut a (b,h) strip into chunks shorter than this
+#ifndef ST3_DECODE_MIN_CHUNK
+#define ST3_DECODE_MIN_CHUNK 64
+#endif
+// never cut a (b,h) strip into chunks shorter than this (32 and 96 rows measured 2-8 % slower per step at B*H = 32 and 40)
+constexpr int kDecodeMinChunk = ST3_DECODE_MIN_CHUNK;
 
 // Number of chunks each (b,h) strip is cut into for a given upper bound on its length.
 inline int decode_nsplit(int B, int H, int max_kv, int target_wgs = kDecodeTargetWgs) {
