@@ -52,12 +52,12 @@ st3_status validate_kv_value_only(const st3_attn_shape* s, const st3_kv_layer* k
 st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                            int32_t max_kv_len, const void* v_new, const void* src_workspace,
                            size_t src_workspace_bytes, int32_t src_capacity, void* out, void* workspace,
-                           size_t workspace_bytes, hipStream_t st);
+                           size_t workspace_bytes, hipStream_t st, const PlanStash* stash = nullptr);
 st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_kv_layer* kv,
                           const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
                           void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
                           bool keep_all_logits, void* workspace, size_t workspace_bytes, hipStream_t st,
-                          bool defer_merge = false);
+                          bool defer_merge = false, const PlanStash* stash = nullptr);
 bool decode_is_split(const st3_attn_shape* shape, const st3_kv_layer* kv, int32_t max_kv_len);
 
 }  // namespace st3
@@ -232,25 +232,29 @@ static st3_status check_step(const st3_attn_shape* shape, int32_t n_layers, cons
 // Append + attention of layer i of a checked step; the mass stays pending for the layer's plan.
 // merge_in_plan: strips cut into chunks leave their partials for the layer's plan to merge (the
 // whole-step call); else a merge launch follows the attention and `out` is complete right after it.
+// stash (may be null): words the launch leaves in the layer's workspace for the launch that plans the layer.
 static st3_status enqueue_layer_attend(const st3_attn_shape* shape, const st3_layer_step* layers, int i, bool has_heirs,
-                                       hipStream_t st, bool merge_in_plan) {
+                                       hipStream_t st, bool merge_in_plan, const PlanStash* stash = nullptr) {
     const st3_layer_step& L = layers[i];
     if (L.inherit_from >= 0) {
         const st3_layer_step& S = layers[L.inherit_from];
         return enqueue_inherit(shape, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.v_new, S.workspace, S.workspace_bytes,
-                               S.kv.capacity, L.out, L.workspace, L.workspace_bytes, st);
+                               S.kv.capacity, L.out, L.workspace, L.workspace_bytes, st, stash);
     }
     return enqueue_decode(shape, L.q, &L.kv, &L.seg, L.seg.max_kv_len + 1, L.k_new, L.v_new, L.out, L.vis_mass,
                           L.mass_stride, L.vis_mass != nullptr, true, has_heirs, L.workspace, L.workspace_bytes, st,
-                          merge_in_plan);
+                          merge_in_plan, stash);
 }
 
 // Every layer's plan (finish the mass, count the new row, rank, evict) in one launch per 16
 // layers: a plan workgroup is latency bound, so the layers' plans are best run side by side.
+// stashed (may be null): where the layers' attention launches have left a copy of each plan in device
+// memory; the plans are then read from there, as many layers per launch as there are.
 static void enqueue_plan_range(const std::vector<EvictArgs>& plan, const std::vector<char>& needs_apply, int i0, int i1,
-                               int B, hipStream_t st) {
+                               int B, hipStream_t st, const std::vector<const EvictArgs*>* stashed = nullptr) {
     if (i1 <= i0) return;
-    launch_evict_plan_batch(plan.data() + i0, i1 - i0, B, st);
+    if (stashed != nullptr) launch_evict_plan_table(stashed->data() + i0, plan.data() + i0, i1 - i0, B, st);
+    else launch_evict_plan_batch(plan.data() + i0, i1 - i0, B, st);
     for (int i = i0; i < i1; ++i)
         if (needs_apply[(size_t)i]) launch_evict_apply(plan[(size_t)i], B, st);
 }
@@ -369,6 +373,7 @@ extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
         if (lane == nullptr) lane_lock.unlock();
     }
     int planned = 0, forks = 0;         // layers whose plans are enqueued; forks into the side stream so far
+    std::vector<const EvictArgs*> stashed((size_t)n_layers, nullptr);
     for (int i = 0; i < n_layers; ++i) {
         const st3_layer_step& L = layers[i];
         const bool in_plan = L.inherit_from < 0 && decode_is_split(shape, &L.kv, L.seg.max_kv_len + 1);
@@ -383,7 +388,15 @@ extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
             plan[i].pending = reinterpret_cast<const int32_t*>(ws + wl.pending);
             plan[i].nsplit_cap = wl.nsplit_cap;
         }
-        s = enqueue_layer_attend(shape, layers, i, has_heirs[i] != 0, st, in_plan);
+        // the layer's plan travels with its attention launch into the layer's workspace; the plan launches read it there
+        PlanStash stash{};
+        std::memcpy(stash.w, &plan[i], sizeof(EvictArgs));
+        {
+            const DecodeWs wl = decode_ws(shape->batch, shape->heads, shape->head_dim, L.kv.capacity);
+            stash.dst = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(L.workspace) + wl.plan_args);
+            stashed[i] = reinterpret_cast<const EvictArgs*>(stash.dst);
+        }
+        s = enqueue_layer_attend(shape, layers, i, has_heirs[i] != 0, st, in_plan, &stash);
         if (s != ST3_OK) break;
         // a full batch of layers has attended and more follow: its plans go to the side stream
         if (lane != nullptr && (i + 1) % kPlanBatch == 0 && i + 1 < n_layers && forks < kPlanForks &&
@@ -391,12 +404,12 @@ extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
             hipError_t e = hipEventRecord(lane->fork[forks], st);
             if (e == hipSuccess) e = hipStreamWaitEvent(lane->side, lane->fork[forks], 0);
             if (e != hipSuccess) { set_last_hip_error(e); s = ST3_ERR_HIP; break; }
-            enqueue_plan_range(plan, needs_apply, planned, i + 1, shape->batch, lane->side);
+            enqueue_plan_range(plan, needs_apply, planned, i + 1, shape->batch, lane->side, &stashed);
             planned = i + 1;
             ++forks;
         }
     }
-    if (s == ST3_OK) enqueue_plan_range(plan, needs_apply, planned, n_layers, shape->batch, st);
+    if (s == ST3_OK) enqueue_plan_range(plan, needs_apply, planned, n_layers, shape->batch, st, &stashed);
     if (forks > 0) {
         // whatever happened above, the caller's stream waits for what the side stream was given
         hipError_t e = hipEventRecord(lane->join, lane->side);

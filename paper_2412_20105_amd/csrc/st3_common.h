@@ -117,8 +117,17 @@ inline int decode_chunk(int max_kv, int nsplit) {
     return c < 32 ? 32 : c;
 }
 
+// A layer's attention launch can leave up to 256 bytes of the host's choosing in the layer's workspace (one workgroup stores
+// them): the whole-step call passes each layer's eviction-plan arguments this way, so that ONE plan launch can serve every
+// layer of the step - by value, 16 layers' arguments fill the kernel-argument block.
+constexpr int kPlanStashWords = 64;
+struct PlanStash {
+    uint32_t w[kPlanStashWords];
+    uint32_t* dst;              // DEVICE, in the layer's workspace; null: nothing to leave
+};
+
 struct DecodeWs {
-    size_t part_o, part_ml, logits, pending, moves_cnt, moves, total;
+    size_t part_o, part_ml, logits, pending, plan_args, moves_cnt, moves, total;
     int nsplit_cap;
     int max_moves;
 };
@@ -134,6 +143,7 @@ inline DecodeWs decode_ws(int B, int H, int D, int capacity) {
     w.part_ml = off;    off = align_up(off + BH * w.nsplit_cap * 2 * sizeof(float), 256);
     w.logits = off;     off = align_up(off + BH * (size_t)capacity * sizeof(float), 256);   // [B,H,capacity]
     w.pending = off;    off = align_up(off + (size_t)B * 4 * sizeof(int32_t), 256);         // [B][4]
+    w.plan_args = off;  off = align_up(off + kPlanStashWords * sizeof(uint32_t), 256);       // what a PlanStash leaves
     w.moves_cnt = off;  off = align_up(off + (size_t)B * sizeof(int32_t), 256);
     w.moves = off;      off = align_up(off + (size_t)B * w.max_moves * 2 * sizeof(int32_t), 256);
     w.total = off;

@@ -70,6 +70,13 @@ struct DecodeArgs {
     void* out;              // [B,H,D]
 };
 
+// Workgroup (0,0,0) of a launch leaves the stash words in the workspace (plain vector stores).  The stash is a kernel
+// parameter of its own, behind the argument struct, so that the struct's fields keep their places in the argument block.
+__device__ __forceinline__ void leave_stash(const PlanStash& st) {
+    if (st.dst != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x < kPlanStashWords)
+        st.dst[threadIdx.x] = st.w[threadIdx.x];
+}
+
 template <typename T>
 __device__ __forceinline__ void store_out(void* out, int64_t idx, float o) {
     if (sizeof(T) == 4) reinterpret_cast<float*>(out)[idx] = o;
@@ -104,7 +111,7 @@ struct NewRow<T, e4m3_t, D> {
 template <typename T, typename KT, int D, int U>
 __global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS)
 __attribute__((amdgpu_waves_per_eu(ST3_DECODE_MIN_BLOCKS, ST3_DECODE_MIN_BLOCKS)))    // do not spill to reach a third wave
-void decode_attend_kernel(DecodeArgs a) {
+void decode_attend_kernel(DecodeArgs a, PlanStash stash) {
     using M = RowMap<KT, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, TILE = U * M::RPL;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -135,6 +142,7 @@ void decode_attend_kernel(DecodeArgs a) {
     const SeqLayout lay = seq_layout(a.sys_len, a.vis_len[b], a.max_vis, len_phys, a.tail_start, b);
     const int len = lay.vlen;
     const RowShift sh = lay.shift();
+    leave_stash(stash);
     if (split == 0 && h == 0 && tid == 0 && a.pending != nullptr) {
         // bit 0: the mass of this launch is still to be finished; above it: the rows this launch attends over
         a.pending[b * 4 + 0] = ((a.logits != nullptr && len > 0 && a.defer) ? 1 : 0) | (max(len, 0) << 1);
@@ -307,10 +315,11 @@ __device__ __forceinline__ void wave_inherit(const T* vbase, int64_t stride_t, i
 
 // grid (nsplit, H, B)
 template <typename T, typename KT, int D, int U>
-__global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_inherit_kernel(InheritArgs a) {
+__global__ __launch_bounds__(kDecodeThreads, ST3_DECODE_MIN_BLOCKS) void decode_inherit_kernel(InheritArgs a, PlanStash stash) {
     using M = RowMap<KT, D>;
     constexpr int EPL = M::EPL, LPR = M::LPR, TILE = U * M::RPL;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    leave_stash(stash);
     const int len_phys = min(a.kv_len[b] + (a.v_new != nullptr ? 1 : 0), a.max_kv);
     // rows are numbered without the gap a fixed-tail cache keeps behind its visual segment, as in the
     // source layer's attend launch (same lengths, same layout): its logits are indexed the same way
@@ -550,25 +559,25 @@ inline int cheapest(const double* cost, int n) {
 }
 
 template <typename T, typename KT, int D, int U>
-void launch_attend_u(const DecodeArgs& da, int B, hipStream_t st) {
+void launch_attend_u(const DecodeArgs& da, const PlanStash& ps, int B, hipStream_t st) {
     const dim3 grid(da.nsplit, da.H, B);
     const size_t lds = (size_t)da.stage_rows * sizeof(float);       // dynamic LDS: the logit staging area
     hipEvent_t e0, e1;
     if (profile_take(&e0, &e1))     // timed launch: the events receive the kernel's own start and end
-        hipExtLaunchKernelGGL((decode_attend_kernel<T, KT, D, U>), grid, dim3(kDecodeThreads), lds, st, e0, e1, 0, da);
+        hipExtLaunchKernelGGL((decode_attend_kernel<T, KT, D, U>), grid, dim3(kDecodeThreads), lds, st, e0, e1, 0, da, ps);
     else
-        decode_attend_kernel<T, KT, D, U><<<grid, kDecodeThreads, lds, st>>>(da);
+        decode_attend_kernel<T, KT, D, U><<<grid, kDecodeThreads, lds, st>>>(da, ps);
 }
 
 // Takes the cheapest of the builds Us... (in order of preference) for this launch.
 template <typename T, typename KT, int D, int... Us>
-void launch_attend_best(const DecodeArgs& da, int B, hipStream_t st, std::integer_sequence<int, Us...>) {
+void launch_attend_best(const DecodeArgs& da, const PlanStash& ps, int B, hipStream_t st, std::integer_sequence<int, Us...>) {
     constexpr int N = sizeof...(Us);
     static std::atomic<int> slots[N][kMaxDevices];  // resident workgroups of each build, per device
     const int us[N] = {Us...};
     const int g_forced_tile = debug_state().attend_tile;    // 0 unless the debug block is enabled
     if (g_forced_tile != 0 && ((g_forced_tile == Us) || ...)) {
-        ((g_forced_tile == Us ? (launch_attend_u<T, KT, D, Us>(da, B, st), 0) : 0), ...);
+        ((g_forced_tile == Us ? (launch_attend_u<T, KT, D, Us>(da, ps, B, st), 0) : 0), ...);
         return;
     }
     const int64_t items = (int64_t)da.nsplit * da.H * B;
@@ -576,21 +585,21 @@ void launch_attend_best(const DecodeArgs& da, int B, hipStream_t st, std::intege
     int i = 0;
     ((cost[i] = last_round_cost(items, resident_workgroups(decode_attend_kernel<T, KT, D, Us>, slots[i])), ++i), ...);
     const int pick = us[cheapest(cost, N)];
-    ((pick == Us ? (launch_attend_u<T, KT, D, Us>(da, B, st), 0) : 0), ...);
+    ((pick == Us ? (launch_attend_u<T, KT, D, Us>(da, ps, B, st), 0) : 0), ...);
 }
 
 template <typename T, typename KT, int D>
-void launch_attend(const DecodeArgs& da, int B, hipStream_t st) {
-    if constexpr (sizeof(KT) == 1) launch_attend_best<T, KT, D>(da, B, st, std::integer_sequence<int, 3, 4, 1>{});
-    else launch_attend_best<T, KT, D>(da, B, st, std::integer_sequence<int, 4, 6, 8, 1>{});
+void launch_attend(const DecodeArgs& da, const PlanStash& ps, int B, hipStream_t st) {
+    if constexpr (sizeof(KT) == 1) launch_attend_best<T, KT, D>(da, ps, B, st, std::integer_sequence<int, 3, 4, 1>{});
+    else launch_attend_best<T, KT, D>(da, ps, B, st, std::integer_sequence<int, 4, 6, 8, 1>{});
 }
 
 // The V-only kernel of lazy layers: 4 loads per lane and tile (4 KB per wave) were the fastest or
 // within 2 % of it at every batch size and for both cache formats (8, 12 and 16 loads lose up to
 // 17 % where the launch has more workgroups than fit at once; 2 loads lose at small batches).
 template <typename T, typename KT, int D>
-void launch_inherit(const InheritArgs& ia, int B, hipStream_t st) {
-    decode_inherit_kernel<T, KT, D, 4><<<dim3(ia.nsplit, ia.H, B), kDecodeThreads, 0, st>>>(ia);
+void launch_inherit(const InheritArgs& ia, const PlanStash& ps, int B, hipStream_t st) {
+    decode_inherit_kernel<T, KT, D, 4><<<dim3(ia.nsplit, ia.H, B), kDecodeThreads, 0, st>>>(ia, ps);
 }
 
 template <typename T, int D>
@@ -674,7 +683,7 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
                           const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
                           void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
                           bool keep_all_logits, void* workspace, size_t workspace_bytes, hipStream_t st,
-                          bool defer_merge) {
+                          bool defer_merge, const PlanStash* stash) {
     const int B = shape->batch, H = shape->heads, D = shape->head_dim;
     const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
     if (workspace_bytes < wl.total) return ST3_ERR_WORKSPACE_TOO_SMALL;
@@ -712,7 +721,8 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
     da.k_new = k_new; da.v_new = v_new;
     da.out = out;
     da.defer = (want_mass && defer_mass) ? 1 : 0;
-    ST3_DISPATCH_KV(launch_attend, shape, kv, da, B, st);
+    const PlanStash ps = stash != nullptr ? *stash : PlanStash{};
+    ST3_DISPATCH_KV(launch_attend, shape, kv, da, ps, B, st);
     const bool mass_now = want_mass && !defer_mass;
     // defer_merge: the caller's eviction plan merges the chunk partials (whole-step call)
     if ((da.nsplit > 1 && !defer_merge) || mass_now) {
@@ -755,7 +765,7 @@ st3_status validate_kv_value_only(const st3_attn_shape* s, const st3_kv_layer* k
 st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, const st3_segments* seg,
                            int32_t max_kv_len, const void* v_new, const void* src_workspace,
                            size_t src_workspace_bytes, int32_t src_capacity, void* out, void* workspace,
-                           size_t workspace_bytes, hipStream_t st) {
+                           size_t workspace_bytes, hipStream_t st, const PlanStash* stash) {
     const int B = shape->batch, H = shape->heads, D = shape->head_dim;
     const DecodeWs wl = decode_ws(B, H, D, kv->capacity);
     const DecodeWs sl = decode_ws(B, H, D, src_capacity);
@@ -781,7 +791,8 @@ st3_status enqueue_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv, 
     ia.part_o = reinterpret_cast<float*>(ws + wl.part_o);
     ia.v_new = v_new; ia.out = out;
     if (kv->format == ST3_KV_E4M3) ia.v_scale = kv->v_scale;
-    ST3_DISPATCH_KV(launch_inherit, shape, kv, ia, B, st);
+    const PlanStash ps = stash != nullptr ? *stash : PlanStash{};
+    ST3_DISPATCH_KV(launch_inherit, shape, kv, ia, ps, B, st);
     if (ia.nsplit > 1) {
         FinishArgs fa{};
         fa.part_o = ia.part_o; fa.kv_len = seg->kv_len; fa.vis_len = seg->vis_len; fa.tail_start = seg->tail_start;
@@ -809,7 +820,7 @@ extern "C" st3_status st3_decode_attention(const st3_attn_shape* shape, const vo
     if (vis_mass && mass_stride < seg->max_vis_len) return ST3_ERR_INVALID_ARG;
     return st3::enqueue_decode(shape, q, kv, seg, seg->max_kv_len, nullptr, nullptr, out, vis_mass, mass_stride,
                                vis_mass != nullptr, false, true, workspace, workspace_bytes,
-                               reinterpret_cast<hipStream_t>(stream), false);
+                               reinterpret_cast<hipStream_t>(stream), false, nullptr);
 }
 
 extern "C" st3_status st3_decode_attention_inherit(const st3_attn_shape* shape, const st3_kv_layer* kv,
@@ -824,7 +835,7 @@ extern "C" st3_status st3_decode_attention_inherit(const st3_attn_shape* shape, 
     if (!st3::aligned16(workspace) || !st3::aligned16(src_workspace)) return ST3_ERR_INVALID_ARG;
     return st3::enqueue_inherit(shape, kv, seg, seg->max_kv_len, nullptr, src_workspace, src_workspace_bytes,
                                 src_kv_capacity, out, workspace, workspace_bytes,
-                                reinterpret_cast<hipStream_t>(stream));
+                                reinterpret_cast<hipStream_t>(stream), nullptr);
 }
 
 extern "C" st3_status st3_quantize_rows(const st3_attn_shape* shape, const st3_tensor4* src, const st3_kv_layer* kv,

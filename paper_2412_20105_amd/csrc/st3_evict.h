@@ -353,6 +353,11 @@ void launch_evict_plan(const EvictArgs& ea, int B, hipStream_t st);
 constexpr int kPlanBatch = 16;
 // Plans of n layers (device work of one decode step) with one launch per kPlanBatch layers.
 void launch_evict_plan_batch(const EvictArgs* plans, int n, int B, hipStream_t st);
+// The same for plans that the layers' attention launches have left in device memory (PlanStash):
+// stashed[i] is where layer i's copy of plans[i] lies; one launch per kPlanTableMax layers.
+constexpr int kPlanTableMax = 64;
+static_assert(sizeof(EvictArgs) <= kPlanStashWords * sizeof(uint32_t), "a layer's plan must fit the stash");
+void launch_evict_plan_table(const EvictArgs* const* stashed, const EvictArgs* plans, int n, int B, hipStream_t st);
 void launch_evict_apply(const EvictArgs& ea, int B, hipStream_t st);
 
 }  // namespace st3

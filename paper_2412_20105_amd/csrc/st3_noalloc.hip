@@ -14,7 +14,7 @@ st3_status enqueue_decode(const st3_attn_shape* shape, const void* q, const st3_
                           const st3_segments* seg, int32_t max_kv_len, const void* k_new, const void* v_new,
                           void* out, float* vis_mass, int64_t mass_stride, bool want_mass, bool defer_mass,
                           bool keep_all_logits, void* workspace, size_t workspace_bytes, hipStream_t st,
-                          bool defer_merge = false);
+                          bool defer_merge = false, const PlanStash* stash = nullptr);
 bool decode_is_split(const st3_attn_shape* shape, const st3_kv_layer* kv, int32_t max_kv_len);
 
 namespace {

@@ -346,6 +346,39 @@ void launch_evict_plan_batch(const EvictArgs* plans, int n, int B, hipStream_t s
     }
 }
 
+// The same with the plans read from device memory, where the layers' attention launches left them
+// (PlanStash): up to kPlanTableMax layers per launch.  grid as above.
+struct PlanTable {
+    const EvictArgs* layer[kPlanTableMax];
+};
+
+__global__ __launch_bounds__(kSelThreads) void evict_plan_table_kernel(PlanTable table) {
+    __shared__ SelShared sm;
+    // read once, ahead of every store of this kernel: uniform address, so the fields arrive in scalar registers
+    const EvictArgs a = *table.layer[blockIdx.y];
+    if (blockIdx.z == 0) {
+        evict_plan_body(a, blockIdx.x, sm);
+    } else if (a.merge_out != nullptr && a.pending != nullptr) {
+        const int h0 = ((int)blockIdx.z - 1) * kMergeHeads;
+        if (h0 < a.H) merge_chunks(a, blockIdx.x, h0, h0 + kMergeHeads);
+    }
+}
+
+void launch_evict_plan_table(const EvictArgs* const* stashed, const EvictArgs* plans, int n, int B, hipStream_t st) {
+    for (int i0 = 0; i0 < n; i0 += kPlanTableMax) {
+        const int cnt = n - i0 < kPlanTableMax ? n - i0 : kPlanTableMax;
+        PlanTable table;
+        int merge_heads = 0;
+        for (int i = 0; i < cnt; ++i) {
+            table.layer[i] = stashed[i0 + i];
+            if (plans[i0 + i].merge_out != nullptr && plans[i0 + i].H > merge_heads) merge_heads = plans[i0 + i].H;
+        }
+        for (int i = cnt; i < kPlanTableMax; ++i) table.layer[i] = nullptr;
+        const int merge_wgs = (merge_heads + kMergeHeads - 1) / kMergeHeads;
+        evict_plan_table_kernel<<<dim3(B, cnt, 1 + merge_wgs), kSelThreads, 0, st>>>(table);
+    }
+}
+
 void launch_evict_apply(const EvictArgs& ea, int B, hipStream_t st) {
     ApplyArgs aa{};
     aa.k = ea.k; aa.v = ea.v;
