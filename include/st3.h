@@ -345,7 +345,9 @@ ST3_EXPORT st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
  * st3_decode_layer_step takes for that layer.  The result is the same as calling
  * st3_decode_layer_step for i = 0 .. n_layers-1 in order.  Step (2) of a layer depends on that
  * layer's attention only, so all layers attend first (one launch each) and their steps (2) then
- * run side by side, 16 layers per launch.  Every layer needs buffers and a workspace of its own.
+ * run side by side in one launch (up to 64 layers; each attention launch leaves its layer's
+ * step-(2) arguments in the layer's workspace, where that launch reads them).  Every layer needs
+ * buffers and a workspace of its own.
  * Lazy layers (inherit_from >= 0) are available through this call only: a group's evictions must
  * wait until its last lazy layer has attended, which the per-layer call cannot arrange.
  * With more than 16 layers, in a step that evicts several rows per layer and sequence, the steps

@@ -246,10 +246,10 @@ static st3_status enqueue_layer_attend(const st3_attn_shape* shape, const st3_la
                           merge_in_plan, stash);
 }
 
-// Every layer's plan (finish the mass, count the new row, rank, evict) in one launch per 16
-// layers: a plan workgroup is latency bound, so the layers' plans are best run side by side.
-// stashed (may be null): where the layers' attention launches have left a copy of each plan in device
-// memory; the plans are then read from there, as many layers per launch as there are.
+// The plans of layers [i0, i1) (finish the mass, count the new row, rank, evict): a plan workgroup is
+// latency bound, so the layers' plans are best run side by side.  Their arguments travel by value,
+// 16 layers per launch, unless `stashed` tells where the layers' attention launches have left a copy
+// of each plan in device memory: then one launch reads them there (up to 64 layers).
 static void enqueue_plan_range(const std::vector<EvictArgs>& plan, const std::vector<char>& needs_apply, int i0, int i1,
                                int B, hipStream_t st, const std::vector<const EvictArgs*>* stashed = nullptr) {
     if (i1 <= i0) return;
