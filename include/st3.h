@@ -16,8 +16,7 @@
  *     What the library does keep, process-wide: the last HIP error (thread-local), per-device
  *     caches of device properties (compute units, resident workgroups per kernel build; written
  *     once, same value from every thread), the device address of the st3_decode_attention_noalloc
- *     array, one extra stream with its events per device for st3_decode_step (see there), and the
- *     diagnostic switches of the st3_debug_* / st3_profile_* block at the end of
+ *     array, and the diagnostic switches of the st3_debug_* / st3_profile_* block at the end of
  *     this header, which stay at their defaults unless ST3_DEBUG=1 was in the environment when
  *     the library was loaded.  Calls from several threads are safe as long as they do not share
  *     buffers.
@@ -350,14 +349,6 @@ ST3_EXPORT st3_status st3_decode_layer_step(const st3_attn_shape* shape, const s
  * buffers and a workspace of its own.
  * Lazy layers (inherit_from >= 0) are available through this call only: a group's evictions must
  * wait until its last lazy layer has attended, which the per-layer call cannot arrange.
- * With more than 16 layers, in a step that evicts several rows per layer and sequence, the steps
- * (2) of each 16 layers that have attended run on a stream of
- * the library's own (one per device, default priority, created at the first such call) beside the
- * attention of the layers that follow; the call forks into that stream and joins it again with
- * events, so that everything it enqueues is ordered on `stream` as if it had run there: the next
- * thing enqueued on `stream` sees every result.  A `stream` that is being captured into a graph
- * keeps all launches on itself.  Calls from several threads take turns enqueueing (a mutex held
- * for the duration of the call).
  * ------------------------------------------------------------------------------------------- */
 typedef struct {
     st3_kv_layer kv;
@@ -477,17 +468,12 @@ ST3_EXPORT st3_status st3_cosine_similarity(const float* va, const int32_t* ids_
  *   tile_loads != 0 makes every later launch use that build when the cache type has it (plain
  *   caches: 1, 4, 6, 8; E4M3: 1, 3, 4; any other value: automatic choice, as with 0).  Results do
  *   not depend on the tile size beyond float32 rounding order.
- * st3_debug_set_plan_overlap: 0 = st3_decode_step decides per step whether plan launches run on
- *   the library's side stream beside the attention of later layers (see that call), 1 = it keeps
- *   every launch on the caller's stream, 2 = it uses the side stream whenever there are more
- *   than 16 layers.  Results are the same bit for bit in all three.
  * ------------------------------------------------------------------------------------------- */
 ST3_EXPORT int st3_debug_enabled(void);
 ST3_EXPORT st3_status st3_profile_enable(int32_t max_launches);
 ST3_EXPORT st3_status st3_profile_read(double* total_ms, int64_t* launches, double* min_ms, double* max_ms);
 ST3_EXPORT st3_status st3_debug_set_prefill_path(int path);
 ST3_EXPORT st3_status st3_debug_set_attend_tile(int tile_loads);
-ST3_EXPORT st3_status st3_debug_set_plan_overlap(int mode);
 
 #ifdef __cplusplus
 }

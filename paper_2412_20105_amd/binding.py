@@ -32,7 +32,7 @@ EXPORTED = [
     "st3_compact_rows", "st3_gather_rows", "st3_select_compact_layer", "st3_decode_layer_step", "st3_decode_step",
     "st3_decode_layer_attend", "st3_decode_plans",
     "st3_schedule_pvtp", "st3_schedule_linear", "st3_schedule_anneal", "st3_kv_bytes",
-    "st3_debug_enabled", "st3_debug_set_prefill_path", "st3_debug_set_attend_tile", "st3_debug_set_plan_overlap", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
+    "st3_debug_enabled", "st3_debug_set_prefill_path", "st3_debug_set_attend_tile", "st3_profile_enable", "st3_profile_read", "st3_overlap_topk",
     "st3_cosine_similarity",
 ]
 
@@ -164,8 +164,6 @@ def lib() -> C.CDLL:
         L.st3_debug_set_prefill_path.restype = C.c_int
         L.st3_debug_set_attend_tile.argtypes = [C.c_int]
         L.st3_debug_set_attend_tile.restype = C.c_int
-        L.st3_debug_set_plan_overlap.argtypes = [C.c_int]
-        L.st3_debug_set_plan_overlap.restype = C.c_int
         L.st3_debug_enabled.restype = C.c_int
         _lib = L
     return _lib
@@ -425,7 +423,3 @@ def st3_debug_set_prefill_path(path: int) -> None:
 
 def st3_debug_set_attend_tile(tile_loads: int) -> None:
     _check(lib().st3_debug_set_attend_tile(tile_loads), "st3_debug_set_attend_tile")
-
-
-def st3_debug_set_plan_overlap(mode: int) -> None:
-    _check(lib().st3_debug_set_plan_overlap(mode), "st3_debug_set_plan_overlap")

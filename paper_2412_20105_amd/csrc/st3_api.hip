@@ -16,7 +16,7 @@ void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 DebugState& debug_state() {
     static DebugState st = [] {
         const char* e = std::getenv("ST3_DEBUG");
-        return DebugState{e != nullptr && std::strcmp(e, "1") == 0, 0, 0, 0};
+        return DebugState{e != nullptr && std::strcmp(e, "1") == 0, 0, 0};
     }();
     return st;
 }
@@ -265,62 +265,6 @@ static st3_status enqueue_plans(const std::vector<EvictArgs>& plan, const std::v
     return check_launch();
 }
 
-// ---------------------------------------------------------------------------------------------
-// The whole-step call runs the plans of the layers that have attended beside the attention of the
-// layers still to come: a plan launch is bound by its chain of dependent steps, not by bandwidth,
-// and behind the last attention it is pure waiting.  One extra stream per device (default priority,
-// not synchronised with the null stream), created at the first step that can use it; every step
-// forks into it with an event after each kPlanBatch layers and joins it before returning, so to
-// the caller all work of the step is still ordered on the caller's stream.
-// ---------------------------------------------------------------------------------------------
-constexpr int kPlanForks = 8;           // plan launches per step that can run beside the attention
-struct PlanLane {
-    hipStream_t side = nullptr;
-    hipEvent_t fork[kPlanForks] = {};
-    hipEvent_t join = nullptr;
-    int state = 0;                      // 0 = not tried, 1 = ready, -1 = could not be created (never tried again)
-};
-static std::mutex g_lane_mu;            // held while a step forks and joins: the events are shared by all callers
-static PlanLane g_lane[kMaxDevices];
-
-// The lane of the current device, or null if there is none (creation failed, device id out of range).
-// Call with g_lane_mu held.
-static PlanLane* plan_lane() {
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
-    PlanLane& ln = g_lane[dev];
-    if (ln.state == 0) {
-        bool ok = hipStreamCreateWithFlags(&ln.side, hipStreamNonBlocking) == hipSuccess;
-        for (int i = 0; ok && i < kPlanForks; ++i)
-            ok = hipEventCreateWithFlags(&ln.fork[i], hipEventDisableTiming) == hipSuccess;
-        ok = ok && hipEventCreateWithFlags(&ln.join, hipEventDisableTiming) == hipSuccess;
-        if (!ok) (void)hipGetLastError();        // the step simply stays on the caller's stream
-        ln.state = ok ? 1 : -1;
-    }
-    return ln.state == 1 ? &ln : nullptr;
-}
-
-// Forking costs two event operations on the caller's stream and the plans then compete with the
-// attention for the compute units: measured on the 13B shape at batch 32, a step that evicts a
-// row or two per layer and sequence (cosine annealing over 512 steps) is 0.8 % slower with its
-// plans forked, one that evicts ten (the paper's tau = 50) 3 % faster.  So a batch of plans is
-// forked only when its layers may evict this many rows per layer and sequence on average.
-constexpr int kForkMinRows = 4;
-static int64_t evicted_rows_bound(const st3_layer_step* layers, int i0, int i1) {
-    int64_t rows = 0;
-    for (int i = i0; i < i1; ++i)
-        if (layers[i].keep_after >= 0 && layers[i].keep_after < layers[i].seg.max_vis_len)
-            rows += layers[i].seg.max_vis_len - layers[i].keep_after;
-    return rows;
-}
-
-// A stream that is being captured into a graph keeps the whole step on itself.
-static bool stream_is_capturing(hipStream_t st) {
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(st, &cs) != hipSuccess) { (void)hipGetLastError(); return true; }
-    return cs != hipStreamCaptureStatusNone;
-}
-
 }  // namespace st3
 
 extern "C" st3_status st3_decode_layer_attend(const st3_attn_shape* shape, int32_t n_layers, const st3_layer_step* layers,
@@ -365,14 +309,6 @@ extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
     // All of a step's inputs are here, so nothing needs a layer's output before the step ends: where
     // the strips are cut into chunks (B*H alone does not fill the chip) the chunk partials are merged
     // by the layer's plan instead of by a launch of their own behind every attention.
-    std::unique_lock<std::mutex> lane_lock(g_lane_mu, std::defer_lock);
-    PlanLane* lane = nullptr;
-    if (n_layers > kPlanBatch && debug_state().plan_overlap != 1 && !stream_is_capturing(st)) {
-        lane_lock.lock();
-        lane = plan_lane();
-        if (lane == nullptr) lane_lock.unlock();
-    }
-    int planned = 0, forks = 0;         // layers whose plans are enqueued; forks into the side stream so far
     std::vector<const EvictArgs*> stashed((size_t)n_layers, nullptr);
     for (int i = 0; i < n_layers; ++i) {
         const st3_layer_step& L = layers[i];
@@ -397,26 +333,10 @@ extern "C" st3_status st3_decode_step(const st3_attn_shape* shape, int32_t n_lay
             stashed[i] = reinterpret_cast<const EvictArgs*>(stash.dst);
         }
         s = enqueue_layer_attend(shape, layers, i, has_heirs[i] != 0, st, in_plan, &stash);
-        if (s != ST3_OK) break;
-        // a full batch of layers has attended and more follow: its plans go to the side stream
-        if (lane != nullptr && (i + 1) % kPlanBatch == 0 && i + 1 < n_layers && forks < kPlanForks &&
-            (debug_state().plan_overlap == 2 || evicted_rows_bound(layers, planned, i + 1) >= kForkMinRows * (i + 1 - planned))) {
-            hipError_t e = hipEventRecord(lane->fork[forks], st);
-            if (e == hipSuccess) e = hipStreamWaitEvent(lane->side, lane->fork[forks], 0);
-            if (e != hipSuccess) { set_last_hip_error(e); s = ST3_ERR_HIP; break; }
-            enqueue_plan_range(plan, needs_apply, planned, i + 1, shape->batch, lane->side, &stashed);
-            planned = i + 1;
-            ++forks;
-        }
+        if (s != ST3_OK) return s;
     }
-    if (s == ST3_OK) enqueue_plan_range(plan, needs_apply, planned, n_layers, shape->batch, st, &stashed);
-    if (forks > 0) {
-        // whatever happened above, the caller's stream waits for what the side stream was given
-        hipError_t e = hipEventRecord(lane->join, lane->side);
-        if (e == hipSuccess) e = hipStreamWaitEvent(st, lane->join, 0);
-        if (e != hipSuccess && s == ST3_OK) { set_last_hip_error(e); s = ST3_ERR_HIP; }
-    }
-    return s != ST3_OK ? s : check_launch();
+    enqueue_plan_range(plan, needs_apply, 0, n_layers, shape->batch, st, &stashed);
+    return check_launch();
 }
 
 extern "C" st3_status st3_profile_enable(int32_t max_launches) {
@@ -462,13 +382,6 @@ extern "C" st3_status st3_debug_set_prefill_path(int path) {
     if (!st3::debug_state().enabled) return ST3_ERR_UNSUPPORTED;
     if (path < 0 || path > 2) return ST3_ERR_INVALID_ARG;
     st3::debug_state().prefill_path = path;
-    return ST3_OK;
-}
-
-extern "C" st3_status st3_debug_set_plan_overlap(int mode) {
-    if (!st3::debug_state().enabled) return ST3_ERR_UNSUPPORTED;
-    if (mode < 0 || mode > 2) return ST3_ERR_INVALID_ARG;
-    st3::debug_state().plan_overlap = mode;
     return ST3_OK;
 }
 

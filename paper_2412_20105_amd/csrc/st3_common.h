@@ -21,7 +21,6 @@ struct DebugState {
     bool enabled;           // ST3_DEBUG=1 at load
     int prefill_path;       // 0 = automatic, 1 = float32 row kernel, 2 = MFMA kernel or fail
     int attend_tile;        // 0 = automatic, else the forced tile size of the decode attention kernel
-    int plan_overlap;       // whole-step call: 0 = automatic, 1 = every launch on the caller's stream, 2 = fork whenever possible
 };
 DebugState& debug_state();  // st3_api.hip
 constexpr int kMaxDevices = 64;     // per-device caches (occupancy, scratch addresses) are indexed by the HIP device id

@@ -350,7 +350,7 @@ st3_status build_evict_args(const st3_attn_shape* shape, const st3_kv_layer* kv,
                             int64_t mass_stride, EvictArgs& ea, bool& needs_apply, bool batched,
                             const void* mass_workspace = nullptr, int32_t mass_capacity = 0);
 void launch_evict_plan(const EvictArgs& ea, int B, hipStream_t st);
-constexpr int kPlanBatch = 16;     // plans that fit the kernel-argument block by value; also the whole-step call's fork interval
+constexpr int kPlanBatch = 16;     // plans that fit the kernel-argument block by value
 // Plans of n layers (device work of one decode step) with one launch per kPlanBatch layers.
 void launch_evict_plan_batch(const EvictArgs* plans, int n, int B, hipStream_t st);
 // The same for plans that the layers' attention launches have left in device memory (PlanStash):

@@ -182,7 +182,8 @@ def test_many_layers_whole_step_call_current_mode():
 
 
 def _many_layers_with_a_group_across_the_fork():
-    """34 layers; layers 15-17 inherit from layer 14, so the group lies on both sides of layer 16."""
+    """34 layers; layers 15-17 inherit from layer 14 (the group lies on both sides of layer 16, where the by-value
+    plan launches of the per-layer path change batch)."""
     keep = [120] * 3 + [100] * 11 + [80] * 4 + [60] * 16
     w = dataclasses.replace(get_workload("llava15_7b"), layers=34, heads=2, steps=4, n_vis=120, n_txt=9,
                             layer_schedule={"kind": "table", "keep": keep}, step_schedule={"kind": "cos", "tau": 5})
@@ -190,15 +191,11 @@ def _many_layers_with_a_group_across_the_fork():
 
 
 @pytest.mark.parametrize("mode", ["static", "current"])
-def test_plans_run_beside_the_attention_of_later_layers(mode):
-    """With more than 16 layers the whole-step call hands the plans of layers 0-15 and 16-31 to the library's side
-    stream while later layers attend; the last two layers' plans stay on the caller's stream."""
+def test_many_layers_and_a_heredity_group_in_one_plan_launch(mode):
+    """34 layers, three of them lazy: every layer's plan arguments reach the step's one plan launch through the
+    layer's workspace, where the layer's attend (or inherit) launch has left them."""
     w, lazy = _many_layers_with_a_group_across_the_fork()
-    st3.st3_debug_set_plan_overlap(2)               # in every step, not only in those the library would pick
-    try:
-        _run_and_compare(w, 2, mode=mode, whole_step=True, lazy=lazy)
-    finally:
-        st3.st3_debug_set_plan_overlap(0)
+    _run_and_compare(w, 2, mode=mode, whole_step=True, lazy=lazy)
 
 
 def _run_job_whole_steps(w, lazy, B, stream=None):
@@ -230,47 +227,36 @@ def _assert_same_bits(a_steps, b_steps, what):
             assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), f"{what}: step {t + 1}, tensor {i}"
 
 
-def test_plans_beside_the_attention_change_no_bit():
-    """The same job with the side stream in use and with every launch on the caller's stream: outputs, masses, kept
-    ids and lengths are equal bit for bit at every step."""
+def test_whole_step_calls_repeat_bit_for_bit():
+    """The same job twice through whole-step calls: outputs, masses, kept ids and lengths are equal bit for bit at
+    every step (head and chunk reductions run in a fixed order)."""
     w, lazy = _many_layers_with_a_group_across_the_fork()
-    runs = []
-    for overlap in (2, 1):                           # always, never
-        st3.st3_debug_set_plan_overlap(overlap)
-        try:
-            runs.append(_run_job_whole_steps(w, lazy, 3))
-        finally:
-            st3.st3_debug_set_plan_overlap(0)
-    _assert_same_bits(runs[0], runs[1], "forked against not forked")
+    runs = [_run_job_whole_steps(w, lazy, 3) for _ in range(2)]
+    _assert_same_bits(runs[0], runs[1], "second run against first")
 
 
-def test_two_threads_share_the_side_stream():
-    """Two host threads run a job each, on streams of their own, through whole-step calls that fork into the one side
-    stream of the device: both get the bits a job gets alone."""
+def test_two_threads_run_whole_step_calls_at_once():
+    """Two host threads run a job each, on streams of their own: both get the bits a job gets alone."""
     import threading
     w, lazy = _many_layers_with_a_group_across_the_fork()
-    st3.st3_debug_set_plan_overlap(2)
-    try:
-        alone = _run_job_whole_steps(w, lazy, 2)
-        streams = [torch.cuda.Stream(device=DEV) for _ in range(2)]
-        got, errors = [None, None], []
+    alone = _run_job_whole_steps(w, lazy, 2)
+    streams = [torch.cuda.Stream(device=DEV) for _ in range(2)]
+    got, errors = [None, None], []
 
-        def job(i):
-            try:
-                torch.cuda.set_device(DEV)
-                got[i] = _run_job_whole_steps(w, lazy, 2, streams[i])
-            except Exception as e:                  # surfaced in the main thread below
-                errors.append(e)
+    def job(i):
+        try:
+            torch.cuda.set_device(DEV)
+            got[i] = _run_job_whole_steps(w, lazy, 2, streams[i])
+        except Exception as e:                  # surfaced in the main thread below
+            errors.append(e)
 
-        threads = [threading.Thread(target=job, args=(i,)) for i in range(2)]
-        for th in threads:
-            th.start()
-        for th in threads:
-            th.join()
-        torch.cuda.synchronize()
-        assert not errors, errors
-    finally:
-        st3.st3_debug_set_plan_overlap(0)
+    threads = [threading.Thread(target=job, args=(i,)) for i in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
     for i in range(2):
         _assert_same_bits(alone, got[i], f"thread {i} against a job alone")
 
@@ -478,23 +464,20 @@ def _random_generation(seed):
                 fixed_tail=bool(rng.random() < 0.5), whole_step=bool(lazy) or bool(rng.random() < 0.5),
                 window=min(int(rng.choice([1, 1, 2, 4])), n_txt), lazy=lazy or None,
                 kv_scale=6 * w.sigma / 448 if (w.dtype == "bf16" and rng.random() < 0.3) else None)
-    return w, B, opts, int(rng.choice([0, 2]))
+    rng.choice([0, 2])                                                  # (keeps the later draws of older seeds in place)
+    return w, B, opts
 
 
 @pytest.mark.parametrize("block", range(4))
 def test_whole_generations_of_random_shape_and_options(block):
     """Shapes, retention tables, annealing kinds, heredity groups, both cache layouts and compaction modes, both ways of
-    calling a step, score windows, E4M3 caches, 2 to 35 layers, with the whole-step call's plans forked or not."""
+    calling a step, score windows, E4M3 caches, 2 to 35 layers."""
     compared = total = 0
     for seed in range(block * 20, block * 20 + 20):
-        w, B, opts, overlap = _random_generation(seed)
+        w, B, opts = _random_generation(seed)
         print("generation case", seed, w.layers, w.heads, w.head_dim, B, (w.n_sys, w.n_vis, w.n_txt), w.steps,
-              w.layer_schedule["keep"], w.step_schedule, opts, overlap, flush=True)
-        st3.st3_debug_set_plan_overlap(overlap)
-        try:
-            _, div = _run_and_compare(w, B, min_compared=0.0, **opts)
-        finally:
-            st3.st3_debug_set_plan_overlap(0)
+              w.layer_schedule["keep"], w.step_schedule, opts, flush=True)
+        _, div = _run_and_compare(w, B, min_compared=0.0, **opts)
         compared += int((~div).sum())
         total += div.size
     assert compared >= 0.9 * total, f"only {compared} of {total} (layer, sequence) pairs were compared to the end"

@@ -36,14 +36,14 @@ def test_diagnostic_block_is_inert_without_the_environment_switch():
     import sys
     code = ("import ctypes as C; L = C.CDLL(%r); L.st3_debug_enabled.restype = C.c_int; "
             "print(L.st3_debug_enabled(), L.st3_debug_set_attend_tile(8), L.st3_debug_set_prefill_path(1), "
-            "L.st3_profile_enable(4), L.st3_profile_read(None, None, None, None), L.st3_debug_set_plan_overlap(1))" % st3.LIB_PATH)
+            "L.st3_profile_enable(4), L.st3_profile_read(None, None, None, None))" % st3.LIB_PATH)
     env = {k: v for k, v in os.environ.items() if k != "ST3_DEBUG"}
     out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, check=True).stdout.split()
-    assert out == ["0", "2", "2", "2", "2", "2"]                 # ST3_ERR_UNSUPPORTED from every setter
+    assert out == ["0", "2", "2", "2", "2"]                 # ST3_ERR_UNSUPPORTED from every setter
     env["ST3_DEBUG"] = "1"
     out = subprocess.run([sys.executable, "-c", code.replace("L.st3_profile_enable(4), L.st3_profile_read(None, None, None, None)", "0, 0")],
                          env=env, capture_output=True, text=True, check=True).stdout.split()
-    assert out == ["1", "0", "0", "0", "0", "0"]
+    assert out == ["1", "0", "0", "0", "0"]
     assert st3.st3_debug_enabled()                          # this process: switched on by conftest.py
 
 
